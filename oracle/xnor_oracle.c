@@ -1,0 +1,160 @@
+/*
+ * CPU oracle for the XNOR-Net forward binary convolution.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition that the
+ * GPU library is checked against.  It shares no code, header, table or helper
+ * with the HIP path, and nothing in the product path may call it.
+ *
+ * What it evaluates (paper section 3.2 "Binary Convolution", the equation
+ * I * W ~ (sign(I) (*) sign(W)) . K alpha):
+ *   sign(v)  = +1 if v >= 0, -1 otherwise        (sec. 3.1, rule given with B* = sign(W))
+ *   alpha_k  = (1/n) sum |W_k|, n = c*kh*kw      (sec. 3.1, optimal scaling factor)
+ *   A        = (1/c) sum_c |I[c]|                (sec. 3.2, matrix A)
+ *   K        = A conv k, k_ij = 1/(kh*kw)        (sec. 3.2, matrix K)
+ *   dot      = sum over the window of sign(I)*sign(W)   (what XNOR+bitcount reaches)
+ *   out      = dot * K * alpha
+ *
+ * The fast method (XNOR + bitcount) reaches exactly the integer that the plain
+ * +-1 correlation defines, so the oracle is that definition written out: a
+ * direct correlation over +-1 tensors with exact integer accumulation.  All
+ * real-valued quantities are accumulated in double and rounded to float once.
+ *
+ * Readings of points on which the paper is silent:
+ *   - padding: a padded position contributes 0 to the dot product and 0 to A;
+ *   - the divisor of K is always kh*kw (the box filter has fixed taps 1/(kh*kw));
+ *   - correlation, not flipped convolution; NCHW storage; K indexed [oy][ox];
+ *   - A and K are per image, alpha is shared by the batch;
+ *   - sign uses a comparison, so sign(-0.0f) = +1 and NaN -> -1;
+ *   - batch normalisation (block order BatchNorm -> BinActiv -> BinConv) is the
+ *     inference affine map y = fmaf(x, scale_c, shift_c) evaluated in float,
+ *     because that float value decides the sign bit.
+ *
+ * Pins (tests/test_oracle_pins.py): brute-force least squares for alpha and B,
+ * per-window beta = |X|_1/n against K, exhaustive +-1 dot vs bitcount identity,
+ * all-ones input closed form, constant-magnitude special case against a library
+ * float convolution, sign flip antisymmetry, parity/bound invariants, the FC =
+ * whole-input-filter equivalence.  Every function below is pinned by at least one.
+ *
+ * Build: gcc -O3 -fopenmp -ffp-contract=off -shared -fPIC
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+
+/* y = x*scale_c + shift_c in float with one rounding (fmaf); scale==NULL copies x.
+ * Block order of sec. 3.2 "Training XNOR-Networks": normalise before binarising. */
+void xo_batchnorm(const float *x, const float *scale, const float *shift, float *y,
+                  int n, int c, int h, int w)
+{
+    const size_t hw = (size_t)h * w;
+    for (int b = 0; b < n; ++b)
+        for (int ch = 0; ch < c; ++ch) {
+            const float *src = x + ((size_t)b * c + ch) * hw;
+            float *dst = y + ((size_t)b * c + ch) * hw;
+            for (size_t i = 0; i < hw; ++i)
+                dst[i] = scale ? fmaf(src[i], scale[ch], shift[ch]) : src[i];
+        }
+}
+
+/* sign of sec. 3.1: +1 when v >= 0, -1 when v < 0 (also applied to inputs). */
+void xo_sign(const float *v, int8_t *s, size_t count)
+{
+    for (size_t i = 0; i < count; ++i)
+        s[i] = (v[i] >= 0.0f) ? (int8_t)1 : (int8_t)-1;
+}
+
+/* alpha_k = ||W_k||_1 / n  (sec. 3.1, closed form of the optimal scale). */
+void xo_alpha(const float *W, double *alpha, int k_out, int c, int kh, int kw)
+{
+    const size_t n = (size_t)c * kh * kw;
+    for (int k = 0; k < k_out; ++k) {
+        double s = 0.0;
+        for (size_t i = 0; i < n; ++i)
+            s += fabs((double)W[(size_t)k * n + i]);
+        alpha[k] = s / (double)n;
+    }
+}
+
+/* A[b][y][x] = (1/c) sum_ch |I[b][ch][y][x]|  (sec. 3.2). */
+void xo_A(const float *I, double *A, int n, int c, int h, int w)
+{
+    const size_t hw = (size_t)h * w;
+    for (int b = 0; b < n; ++b)
+        for (size_t p = 0; p < hw; ++p) {
+            double s = 0.0;
+            for (int ch = 0; ch < c; ++ch)
+                s += fabs((double)I[((size_t)b * c + ch) * hw + p]);
+            A[(size_t)b * hw + p] = s / (double)c;
+        }
+}
+
+/* K = A correlated with the constant filter 1/(kh*kw), evaluated at the output
+ * positions of the convolution; out-of-range A counts as 0 (sec. 3.2). */
+void xo_K(const double *A, double *K, int n, int h, int w, int kh, int kw,
+          int stride_h, int stride_w, int pad_h, int pad_w)
+{
+    const int ho = (h + 2 * pad_h - kh) / stride_h + 1;
+    const int wo = (w + 2 * pad_w - kw) / stride_w + 1;
+    for (int b = 0; b < n; ++b)
+        for (int oy = 0; oy < ho; ++oy)
+            for (int ox = 0; ox < wo; ++ox) {
+                double s = 0.0;
+                for (int dy = 0; dy < kh; ++dy)
+                    for (int dx = 0; dx < kw; ++dx) {
+                        const int iy = oy * stride_h - pad_h + dy;
+                        const int ix = ox * stride_w - pad_w + dx;
+                        if (iy >= 0 && iy < h && ix >= 0 && ix < w)
+                            s += A[((size_t)b * h + iy) * w + ix];
+                    }
+                K[((size_t)b * ho + oy) * wo + ox] = s / (double)(kh * kw);
+            }
+}
+
+/* dot[b][k][oy][ox] = sum_{ch,dy,dx in bounds} sI[b][ch][iy][ix] * sW[k][ch][dy][dx]
+ * over +-1 tensors: the value XNOR + bitcount computes (sec. 3.2).  Exact in int32. */
+void xo_dot(const int8_t *sI, const int8_t *sW, int32_t *dot,
+            int n, int c, int h, int w, int k_out, int kh, int kw,
+            int stride_h, int stride_w, int pad_h, int pad_w)
+{
+    const int ho = (h + 2 * pad_h - kh) / stride_h + 1;
+    const int wo = (w + 2 * pad_w - kw) / stride_w + 1;
+    const long jobs = (long)n * k_out;
+#pragma omp parallel for schedule(static)
+    for (long job = 0; job < jobs; ++job) {
+        const int b = (int)(job / k_out), k = (int)(job % k_out);
+        int32_t *acc = dot + (size_t)job * ho * wo;
+        for (int i = 0; i < ho * wo; ++i)
+            acc[i] = 0;
+        for (int ch = 0; ch < c; ++ch)
+            for (int dy = 0; dy < kh; ++dy)
+                for (int dx = 0; dx < kw; ++dx) {
+                    const int32_t sw = sW[(((size_t)k * c + ch) * kh + dy) * kw + dx];
+                    const int8_t *plane = sI + ((size_t)b * c + ch) * h * w;
+                    for (int oy = 0; oy < ho; ++oy) {
+                        const int iy = oy * stride_h - pad_h + dy;
+                        if (iy < 0 || iy >= h)
+                            continue;
+                        for (int ox = 0; ox < wo; ++ox) {
+                            const int ix = ox * stride_w - pad_w + dx;
+                            if (ix < 0 || ix >= w)
+                                continue;
+                            acc[oy * wo + ox] += (int32_t)plane[(size_t)iy * w + ix] * sw;
+                        }
+                    }
+                }
+    }
+}
+
+/* out = (float)(dot * K * alpha), the right-hand side of the binary-convolution
+ * equation; product formed in double, rounded once. */
+void xo_scale(const int32_t *dot, const double *K, const double *alpha, float *out,
+              int n, int k_out, int ho, int wo)
+{
+    const size_t px = (size_t)ho * wo;
+    for (int b = 0; b < n; ++b)
+        for (int k = 0; k < k_out; ++k)
+            for (size_t p = 0; p < px; ++p) {
+                const size_t o = ((size_t)b * k_out + k) * px + p;
+                out[o] = (float)((double)dot[o] * K[(size_t)b * px + p] * alpha[k]);
+            }
+}

@@ -1,0 +1,142 @@
+"""numpy front end of the C oracle (oracle/xnor_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Each function marshals numpy arrays into the plain C
+routine of the same name and returns new arrays; the arithmetic lives in the C file,
+whose header states the passages of the paper it follows and the readings taken.
+Nothing here imports or calls the HIP library.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build_oracle
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = build_oracle.build(force=False)
+        _lib = ctypes.CDLL(path)
+    return _lib
+
+
+def _p(a, ct):
+    return a.ctypes.data_as(ctypes.POINTER(ct)) if a is not None else None
+
+
+def out_hw(h, w, kh, kw, stride, pad):
+    sh, sw = stride
+    ph, pw = pad
+    return (h + 2 * ph - kh) // sh + 1, (w + 2 * pw - kw) // sw + 1
+
+
+def batchnorm(x, scale=None, shift=None):
+    """y = fmaf(x, scale_c, shift_c) in float32 (block order, sec. 3.2); identity if scale is None."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    n, c, h, w = x.shape
+    y = np.empty_like(x)
+    if scale is not None:
+        scale = np.ascontiguousarray(scale, dtype=np.float32)
+        shift = np.ascontiguousarray(shift, dtype=np.float32)
+        assert scale.shape == (c,) and shift.shape == (c,)
+    _load().xo_batchnorm(_p(x, ctypes.c_float), _p(scale, ctypes.c_float), _p(shift, ctypes.c_float),
+                         _p(y, ctypes.c_float), n, c, h, w)
+    return y
+
+
+def sign(v):
+    """+1 where v >= 0, -1 elsewhere, as int8 (sec. 3.1)."""
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    s = np.empty(v.shape, dtype=np.int8)
+    _load().xo_sign(_p(v, ctypes.c_float), _p(s, ctypes.c_int8), ctypes.c_size_t(v.size))
+    return s
+
+
+def alpha(W):
+    """alpha_k = ||W_k||_1 / n per filter, float64 (sec. 3.1)."""
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    k, c, kh, kw = W.shape
+    a = np.empty(k, dtype=np.float64)
+    _load().xo_alpha(_p(W, ctypes.c_float), _p(a, ctypes.c_double), k, c, kh, kw)
+    return a
+
+
+def A_map(I):
+    """A = channel mean of |I|, float64 [n][h][w] (sec. 3.2)."""
+    I = np.ascontiguousarray(I, dtype=np.float32)
+    n, c, h, w = I.shape
+    A = np.empty((n, h, w), dtype=np.float64)
+    _load().xo_A(_p(I, ctypes.c_float), _p(A, ctypes.c_double), n, c, h, w)
+    return A
+
+
+def K_map(A, kh, kw, stride=(1, 1), pad=(0, 0)):
+    """K = A box-filtered by 1/(kh*kw) at the conv's output positions, float64 (sec. 3.2)."""
+    A = np.ascontiguousarray(A, dtype=np.float64)
+    n, h, w = A.shape
+    ho, wo = out_hw(h, w, kh, kw, stride, pad)
+    K = np.empty((n, ho, wo), dtype=np.float64)
+    _load().xo_K(_p(A, ctypes.c_double), _p(K, ctypes.c_double), n, h, w, kh, kw,
+                 stride[0], stride[1], pad[0], pad[1])
+    return K
+
+
+def dot_map(sI, sW, stride=(1, 1), pad=(0, 0)):
+    """Exact int32 correlation of +-1 tensors with zero padding (what XNOR+bitcount reaches)."""
+    sI = np.ascontiguousarray(sI, dtype=np.int8)
+    sW = np.ascontiguousarray(sW, dtype=np.int8)
+    n, c, h, w = sI.shape
+    k, c2, kh, kw = sW.shape
+    assert c == c2
+    ho, wo = out_hw(h, w, kh, kw, stride, pad)
+    d = np.empty((n, k, ho, wo), dtype=np.int32)
+    _load().xo_dot(_p(sI, ctypes.c_int8), _p(sW, ctypes.c_int8), _p(d, ctypes.c_int32),
+                   n, c, h, w, k, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    return d
+
+
+def scale_output(dot, K, alpha_):
+    """out = float32(dot * K * alpha) (right-hand side of the binary-convolution equation)."""
+    dot = np.ascontiguousarray(dot, dtype=np.int32)
+    K = np.ascontiguousarray(K, dtype=np.float64)
+    alpha_ = np.ascontiguousarray(alpha_, dtype=np.float64)
+    n, k, ho, wo = dot.shape
+    assert K.shape == (n, ho, wo) and alpha_.shape == (k,)
+    out = np.empty(dot.shape, dtype=np.float32)
+    _load().xo_scale(_p(dot, ctypes.c_int32), _p(K, ctypes.c_double), _p(alpha_, ctypes.c_double),
+                     _p(out, ctypes.c_float), n, k, ho, wo)
+    return out
+
+
+def binary_conv2d(x, W, stride=(1, 1), pad=(0, 0), bn_scale=None, bn_shift=None):
+    """Whole block BatchNorm -> BinActiv -> BinConv.  Returns dict(dot, K, alpha, out, y)."""
+    y = batchnorm(x, bn_scale, bn_shift)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    kh, kw = W.shape[2], W.shape[3]
+    d = dot_map(sign(y), sign(W), stride, pad)
+    K = K_map(A_map(y), kh, kw, stride, pad)
+    a = alpha(W)
+    return {"dot": d, "K": K, "alpha": a, "out": scale_output(d, K, a), "y": y}
+
+
+def binary_linear(x, W):
+    """Fully connected layer as the convolution whose filter covers the whole input
+    (footnote of sec. 1): x [batch][in_f], W [out_f][in_f].  Returns dict(dot, K, alpha, out)
+    with dot/out [batch][out_f], K [batch]."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    b, f = x.shape
+    o, f2 = W.shape
+    assert f == f2
+    r = binary_conv2d(x.reshape(b, f, 1, 1), W.reshape(o, f, 1, 1))
+    return {"dot": r["dot"].reshape(b, o), "K": r["K"].reshape(b), "alpha": r["alpha"],
+            "out": r["out"].reshape(b, o)}
+
+
+def threads():
+    """Number of OpenMP threads xo_dot uses."""
+    lib = ctypes.CDLL("libgomp.so.1")
+    return int(lib.omp_get_max_threads())
