@@ -1,0 +1,145 @@
+/*
+ * libxnor — forward binary convolution of XNOR-Net on AMD MI355X (gfx950).
+ *
+ *     I * W  ~  (sign(I) (*) sign(W)) . K alpha            (sec. 3.2, binary-convolution equation)
+ *
+ * with  alpha = ||W||_1 / n  per filter, n = c*kh*kw        (sec. 3.1, optimal scaling factor),
+ *       A     = (1/c) sum_c |I[c]|                          (sec. 3.2, matrix A),
+ *       K     = A filtered by the constant kh x kw box 1/(kh*kw)   (sec. 3.2, matrix K),
+ * and (*) the convolution of +-1 tensors evaluated with XNOR + bitcount (sec. 3.2).
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - Every pointer is a DEVICE pointer to memory the CALLER owns, except descriptors
+ *    (`const xnor_conv_desc*`), which are HOST pointers read during the call.
+ *    The library allocates nothing, frees nothing and keeps no pointer after returning.
+ *  - `hip_stream` is a hipStream_t (NULL = the default stream).  All work is enqueued on it
+ *    asynchronously; no entry point synchronises.
+ *  - Return value: XNOR_OK (0) or a negative xnor_status.  On error nothing was launched.
+ *  - Real tensors are float32, NCHW, densely packed, row-major:
+ *        x   [n][c][h_in][w_in]      w [k_out][c][kh][kw]      out [n][k_out][h_out][w_out]
+ *    h_out = (h_in + 2*pad_h - kh)/stride_h + 1 (floor), same for w_out.
+ *  - Packed tensors put channels innermost, 32 channels per uint32 word, Cw = ceil(c/32):
+ *        xbits [n][h_in][w_in][Cw]         wbits [k_out][kh][kw][Cw]
+ *    bit j of word i <-> channel 32*i + j; bit 1 <-> value >= 0 (+1), bit 0 <-> value < 0 (-1)
+ *    (sign rule of sec. 3.1, decided by a comparison: -0.0 -> +1, NaN -> -1).
+ *    Bits of channels >= c are 0 in both operands.
+ *  - Padding: a padded position contributes 0 to the dot product and 0 to A; the divisor of
+ *    K is always kh*kw.  The operation is a correlation (no filter flip).  No bias, groups = 1,
+ *    dilation = 1 (the paper's filters have no bias; sec. 3).
+ *  - All device pointers must be 16-byte aligned (XNOR_ERR_ALIGN otherwise).
+ */
+#ifndef XNOR_H
+#define XNOR_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    XNOR_OK = 0,
+    XNOR_ERR_NULL = -1,        /* a required pointer is NULL                                  */
+    XNOR_ERR_SHAPE = -2,       /* non-positive size, filter larger than padded input, overflow */
+    XNOR_ERR_UNSUPPORTED = -3, /* a combination this build has no kernel for                  */
+    XNOR_ERR_ALIGN = -4,       /* a device pointer is not 16-byte aligned                     */
+    XNOR_ERR_HIP = -5          /* the HIP runtime reported an error at launch                 */
+} xnor_status;
+
+/* Which inner loop xnor_conv2d / xnor_linear run.  Both produce the same integers. */
+typedef enum {
+    XNOR_ALGO_AUTO = 0,     /* the library's choice for the shape                                  */
+    XNOR_ALGO_POPCOUNT = 1, /* XOR + bitcount on the vector ALU over the packed words              */
+    XNOR_ALGO_MFMA_I8 = 2   /* +-1 (0 for padding) widened to int8 on chip, int8 matrix cores      */
+} xnor_algo;
+
+/* Problem statement of sec. 3: input c x w_in x h_in, filters c x w x h, plus stride and pad. */
+typedef struct {
+    int n, c, h_in, w_in;   /* input  [n][c][h_in][w_in]                 */
+    int k_out, kh, kw;      /* filters [k_out][c][kh][kw]                */
+    int stride_h, stride_w; /* >= 1                                      */
+    int pad_h, pad_w;       /* >= 0, zero padding on both sides          */
+} xnor_conv_desc;
+
+/* Cw = ceil(c/32): uint32 words per pixel of a packed tensor. */
+int xnor_words_per_pixel(int c);
+
+/* Output extent of the convolution; returns XNOR_ERR_SHAPE if the descriptor is invalid. */
+int xnor_output_hw(const xnor_conv_desc *d, int *h_out, int *w_out);
+
+/* Static string for a status code. */
+const char *xnor_status_string(int status);
+
+/* Bytes of the matrix-core weight image written by xnor_pack_weights (0 if the shape is invalid). */
+size_t xnor_wmfma_bytes(int k_out, int c, int kh, int kw);
+
+/*
+ * sign(I) packed to bits (BinActiv layer, sec. 3.2; sign rule of sec. 3.1).
+ * Optional batch normalisation first (block order BatchNorm -> BinActiv, sec. 3.2):
+ * y = fmaf(x, bn_scale[ch], bn_shift[ch]) in float32; bn_scale == bn_shift == NULL means y = x.
+ *   x      in   float32 [n][c][h][w]
+ *   xbits  out  uint32  [n][h][w][Cw]
+ */
+int xnor_binarize_pack(const float *x, const float *bn_scale, const float *bn_shift,
+                       uint32_t *xbits, int n, int c, int h, int w, void *hip_stream);
+
+/*
+ * A = channel mean of |y| and K = A box-filtered by 1/(kh*kw) at the output positions (sec. 3.2).
+ *   x  in   float32 [n][c][h_in][w_in]   (y as in xnor_binarize_pack)
+ *   A  out  float32 [n][h_in][w_in]      (required: K is computed from it)
+ *   K  out  float32 [n][h_out][w_out]
+ */
+int xnor_compute_K(const float *x, const float *bn_scale, const float *bn_shift,
+                   float *A, float *K, const xnor_conv_desc *d, void *hip_stream);
+
+/*
+ * The whole BinActiv layer in one pass over x: xbits, A and K as the two calls above produce them
+ * (bit-identical), reading the float input once.
+ */
+int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
+                  uint32_t *xbits, float *A, float *K, const xnor_conv_desc *d, void *hip_stream);
+
+/*
+ * B = sign(W) packed to bits and alpha = ||W||_1/n per filter (sec. 3.1; first loop of the
+ * training algorithm).  Run once per layer: at inference only B and alpha are kept.
+ *   w      in   float32 [k_out][c][kh][kw]
+ *   wbits  out  uint32  [k_out][kh][kw][Cw]
+ *   alpha  out  float32 [k_out]
+ *   wmfma  out  (nullable) xnor_wmfma_bytes(...) bytes: the same signs laid out for the matrix
+ *               cores; required by XNOR_ALGO_MFMA_I8, opaque to the caller.
+ */
+int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
+                      int k_out, int c, int kh, int kw, void *hip_stream);
+
+/*
+ * BinConv layer: out = float(dot) * K * alpha with
+ * dot[n][k][oy][ox] = sum over in-bounds taps and channels of sign(I)*sign(W)
+ *                   = n_valid - 2*bitcount(xbits XOR wbits)        (sec. 3.2).
+ *   xbits, wbits, K, alpha  in   as produced above
+ *   wmfma    in   (nullable) from xnor_pack_weights; NULL forces XNOR_ALGO_POPCOUNT under AUTO and
+ *                 is an XNOR_ERR_NULL under XNOR_ALGO_MFMA_I8
+ *   out      out  float32 [n][k_out][h_out][w_out]
+ *   dot_out  out  (nullable) int32 same shape: the exact integer map, for verification
+ *   algo          an xnor_algo
+ */
+int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+                const float *K, const float *alpha, float *out, int32_t *dot_out,
+                const xnor_conv_desc *d, int algo, void *hip_stream);
+
+/*
+ * Fully connected layer = convolution whose filter covers the whole input (footnote of sec. 1).
+ *   xbits [batch][Fw], wbits [out_features][Fw], Fw = ceil(in_features/32)
+ *   Krow  [batch]  = mean_j |x[b][j]|  (xnor_compute_K / xnor_binactiv with c = in_features, 1x1)
+ *   alpha [out_features], out / dot_out [batch][out_features]
+ *   wmfma as in xnor_conv2d, packed with (k_out = out_features, c = in_features, 1, 1).
+ */
+int xnor_linear(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+                const float *Krow, const float *alpha, float *out, int32_t *dot_out,
+                int batch, int in_features, int out_features, int algo, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* XNOR_H */

@@ -1,0 +1,172 @@
+// C ABI of libxnor: argument validation and dispatch.  Declarations and contracts: include/xnor.h.
+#include "xnor_internal.h"
+
+using namespace xnor;
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Validates a descriptor and derives the kernel geometry.
+xnor_status make_geom(const xnor_conv_desc *d, ConvGeom *g)
+{
+    if (!d) return XNOR_ERR_NULL;
+    if (d->n <= 0 || d->c <= 0 || d->h_in <= 0 || d->w_in <= 0 || d->k_out <= 0 || d->kh <= 0 ||
+        d->kw <= 0 || d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0)
+        return XNOR_ERR_SHAPE;
+    const long long hp = (long long)d->h_in + 2LL * d->pad_h, wp = (long long)d->w_in + 2LL * d->pad_w;
+    if (d->kh > hp || d->kw > wp) return XNOR_ERR_SHAPE;
+    if (d->pad_h >= d->kh || d->pad_w >= d->kw) return XNOR_ERR_UNSUPPORTED;  // windows made of padding only
+    const long long ho = (hp - d->kh) / d->stride_h + 1, wo = (wp - d->kw) / d->stride_w + 1;
+    const long long cw = ((long long)d->c + 31) / 32;
+    const long long lim = 0x7fffffffLL;
+    const long long m = (long long)d->n * ho * wo;
+    if (m > lim || m * d->k_out > (lim << 4) || (long long)d->n * d->h_in * d->w_in * cw > lim ||
+        (long long)d->n * hp > lim || (long long)d->k_out * d->kh * d->kw * cw > lim ||
+        hp > 65535 || wp > 65535 || (long long)d->kh * d->kw > 4096)
+        return XNOR_ERR_SHAPE;
+    g->n = d->n; g->c = d->c; g->h = d->h_in; g->w = d->w_in;
+    g->k_out = d->k_out; g->kh = d->kh; g->kw = d->kw;
+    g->sh = d->stride_h; g->sw = d->stride_w; g->ph = d->pad_h; g->pw = d->pad_w;
+    g->ho = (int)ho; g->wo = (int)wo; g->cw = (int)cw; g->taps = d->kh * d->kw;
+    g->hp = (int)hp; g->wp = (int)wp; g->m_total = (int)m;
+    g->fblocks = (d->k_out + 31) / 32;
+    g->div_wo = FastDiv::make((uint32_t)wo);
+    g->div_howo = FastDiv::make((uint32_t)(ho * wo));
+    return XNOR_OK;
+}
+
+xnor_status check_bn(const float *bn_scale, const float *bn_shift)
+{
+    if ((bn_scale == nullptr) != (bn_shift == nullptr)) return XNOR_ERR_NULL;
+    if (!aligned16(bn_scale) || !aligned16(bn_shift)) return XNOR_ERR_ALIGN;
+    return XNOR_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int xnor_words_per_pixel(int c) { return c > 0 ? (c + 31) / 32 : 0; }
+
+int xnor_output_hw(const xnor_conv_desc *d, int *h_out, int *w_out)
+{
+    ConvGeom g;
+    const xnor_status s = make_geom(d, &g);
+    if (s != XNOR_OK) return s;
+    if (h_out) *h_out = g.ho;
+    if (w_out) *w_out = g.wo;
+    return XNOR_OK;
+}
+
+const char *xnor_status_string(int status)
+{
+    switch (status) {
+    case XNOR_OK: return "ok";
+    case XNOR_ERR_NULL: return "a required pointer is NULL";
+    case XNOR_ERR_SHAPE: return "invalid shape";
+    case XNOR_ERR_UNSUPPORTED: return "unsupported configuration";
+    case XNOR_ERR_ALIGN: return "device pointer not 16-byte aligned";
+    case XNOR_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+size_t xnor_wmfma_bytes(int k_out, int c, int kh, int kw)
+{
+    if (k_out <= 0 || c <= 0 || kh <= 0 || kw <= 0) return 0;
+    return (size_t)((k_out + 31) / 32) * (size_t)kh * kw * (size_t)((c + 31) / 32) * 1024u;
+}
+
+int xnor_binarize_pack(const float *x, const float *bn_scale, const float *bn_shift,
+                       uint32_t *xbits, int n, int c, int h, int w, void *hip_stream)
+{
+    if (!x || !xbits) return XNOR_ERR_NULL;
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return XNOR_ERR_SHAPE;
+    if ((long long)h * w > 0x7fffffffLL || (long long)n * h * w * ((c + 31) / 32) > 0x7fffffffLL)
+        return XNOR_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(xbits)) return XNOR_ERR_ALIGN;
+    if (xnor_status s = check_bn(bn_scale, bn_shift)) return s;
+    return launch_binactiv(x, bn_scale, bn_shift, xbits, nullptr, n, c, h * w, (hipStream_t)hip_stream);
+}
+
+int xnor_compute_K(const float *x, const float *bn_scale, const float *bn_shift,
+                   float *A, float *K, const xnor_conv_desc *d, void *hip_stream)
+{
+    if (!x || !A || !K) return XNOR_ERR_NULL;
+    ConvGeom g;
+    if (xnor_status s = make_geom(d, &g)) return s;
+    if (!aligned16(x) || !aligned16(A) || !aligned16(K)) return XNOR_ERR_ALIGN;
+    if (xnor_status s = check_bn(bn_scale, bn_shift)) return s;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (xnor_status s = launch_binactiv(x, bn_scale, bn_shift, nullptr, A, g.n, g.c, g.h * g.w, st)) return s;
+    return launch_boxfilter(A, K, g, st);
+}
+
+int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
+                  uint32_t *xbits, float *A, float *K, const xnor_conv_desc *d, void *hip_stream)
+{
+    if (!x || !xbits || !A || !K) return XNOR_ERR_NULL;
+    ConvGeom g;
+    if (xnor_status s = make_geom(d, &g)) return s;
+    if (!aligned16(x) || !aligned16(xbits) || !aligned16(A) || !aligned16(K)) return XNOR_ERR_ALIGN;
+    if (xnor_status s = check_bn(bn_scale, bn_shift)) return s;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (xnor_status s = launch_binactiv(x, bn_scale, bn_shift, xbits, A, g.n, g.c, g.h * g.w, st)) return s;
+    return launch_boxfilter(A, K, g, st);
+}
+
+int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
+                      int k_out, int c, int kh, int kw, void *hip_stream)
+{
+    if (!w || !wbits || !alpha) return XNOR_ERR_NULL;
+    if (k_out <= 0 || c <= 0 || kh <= 0 || kw <= 0) return XNOR_ERR_SHAPE;
+    if ((long long)kh * kw > 4096 || (long long)k_out * kh * kw * ((c + 31) / 32) > 0x7fffffffLL ||
+        (long long)c * kh * kw > 0x7fffffffLL)
+        return XNOR_ERR_SHAPE;
+    if (!aligned16(w) || !aligned16(wbits) || !aligned16(alpha) || !aligned16(wmfma)) return XNOR_ERR_ALIGN;
+    return launch_pack_weights(w, wbits, alpha, wmfma, k_out, c, kh * kw, (hipStream_t)hip_stream);
+}
+
+int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+                const float *K, const float *alpha, float *out, int32_t *dot_out,
+                const xnor_conv_desc *d, int algo, void *hip_stream)
+{
+    if (!xbits || !wbits || !K || !alpha || !out) return XNOR_ERR_NULL;
+    ConvGeom g;
+    if (xnor_status s = make_geom(d, &g)) return s;
+    if (!aligned16(xbits) || !aligned16(wbits) || !aligned16(wmfma) || !aligned16(K) ||
+        !aligned16(alpha) || !aligned16(out) || !aligned16(dot_out))
+        return XNOR_ERR_ALIGN;
+    hipStream_t st = (hipStream_t)hip_stream;
+    switch (algo) {
+    case XNOR_ALGO_POPCOUNT:
+        return launch_conv_popcount(xbits, wbits, K, alpha, out, dot_out, g, st);
+    case XNOR_ALGO_MFMA_I8:
+        if (!wmfma) return XNOR_ERR_NULL;
+        return launch_conv_mfma_i8(xbits, wmfma, K, alpha, out, dot_out, g, st);
+    case XNOR_ALGO_AUTO: {
+        if (wmfma) {
+            const xnor_status s = launch_conv_mfma_i8(xbits, wmfma, K, alpha, out, dot_out, g, st);
+            if (s != XNOR_ERR_UNSUPPORTED) return s;
+        }
+        return launch_conv_popcount(xbits, wbits, K, alpha, out, dot_out, g, st);
+    }
+    default:
+        return XNOR_ERR_UNSUPPORTED;
+    }
+}
+
+int xnor_linear(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+                const float *Krow, const float *alpha, float *out, int32_t *dot_out,
+                int batch, int in_features, int out_features, int algo, void *hip_stream)
+{
+    // A fully connected layer is the convolution whose 1x1 "image" has in_features channels.
+    xnor_conv_desc d;
+    d.n = batch; d.c = in_features; d.h_in = 1; d.w_in = 1;
+    d.k_out = out_features; d.kh = 1; d.kw = 1;
+    d.stride_h = 1; d.stride_w = 1; d.pad_h = 0; d.pad_w = 0;
+    return xnor_conv2d(xbits, wbits, wmfma, Krow, alpha, out, dot_out, &d, algo, hip_stream);
+}
+
+}  // extern "C"

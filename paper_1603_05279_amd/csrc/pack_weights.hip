@@ -1,0 +1,72 @@
+// Weight binarisation (sec. 3.1): B = sign(W) packed to bits, alpha = ||W||_1 / n per filter.
+// Runs once per layer; at inference only B and alpha are kept.  Also writes the same signs as
+// int8 (+1/-1, 0 for channel or filter padding) in the operand order of the 32x32x32 int8
+// matrix instruction, so the convolution can fetch a whole operand as one contiguous KiB.
+#include "xnor_internal.h"
+
+namespace xnor {
+
+// Matrix-core weight image: for filter block fb (32 filters), tap t, channel word wd there is a
+// 1 KiB record; lane l of a wave owns bytes [16*l, 16*l+16): filter fb*32 + (l & 31),
+// channels wd*32 + 16*(l >> 5) + 0..15.
+__global__ __launch_bounds__(256) void pack_weights_kernel(
+    const float *__restrict__ w, uint32_t *__restrict__ wbits, float *__restrict__ alpha,
+    int8_t *__restrict__ wmfma, int k_out, int c, int taps, int cw)
+{
+    __shared__ float red[256];
+    const int k = blockIdx.x;              // grid covers the filters padded to a multiple of 32
+    const int tid = threadIdx.x;
+    const bool real = k < k_out;
+    const size_t n = (size_t)c * taps;
+    const float *wk = w + (size_t)(real ? k : 0) * n;
+
+    if (real) {
+        for (int item = tid; item < taps * cw; item += 256) {
+            const int t = item / cw, wd = item - t * cw;
+            const int nch = min(32, c - wd * 32);
+            uint32_t word = 0;
+            for (int j = 0; j < nch; ++j)
+                word |= (wk[(size_t)(wd * 32 + j) * taps + t] >= 0.0f ? 1u : 0u) << j;
+            wbits[((size_t)k * taps + t) * cw + wd] = word;
+        }
+        float s = 0.0f;
+        for (size_t i = tid; i < n; i += 256) s += __builtin_fabsf(wk[i]);
+        red[tid] = s;
+        __syncthreads();
+        for (int step = 128; step > 0; step >>= 1) {
+            if (tid < step) red[tid] += red[tid + step];
+            __syncthreads();
+        }
+        if (tid == 0) alpha[k] = red[0] / (float)n;
+    }
+    if (wmfma) {
+        const int fb = k >> 5, row = k & 31;
+        for (int item = tid; item < taps * cw * 2; item += 256) {
+            const int half = item & 1;
+            const int tw = item >> 1;               // t*cw + wd
+            const int t = tw / cw, wd = tw - t * cw;
+            const int ch0 = wd * 32 + half * 16;
+            union { int8_t b[16]; uint4 v; } u;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                int8_t s = 0;
+                if (real && ch0 + j < c) s = (wk[(size_t)(ch0 + j) * taps + t] >= 0.0f) ? 1 : -1;
+                u.b[j] = s;
+            }
+            const size_t rec = ((size_t)fb * taps + t) * cw + wd;
+            *reinterpret_cast<uint4 *>(wmfma + rec * 1024 + (size_t)(row + 32 * half) * 16) = u.v;
+        }
+    }
+}
+
+xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
+                                int k_out, int c, int taps, hipStream_t stream)
+{
+    const int cw = (c + 31) / 32;
+    const int kpad = (k_out + 31) / 32 * 32;
+    dim3 grid((unsigned)(wmfma ? kpad : k_out)), block(256);
+    pack_weights_kernel<<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace xnor

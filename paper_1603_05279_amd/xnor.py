@@ -1,0 +1,195 @@
+"""Thin ctypes binding of libxnor (include/xnor.h): same names, argument marshalling only.
+
+Tensors are torch CUDA tensors used as plain device buffers; every step of the path runs in
+the library's HIP kernels.  There is no fallback: a missing library raises at import of the
+first call, a non-zero status raises XnorError.
+"""
+import ctypes
+import os
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libxnor.so")
+
+XNOR_ALGO_AUTO, XNOR_ALGO_POPCOUNT, XNOR_ALGO_MFMA_I8 = 0, 1, 2
+ALGOS = {"auto": XNOR_ALGO_AUTO, "popcount": XNOR_ALGO_POPCOUNT, "mfma_i8": XNOR_ALGO_MFMA_I8}
+
+EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor_wmfma_bytes",
+           "xnor_binarize_pack", "xnor_compute_K", "xnor_binactiv", "xnor_pack_weights",
+           "xnor_conv2d", "xnor_linear"]
+
+
+class XnorError(RuntimeError):
+    def __init__(self, fn, status):
+        self.status = status
+        super().__init__(f"{fn} failed: {status} ({status_string(status)})")
+
+
+class ConvDesc(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int) for k in
+                ("n", "c", "h_in", "w_in", "k_out", "kh", "kw", "stride_h", "stride_w", "pad_h", "pad_w")]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built (python -m paper_1603_05279_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_LIB_PATH):
+            raise ImportError(f"{_LIB_PATH} is missing: build it with paper_1603_05279_amd/build.py "
+                              "(there is no CPU fallback)")
+        L = ctypes.CDLL(_LIB_PATH)
+        vp, ip = ctypes.c_void_p, ctypes.c_int
+        L.xnor_words_per_pixel.argtypes = [ip]
+        L.xnor_words_per_pixel.restype = ip
+        L.xnor_output_hw.argtypes = [ctypes.POINTER(ConvDesc), ctypes.POINTER(ip), ctypes.POINTER(ip)]
+        L.xnor_output_hw.restype = ip
+        L.xnor_status_string.argtypes = [ip]
+        L.xnor_status_string.restype = ctypes.c_char_p
+        L.xnor_wmfma_bytes.argtypes = [ip, ip, ip, ip]
+        L.xnor_wmfma_bytes.restype = ctypes.c_size_t
+        L.xnor_binarize_pack.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp]
+        L.xnor_binarize_pack.restype = ip
+        L.xnor_compute_K.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(ConvDesc), vp]
+        L.xnor_compute_K.restype = ip
+        L.xnor_binactiv.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(ConvDesc), vp]
+        L.xnor_binactiv.restype = ip
+        L.xnor_pack_weights.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp]
+        L.xnor_pack_weights.restype = ip
+        L.xnor_conv2d.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(ConvDesc), ip, vp]
+        L.xnor_conv2d.restype = ip
+        L.xnor_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, vp]
+        L.xnor_linear.restype = ip
+        _lib = L
+    return _lib
+
+
+def status_string(status):
+    return lib().xnor_status_string(int(status)).decode()
+
+
+def words_per_pixel(c):
+    return lib().xnor_words_per_pixel(int(c))
+
+
+def wmfma_bytes(k_out, c, kh, kw):
+    return int(lib().xnor_wmfma_bytes(k_out, c, kh, kw))
+
+
+def make_desc(n, c, h_in, w_in, k_out, kh, kw, stride=(1, 1), pad=(0, 0)):
+    if isinstance(stride, int):
+        stride = (stride, stride)
+    if isinstance(pad, int):
+        pad = (pad, pad)
+    return ConvDesc(n, c, h_in, w_in, k_out, kh, kw, stride[0], stride[1], pad[0], pad[1])
+
+
+def output_hw(desc):
+    ho, wo = ctypes.c_int(0), ctypes.c_int(0)
+    st = lib().xnor_output_hw(ctypes.byref(desc), ctypes.byref(ho), ctypes.byref(wo))
+    if st:
+        raise XnorError("xnor_output_hw", st)
+    return ho.value, wo.value
+
+
+def _ptr(t, dtype=None):
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("libxnor takes device tensors")
+    if not t.is_contiguous():
+        raise ValueError("libxnor takes densely packed tensors")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _check(fn, st):
+    if st:
+        raise XnorError(fn, st)
+
+
+def xnor_binarize_pack(x, bn_scale, bn_shift, xbits, n, c, h, w, stream=None):
+    _check("xnor_binarize_pack", lib().xnor_binarize_pack(
+        _ptr(x, torch.float32), _ptr(bn_scale, torch.float32), _ptr(bn_shift, torch.float32),
+        _ptr(xbits, torch.int32), n, c, h, w, _stream(stream)))
+
+
+def xnor_compute_K(x, bn_scale, bn_shift, A, K, desc, stream=None):
+    _check("xnor_compute_K", lib().xnor_compute_K(
+        _ptr(x, torch.float32), _ptr(bn_scale, torch.float32), _ptr(bn_shift, torch.float32),
+        _ptr(A, torch.float32), _ptr(K, torch.float32), ctypes.byref(desc), _stream(stream)))
+
+
+def xnor_binactiv(x, bn_scale, bn_shift, xbits, A, K, desc, stream=None):
+    _check("xnor_binactiv", lib().xnor_binactiv(
+        _ptr(x, torch.float32), _ptr(bn_scale, torch.float32), _ptr(bn_shift, torch.float32),
+        _ptr(xbits, torch.int32), _ptr(A, torch.float32), _ptr(K, torch.float32),
+        ctypes.byref(desc), _stream(stream)))
+
+
+def xnor_pack_weights(w, wbits, alpha, wmfma, k_out, c, kh, kw, stream=None):
+    _check("xnor_pack_weights", lib().xnor_pack_weights(
+        _ptr(w, torch.float32), _ptr(wbits, torch.int32), _ptr(alpha, torch.float32),
+        _ptr(wmfma, torch.uint8), k_out, c, kh, kw, _stream(stream)))
+
+
+def xnor_conv2d(xbits, wbits, wmfma, K, alpha, out, dot_out, desc, algo=XNOR_ALGO_AUTO, stream=None):
+    _check("xnor_conv2d", lib().xnor_conv2d(
+        _ptr(xbits, torch.int32), _ptr(wbits, torch.int32), _ptr(wmfma, torch.uint8),
+        _ptr(K, torch.float32), _ptr(alpha, torch.float32), _ptr(out, torch.float32),
+        _ptr(dot_out, torch.int32), ctypes.byref(desc), int(algo), _stream(stream)))
+
+
+def xnor_linear(xbits, wbits, wmfma, Krow, alpha, out, dot_out, batch, in_features, out_features,
+                algo=XNOR_ALGO_AUTO, stream=None):
+    _check("xnor_linear", lib().xnor_linear(
+        _ptr(xbits, torch.int32), _ptr(wbits, torch.int32), _ptr(wmfma, torch.uint8),
+        _ptr(Krow, torch.float32), _ptr(alpha, torch.float32), _ptr(out, torch.float32),
+        _ptr(dot_out, torch.int32), batch, in_features, out_features, int(algo), _stream(stream)))
+
+
+# ---------------------------------------------------------------------------------------------
+# Buffer holders: allocation only (torch owns the device memory), no arithmetic.
+class PackedWeights:
+    """wbits / alpha / wmfma buffers of one layer, filled by xnor_pack_weights."""
+
+    def __init__(self, w, device="cuda", with_mfma=True, stream=None):
+        k_out, c, kh, kw = w.shape
+        self.shape = (k_out, c, kh, kw)
+        cw = words_per_pixel(c)
+        self.wbits = torch.empty((k_out, kh, kw, cw), dtype=torch.int32, device=device)
+        self.alpha = torch.empty((k_out,), dtype=torch.float32, device=device)
+        self.wmfma = (torch.empty((wmfma_bytes(k_out, c, kh, kw),), dtype=torch.uint8, device=device)
+                      if with_mfma else None)
+        xnor_pack_weights(w, self.wbits, self.alpha, self.wmfma, k_out, c, kh, kw, stream)
+
+
+class ConvBuffers:
+    """Activation-side buffers of one layer: xbits, A, K, out (and optionally the int32 dot map)."""
+
+    def __init__(self, desc, device="cuda", with_dot=False):
+        self.desc = desc
+        ho, wo = output_hw(desc)
+        cw = words_per_pixel(desc.c)
+        self.xbits = torch.empty((desc.n, desc.h_in, desc.w_in, cw), dtype=torch.int32, device=device)
+        self.A = torch.empty((desc.n, desc.h_in, desc.w_in), dtype=torch.float32, device=device)
+        self.K = torch.empty((desc.n, ho, wo), dtype=torch.float32, device=device)
+        self.out = torch.empty((desc.n, desc.k_out, ho, wo), dtype=torch.float32, device=device)
+        self.dot = (torch.empty((desc.n, desc.k_out, ho, wo), dtype=torch.int32, device=device)
+                    if with_dot else None)
+
+
+def binary_conv_block(x, bn_scale, bn_shift, weights, bufs, algo=XNOR_ALGO_AUTO, stream=None):
+    """BatchNorm -> BinActiv -> BinConv on preallocated buffers: two library calls."""
+    xnor_binactiv(x, bn_scale, bn_shift, bufs.xbits, bufs.A, bufs.K, bufs.desc, stream)
+    xnor_conv2d(bufs.xbits, weights.wbits, weights.wmfma, bufs.K, weights.alpha, bufs.out, bufs.dot,
+                bufs.desc, algo, stream)
+    return bufs.out

@@ -1,0 +1,64 @@
+"""The C-ABI library loads, exports every function include/xnor.h declares, and turns invalid
+arguments into error codes before anything is launched (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1603_05279_amd import xnor
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "xnor.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(xnor_[a-zA-Z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    names = declared_functions()
+    assert set(xnor.EXPORTS) == set(names)
+    L = xnor.lib()
+    for name in names:
+        assert getattr(L, name) is not None
+
+
+def test_small_queries():
+    assert [xnor.words_per_pixel(c) for c in (1, 31, 32, 33, 96, 9216)] == [1, 1, 1, 2, 3, 288]
+    assert xnor.words_per_pixel(0) == 0
+    assert xnor.wmfma_bytes(256, 96, 5, 5) == 8 * 25 * 3 * 1024
+    assert xnor.wmfma_bytes(33, 1, 1, 1) == 2 * 1024
+    assert xnor.wmfma_bytes(0, 1, 1, 1) == 0
+    assert xnor.output_hw(xnor.make_desc(64, 96, 27, 27, 256, 5, 5, 1, 2)) == (27, 27)
+    assert xnor.output_hw(xnor.make_desc(1, 5, 7, 6, 2, 2, 2, 2, 1)) == (4, 4)
+    assert xnor.status_string(0) == "ok"
+    assert "NULL" in xnor.status_string(-1)
+
+
+def test_invalid_arguments_return_error_codes_without_launching():
+    L = xnor.lib()
+    good = xnor.make_desc(1, 64, 14, 14, 64, 3, 3, 1, 1)
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x1004)
+    ERR_NULL, ERR_SHAPE, ERR_UNSUP, ERR_ALIGN = -1, -2, -3, -4
+    assert L.xnor_binarize_pack(None, None, None, fake, 1, 1, 1, 1, None) == ERR_NULL
+    assert L.xnor_binarize_pack(fake, None, None, fake, 0, 1, 1, 1, None) == ERR_SHAPE
+    assert L.xnor_binarize_pack(odd, None, None, fake, 1, 1, 1, 1, None) == ERR_ALIGN
+    assert L.xnor_binarize_pack(fake, fake, None, fake, 1, 1, 1, 1, None) == ERR_NULL   # scale without shift
+    assert L.xnor_compute_K(fake, None, None, None, fake, ctypes.byref(good), None) == ERR_NULL
+    assert L.xnor_compute_K(fake, None, None, fake, fake, None, None) == ERR_NULL
+    assert L.xnor_pack_weights(fake, fake, None, None, 1, 1, 1, 1, None) == ERR_NULL
+    assert L.xnor_pack_weights(fake, fake, fake, None, 1, -1, 1, 1, None) == ERR_SHAPE
+    assert L.xnor_conv2d(fake, fake, None, fake, fake, None, None, ctypes.byref(good), 0, None) == ERR_NULL
+    assert L.xnor_conv2d(fake, fake, None, fake, fake, fake, None, ctypes.byref(good), 2, None) == ERR_NULL  # mfma needs wmfma
+    assert L.xnor_conv2d(fake, fake, None, fake, fake, fake, None, ctypes.byref(good), 99, None) == ERR_UNSUP
+    assert L.xnor_conv2d(fake, fake, None, fake, fake, odd, None, ctypes.byref(good), 1, None) == ERR_ALIGN
+    big_filter = xnor.make_desc(1, 8, 3, 3, 4, 5, 5, 1, 0)
+    assert L.xnor_conv2d(fake, fake, None, fake, fake, fake, None, ctypes.byref(big_filter), 1, None) == ERR_SHAPE
+    zero_stride = xnor.make_desc(1, 8, 3, 3, 4, 3, 3, 0, 0)
+    assert L.xnor_binactiv(fake, None, None, fake, fake, fake, ctypes.byref(zero_stride), None) == ERR_SHAPE
+    assert L.xnor_linear(fake, fake, None, fake, fake, fake, None, 0, 8, 8, 1, None) == ERR_SHAPE
+    with pytest.raises(xnor.XnorError):
+        xnor.output_hw(big_filter)

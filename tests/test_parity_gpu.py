@@ -1,0 +1,95 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import xnor_oracle as xo
+from paper_1603_05279_amd import workloads as wl
+from paper_1603_05279_amd import xnor
+from tests.helpers import RTOL, ATOL, assert_block_matches_oracle, gpu_conv_block, to_dev
+
+pytestmark = pytest.mark.gpu
+
+ALGOS = ["popcount", "mfma_i8"]
+
+# n, c, h, w, k_out, kh, kw, stride, pad — several tiles, ragged tails, odd channel counts
+SMALL = [
+    (1, 1, 1, 1, 1, 1, 1, (1, 1), (0, 0)),          # smallest problem
+    (1, 3, 5, 7, 2, 3, 3, (1, 1), (1, 1)),
+    (2, 31, 9, 8, 5, 3, 2, (1, 1), (1, 0)),
+    (3, 32, 11, 13, 33, 3, 3, (2, 2), (1, 1)),
+    (2, 33, 6, 6, 7, 1, 1, (1, 1), (0, 0)),
+    (5, 64, 14, 14, 64, 3, 3, (1, 1), (1, 1)),
+    (3, 96, 27, 27, 40, 5, 5, (1, 1), (2, 2)),      # > 1 pixel tile per image, 3 words
+    (9, 100, 7, 7, 70, 3, 3, (1, 1), (1, 1)),       # tile spans several images, channel tail
+    (2, 40, 12, 10, 9, 4, 2, (2, 1), (1, 1)),       # even filter, mixed stride
+    (2, 256, 13, 13, 96, 3, 3, (1, 1), (1, 1)),     # several channel chunks in LDS
+    (1, 8, 40, 3, 4, 5, 3, (1, 1), (2, 1)),         # tall thin image
+]
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+@pytest.mark.parametrize("case", SMALL)
+def test_small_cases_match_oracle(case, algo):
+    n, c, h, w, k_out, kh, kw, stride, pad = case
+    x, wt = wl.random_conv_case(7 + c + h, n, c, h, w, k_out, kh, kw, with_zeros=True)
+    print("case", case, algo, flush=True)
+    g = gpu_conv_block(x, wt, stride, pad, algo=algo)
+    assert_block_matches_oracle(g, x, wt, stride, pad)
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+def test_config_tiny_full(algo):
+    layer = wl.config_layers("tiny")[0]
+    d = wl.conv_inputs(layer, wl.config_seed("tiny"))
+    g = gpu_conv_block(d["x"], d["w"], (1, 1), (1, 1), algo=algo)
+    assert_block_matches_oracle(g, d["x"], d["w"], (1, 1), (1, 1))
+
+
+def test_unfused_entry_points_give_identical_bits_and_K():
+    x, wt = wl.random_conv_case(3, 2, 70, 9, 9, 6, 3, 3)
+    a = gpu_conv_block(x, wt, (1, 1), (1, 1), fused=True)
+    b = gpu_conv_block(x, wt, (1, 1), (1, 1), fused=False)
+    for key in ("xbits", "A", "K", "dot", "out"):
+        assert np.array_equal(a[key], b[key]), key
+
+
+def test_batchnorm_block_matches_oracle_and_identity_fold():
+    layer = wl.ConvLayer("bn_small", 4, 96, 13, 13, 48, 3, 3, 1, 1, 0.05, True)
+    d = wl.conv_inputs(layer, 4242)
+    g = gpu_conv_block(d["x"], d["w"], (1, 1), (1, 1), d["bn_scale"], d["bn_shift"])
+    assert_block_matches_oracle(g, d["x"], d["w"], (1, 1), (1, 1), d["bn_scale"], d["bn_shift"])
+    one, zero = np.ones(96, np.float32), np.zeros(96, np.float32)
+    a = gpu_conv_block(d["x"], d["w"], (1, 1), (1, 1), one, zero)
+    b = gpu_conv_block(d["x"], d["w"], (1, 1), (1, 1))
+    for key in ("xbits", "A", "K", "dot", "out"):
+        assert np.array_equal(a[key], b[key]), key
+
+
+def test_runs_are_deterministic():
+    x, wt = wl.random_conv_case(5, 3, 64, 10, 10, 64, 3, 3)
+    a = gpu_conv_block(x, wt, (1, 1), (1, 1), algo="mfma_i8")
+    b = gpu_conv_block(x, wt, (1, 1), (1, 1), algo="mfma_i8")
+    for key in a:
+        assert np.array_equal(a[key], b[key]), key
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+def test_linear_matches_oracle(algo):
+    rng = np.random.default_rng(99)
+    b, f, o = 37, 1000, 130                         # ragged in every dimension
+    x = rng.standard_normal((b, f)).astype(np.float32)
+    w = (0.01 * rng.standard_normal((o, f))).astype(np.float32)
+    r = xo.binary_linear(x, w)
+    xd, wd = to_dev(x), to_dev(w.reshape(o, f, 1, 1))
+    pw = xnor.PackedWeights(wd)
+    desc = xnor.make_desc(b, f, 1, 1, o, 1, 1)
+    bufs = xnor.ConvBuffers(desc, with_dot=True)
+    xnor.xnor_binactiv(xd.reshape(b, f, 1, 1), None, None, bufs.xbits, bufs.A, bufs.K, desc)
+    out = torch.full((b, o), float("nan"), device="cuda")
+    dot = torch.zeros((b, o), dtype=torch.int32, device="cuda")
+    xnor.xnor_linear(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, out, dot, b, f, o, xnor.ALGOS[algo])
+    torch.cuda.synchronize()
+    assert np.array_equal(dot.cpu().numpy(), r["dot"])
+    np.testing.assert_allclose(bufs.K.cpu().numpy().reshape(b), r["K"], rtol=RTOL, atol=ATOL)
+    np.testing.assert_allclose(out.cpu().numpy(), r["out"], rtol=RTOL, atol=ATOL)
