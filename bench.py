@@ -1,0 +1,135 @@
+"""Benchmark of the XNOR-Net binary convolution block on one MI355X.
+
+One step = one pass of the hot path over one batch resident in HBM:
+    xnor_binactiv (BatchNorm fold, sign + bit-pack, A, K)  ->  xnor_conv2d (binary dot + K*alpha).
+The weights are packed once before the timed region (at inference only B and alpha exist; the
+packing time is reported separately).  Prints ONE JSON line on stdout.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload alexnet_conv2] [--algo auto]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAKS = {  # MI355X published dense peaks
+    "mfma_i8": {"bound": "mfma", "peak": 5000.0, "unit": "TOP/s"},        # int8 5.0 POP/s, 2 ops per MAC
+    # vector ALU bitcount: 2 instructions (XOR, bitcount-accumulate) per 32 binary MACs:
+    # 256 CUs x 64 lanes x 2.4 GHz x 16 MAC per lane-instruction
+    "popcount": {"bound": "alu", "peak": 256 * 64 * 2.4e9 * 16 / 1e12, "unit": "Tbinop/s"},
+}
+
+
+def cpu_baseline(layers, inputs):
+    """The oracle as it stands, whole block, on this machine's host cores."""
+    from oracle import xnor_oracle as xo
+    xo.binary_conv2d(inputs[0]["x"][:1], inputs[0]["w"], (1, 1), (0, 0))   # load + warm the library
+    t0 = time.perf_counter()
+    macs = 0
+    for layer, d in zip(layers, inputs):
+        xo.binary_conv2d(d["x"], d["w"], (layer.stride,) * 2, (layer.pad,) * 2, d["bn_scale"], d["bn_shift"])
+        macs += layer.bit_macs
+    dt = time.perf_counter() - t0
+    return {"value": macs / dt / 1e9, "unit": "Gbinop/s", "cores": xo.threads(), "kind": "oracle",
+            "sample": f"full workload ({len(layers)} layer(s), batch {layers[0].n}), {dt:.2f} s wall"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="alexnet_conv2",
+                    choices=["tiny", "alexnet_conv2", "alexnet_conv345", "resnet18"])
+    ap.add_argument("--algo", default="auto", choices=["auto", "popcount", "mfma_i8"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (the path shards over the batch with no "
+                 "exchange step; see DESIGN.md). Run with --gpus 1.")
+
+    import torch
+    from paper_1603_05279_amd import workloads as wl
+    from paper_1603_05279_amd import xnor
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    torch.cuda.set_device(0)
+    layers = wl.config_layers(args.workload)
+    inputs = [wl.conv_inputs(l, wl.config_seed(args.workload, i)) for i, l in enumerate(layers)]
+    algo = xnor.ALGOS[args.algo]
+
+    # device state: inputs, packed weights, preallocated activation buffers
+    dev = []
+    pack_ms = 0.0
+    for layer, d in zip(layers, inputs):
+        x = torch.from_numpy(d["x"]).cuda()
+        w = torch.from_numpy(d["w"]).cuda()
+        sc = torch.from_numpy(d["bn_scale"]).cuda() if d["bn_scale"] is not None else None
+        sf = torch.from_numpy(d["bn_shift"]).cuda() if d["bn_shift"] is not None else None
+        desc = xnor.make_desc(layer.n, layer.c, layer.h, layer.w, layer.k_out, layer.kh, layer.kw,
+                              layer.stride, layer.pad)
+        pw = xnor.PackedWeights(w)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        xnor.xnor_pack_weights(w, pw.wbits, pw.alpha, pw.wmfma, *pw.shape)
+        e1.record()
+        torch.cuda.synchronize()
+        pack_ms += e0.elapsed_time(e1)
+        dev.append((x, sc, sf, pw, xnor.ConvBuffers(desc)))
+
+    def step(events=None):
+        for i, (x, sc, sf, pw, bufs) in enumerate(dev):
+            xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, bufs.K, bufs.desc)
+            if events is not None:
+                events[i][0].record()
+            xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, bufs.out, None, bufs.desc, algo)
+            if events is not None:
+                events[i][1].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in dev]
+          for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for s in range(args.steps):
+        step(ev[s])
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    macs = sum(l.bit_macs for l in layers)
+    ms_per_step = dt / args.steps * 1e3
+    # dominant kernel = the binary convolution; average launch duration from the HIP events
+    conv_ms = [sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)) / args.steps
+               for i in range(len(dev))]
+    dom = max(range(len(dev)), key=lambda i: conv_ms[i])
+    used = "mfma_i8" if args.algo in ("auto", "mfma_i8") else "popcount"
+    pk = PEAKS[used]
+    per_mac = 2.0 if used == "mfma_i8" else 1.0
+    achieved = layers[dom].bit_macs * per_mac / (conv_ms[dom] * 1e-3) / 1e12
+    out = {
+        "metric": "binary conv throughput (Gbinop/s) + % of popcount/MFMA roofline",
+        "value": macs / (dt / args.steps) / 1e9, "unit": "Gbinop/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "i8" if used == "mfma_i8" else "u32", "data": "synthetic",
+        "config": {"workload": args.workload, "layers": [l.name for l in layers], "batch": layers[0].n,
+                   "algo": used, "step": "xnor_binactiv + xnor_conv2d per layer",
+                   "conv_ms": conv_ms, "pack_weights_ms_once": pack_ms,
+                   "conv_only_Gbinop_s": [l.bit_macs / (t * 1e-3) / 1e9 for l, t in zip(layers, conv_ms)]},
+        "roofline": {"bound": pk["bound"], "achieved": achieved, "peak": pk["peak"], "unit": pk["unit"],
+                     "frac": achieved / pk["peak"], "traffic": None, "kernel": f"xnor_conv2d[{layers[dom].name}]"},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(layers, inputs)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
