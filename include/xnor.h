@@ -52,7 +52,9 @@ typedef enum {
 typedef enum {
     XNOR_ALGO_AUTO = 0,     /* the library's choice for the shape                                  */
     XNOR_ALGO_POPCOUNT = 1, /* XOR + bitcount on the vector ALU over the packed words              */
-    XNOR_ALGO_MFMA_I8 = 2   /* +-1 (0 for padding) widened to int8 on chip, int8 matrix cores      */
+    XNOR_ALGO_MFMA_I8 = 2,  /* +-1 (0 for padding) widened to int8 on chip, int8 matrix cores      */
+    XNOR_ALGO_MFMA_F4 = 3   /* same, widened to 4-bit floats (E2M1), f8f6f4 matrix cores; exact:   */
+                            /* products are +-1 or 0 and the float sums stay below 2^24             */
 } xnor_algo;
 
 /* Problem statement of sec. 3: input c x w_in x h_in, filters c x w x h, plus stride and pad. */
@@ -74,6 +76,13 @@ const char *xnor_status_string(int status);
 
 /* Bytes of the matrix-core weight image written by xnor_pack_weights (0 if the shape is invalid). */
 size_t xnor_wmfma_bytes(int k_out, int c, int kh, int kw);
+
+/*
+ * Benchmarking hook (host state, not thread-safe): mfma_tile 1..9 forces one workgroup tiling of
+ * the matrix-core kernels, 0 restores the library's per-shape choice; lds_budget_bytes > 0 caps the
+ * LDS image of a workgroup (0 keeps the current cap).  Results never depend on it.
+ */
+int xnor_set_tuning(int mfma_tile, int lds_budget_bytes);
 
 /*
  * sign(I) packed to bits (BinActiv layer, sec. 3.2; sign rule of sec. 3.1).
@@ -108,7 +117,7 @@ int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
  *   wbits  out  uint32  [k_out][kh][kw][Cw]
  *   alpha  out  float32 [k_out]
  *   wmfma  out  (nullable) xnor_wmfma_bytes(...) bytes: the same signs laid out for the matrix
- *               cores; required by XNOR_ALGO_MFMA_I8, opaque to the caller.
+ *               cores; required by the XNOR_ALGO_MFMA_* loops, opaque to the caller.
  */
 int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
                       int k_out, int c, int kh, int kw, void *hip_stream);
@@ -119,7 +128,7 @@ int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma
  *                   = n_valid - 2*bitcount(xbits XOR wbits)        (sec. 3.2).
  *   xbits, wbits, K, alpha  in   as produced above
  *   wmfma    in   (nullable) from xnor_pack_weights; NULL forces XNOR_ALGO_POPCOUNT under AUTO and
- *                 is an XNOR_ERR_NULL under XNOR_ALGO_MFMA_I8
+ *                 is an XNOR_ERR_NULL under XNOR_ALGO_MFMA_*
  *   out      out  float32 [n][k_out][h_out][w_out]
  *   dot_out  out  (nullable) int32 same shape: the exact integer map, for verification
  *   algo          an xnor_algo

@@ -33,6 +33,7 @@ xnor_status make_geom(const xnor_conv_desc *d, ConvGeom *g)
     g->fblocks = (d->k_out + 31) / 32;
     g->div_wo = FastDiv::make((uint32_t)wo);
     g->div_howo = FastDiv::make((uint32_t)(ho * wo));
+    g->div_kw = FastDiv::make((uint32_t)d->kw);
     return XNOR_OK;
 }
 
@@ -75,7 +76,16 @@ const char *xnor_status_string(int status)
 size_t xnor_wmfma_bytes(int k_out, int c, int kh, int kw)
 {
     if (k_out <= 0 || c <= 0 || kh <= 0 || kw <= 0) return 0;
-    return (size_t)((k_out + 31) / 32) * (size_t)kh * kw * (size_t)((c + 31) / 32) * 1024u;
+    if ((long long)kh * kw > 4096) return 0;
+    return wimg_i8_bytes(k_out, c, kh * kw) + wimg_f4_bytes(k_out, c, kh * kw);
+}
+
+int xnor_set_tuning(int mfma_tile, int lds_budget_bytes)
+{
+    if (mfma_tile < 0 || mfma_tile > 9 || lds_budget_bytes < 0 || lds_budget_bytes > 160 * 1024)
+        return XNOR_ERR_UNSUPPORTED;
+    set_mfma_tuning(mfma_tile, lds_budget_bytes);
+    return XNOR_OK;
 }
 
 int xnor_binarize_pack(const float *x, const float *bn_scale, const float *bn_shift,
@@ -143,11 +153,12 @@ int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
     case XNOR_ALGO_POPCOUNT:
         return launch_conv_popcount(xbits, wbits, K, alpha, out, dot_out, g, st);
     case XNOR_ALGO_MFMA_I8:
+    case XNOR_ALGO_MFMA_F4:
         if (!wmfma) return XNOR_ERR_NULL;
-        return launch_conv_mfma_i8(xbits, wmfma, K, alpha, out, dot_out, g, st);
+        return launch_conv_mfma(algo == XNOR_ALGO_MFMA_F4 ? 1 : 0, xbits, wmfma, K, alpha, out, dot_out, g, st);
     case XNOR_ALGO_AUTO: {
         if (wmfma) {
-            const xnor_status s = launch_conv_mfma_i8(xbits, wmfma, K, alpha, out, dot_out, g, st);
+            const xnor_status s = launch_conv_mfma(1, xbits, wmfma, K, alpha, out, dot_out, g, st);
             if (s != XNOR_ERR_UNSUPPORTED) return s;
         }
         return launch_conv_popcount(xbits, wbits, K, alpha, out, dot_out, g, st);

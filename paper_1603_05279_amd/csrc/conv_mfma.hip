@@ -1,49 +1,129 @@
-// Binary convolution on the int8 matrix cores (sec. 3.2).  The +-1 product-sum that XNOR +
-// bitcount evaluates is the same integer as an int8 dot product of the sign tensors, with 0 for
-// padded positions, so the convolution is run as an implicit GEMM
+// Binary convolution on the matrix cores (sec. 3.2).  The +-1 product-sum that XNOR + bitcount
+// evaluates is the same integer as a dot product of the sign tensors with 0 at padded positions,
+// so the convolution is run as an implicit GEMM
 //     D[filter][pixel] = sum_{tap, channel} sW[filter][tap][channel] * sI[pixel + tap][channel]
-// on v_mfma_i32_32x32x32_i8, followed by the fused scaling by K and alpha.
+// followed by the fused scaling by K and alpha.  Two operand encodings, same kernel:
+//   I8: signs widened to int8 (+1, -1, 0), v_mfma_i32_32x32x32_i8, int32 accumulation;
+//   F4: signs widened to 4-bit floats (E2M1 codes 0x2 = +1, 0xA = -1, 0x0 = 0),
+//       v_mfma_scale_f32_32x32x64_f8f6f4 with unit scales.  Products are +-1 or 0 and the sums
+//       stay far below 2^24, so the float accumulation is exact.
 //
 // Work split: a workgroup owns FT = 32*FW*WF filters x PT = 32*PW*WP consecutive output pixels
 // (pixels flattened over image, row, column so small images still fill the tile).  Per channel
 // chunk it widens the packed activation bits of the input rows its pixels touch (halo included,
-// halo = 0) to int8 in LDS once; every tap then reads the same LDS image at a shifted offset.
+// halo = 0) into LDS once; every tap then reads the same LDS image at a shifted offset.
 // Weights come from the pre-widened image written by the weight packer, one contiguous KiB per
-// 32-filter operand.  Filters are the M operand and pixels the N operand, so each lane of the
-// result holds one pixel column: stores along a filter plane are contiguous across lanes.
+// 32-filter operand, prefetched several K-steps ahead in registers.  Filters are the M operand
+// and pixels the N operand, so each lane of the result holds one pixel column: stores along a
+// filter plane are contiguous across lanes.
 #include "xnor_internal.h"
 
 namespace xnor {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 struct MfmaPlan {
     int cc_words;     // channel words widened per chunk (divides cw)
-    int ps;           // bytes per pixel in LDS: cc_words*32 + 16 (odd multiple of 16: no bank conflicts)
+    int ps;           // bytes per pixel in LDS (an odd multiple of 16: conflict-free 16-byte reads)
     int max_rows;     // padded input rows a pixel tile can touch
     int region_bytes; // max_rows * wp * ps
-    FastDiv div_wp, div_hp, div_ccw;
+    int nsteps;       // K-steps per chunk
+    int tap_jump;     // weight records skipped when a chunk moves to the next tap
+    FastDiv div_wp, div_hp, div_ccw, div_cw;
 };
 
-// 4 sign bits -> 4 int8 lanes of a dword: bit 1 -> +1 (0x01), bit 0 -> -1 (0xFF).
-__device__ __forceinline__ uint32_t widen4(uint32_t nibble)
-{
-    const uint32_t t = __umul24(nibble, 0x00204081u) & 0x01010101u;   // bit i -> byte i
-    return __builtin_amdgcn_perm(0x000001FFu, 0x000001FFu, t);         // byte = table[t], table = {0xFF, 0x01}
-}
+template <int FMT> struct Enc;
 
-template <int FW, int PW, int WF, int WP>
-__global__ __launch_bounds__(64 * WF * WP) void conv_mfma_i8_kernel(
-    const uint32_t *__restrict__ xbits, const v4i *__restrict__ wmfma,
+template <> struct Enc<0> {                    // int8
+    static constexpr int BPS = 1;              // channel words per K-step
+    static constexpr int BPB = 32;             // LDS bytes per pixel per channel word
+    typedef v16i acc_t;
+    static __device__ __forceinline__ acc_t mfma(v4i w, v4i x, acc_t c) {
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, c, 0, 0, 0);
+    }
+    static __device__ __forceinline__ int to_int(acc_t a, int v) { return a[v]; }
+    // 4 sign bits -> 4 int8: bit 1 -> 0x01, bit 0 -> 0xFF
+    static __device__ __forceinline__ uint32_t widen4(uint32_t nibble) {
+        const uint32_t t = __umul24(nibble, 0x00204081u) & 0x01010101u;     // bit i -> byte i
+        return __builtin_amdgcn_perm(0x000001FFu, 0x000001FFu, t);           // byte = {0xFF, 0x01}[t]
+    }
+    // one channel word -> 32 bytes at dst; channels >= nch are 0
+    static __device__ __forceinline__ void widen_word(uint8_t *dst, uint32_t bits, bool ok, int nch) {
+        uint4 lo = make_uint4(0, 0, 0, 0), hi = make_uint4(0, 0, 0, 0);
+        if (ok) {
+            lo.x = widen4(bits & 15u);         lo.y = widen4((bits >> 4) & 15u);
+            lo.z = widen4((bits >> 8) & 15u);  lo.w = widen4((bits >> 12) & 15u);
+            hi.x = widen4((bits >> 16) & 15u); hi.y = widen4((bits >> 20) & 15u);
+            hi.z = widen4((bits >> 24) & 15u); hi.w = widen4(bits >> 28);
+            if (nch < 32) {
+                uint32_t *d = reinterpret_cast<uint32_t *>(&lo);
+                uint32_t *e = reinterpret_cast<uint32_t *>(&hi);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int r0 = nch - 4 * q, r1 = nch - 16 - 4 * q;
+                    d[q] &= r0 >= 4 ? 0xFFFFFFFFu : (r0 <= 0 ? 0u : (1u << (8 * r0)) - 1u);
+                    e[q] &= r1 >= 4 ? 0xFFFFFFFFu : (r1 <= 0 ? 0u : (1u << (8 * r1)) - 1u);
+                }
+            }
+        }
+        *reinterpret_cast<uint4 *>(dst) = lo;
+        *reinterpret_cast<uint4 *>(dst + 16) = hi;
+    }
+};
+
+template <> struct Enc<1> {                    // 4-bit float E2M1
+    static constexpr int BPS = 2;
+    static constexpr int BPB = 16;
+    typedef v16f acc_t;
+    static __device__ __forceinline__ acc_t mfma(v4i w, v4i x, acc_t c) {
+        const v8i w8 = {w[0], w[1], w[2], w[3], 0, 0, 0, 0};
+        const v8i x8 = {x[0], x[1], x[2], x[3], 0, 0, 0, 0};
+        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(w8, x8, c, 4, 4, 0, 127, 0, 127);
+    }
+    static __device__ __forceinline__ int to_int(acc_t a, int v) { return (int)a[v]; }
+    // 8 sign bits -> 8 nibbles: bit 1 -> 0x2 (+1.0), bit 0 -> 0xA (-1.0)
+    static __device__ __forceinline__ uint32_t widen8(uint32_t byte) {
+        uint32_t x = byte;                                   // bit i -> bit 4i by three shift-or steps
+        x = (x | (x << 12)) & 0x000F000Fu;
+        x = (x | (x << 6)) & 0x03030303u;
+        x = (x | (x << 3)) & 0x11111111u;
+        return 0xAAAAAAAAu ^ (x << 3);
+    }
+    static __device__ __forceinline__ void widen_word(uint8_t *dst, uint32_t bits, bool ok, int nch) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (ok) {
+            v.x = widen8(bits & 255u);         v.y = widen8((bits >> 8) & 255u);
+            v.z = widen8((bits >> 16) & 255u); v.w = widen8(bits >> 24);
+            if (nch < 32) {
+                uint32_t *d = reinterpret_cast<uint32_t *>(&v);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int r0 = nch - 8 * q;
+                    d[q] &= r0 >= 8 ? 0xFFFFFFFFu : (r0 <= 0 ? 0u : (1u << (4 * r0)) - 1u);
+                }
+            }
+        }
+        *reinterpret_cast<uint4 *>(dst) = v;
+    }
+};
+
+template <int FMT, int FW, int PW, int WF, int WP>
+__global__ __launch_bounds__(64 * WF * WP) void conv_mfma_kernel(
+    const uint32_t *__restrict__ xbits, const v4i *__restrict__ wimg,
     const float *__restrict__ K, const float *__restrict__ alpha, float *__restrict__ out,
     int32_t *__restrict__ dot_out, ConvGeom g, MfmaPlan pl)
 {
+    typedef Enc<FMT> E;
+    typedef typename E::acc_t acc_t;
     constexpr int NT = 64 * WF * WP;
     constexpr int FT = 32 * FW * WF;
     constexpr int PT = 32 * PW * WP;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     int *rowinfo = reinterpret_cast<int *>(lds + pl.region_bytes);
+    int *xoff_tab = rowinfo + pl.max_rows;     // [nsteps * BPS + pad]
 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -52,6 +132,8 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_i8_kernel(
     const uint32_t m0 = blockIdx.x * (uint32_t)PT;
     const int f0 = blockIdx.y * FT;
     const uint32_t howo = (uint32_t)(g.ho * g.wo);
+    const int ccw = pl.cc_words;
+    const int nsteps = pl.nsteps;
 
     // padded input rows this tile touches: R = image*hp + padded row
     const uint32_t m_last = min(m0 + (uint32_t)PT, (uint32_t)g.m_total) - 1u;
@@ -67,6 +149,19 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_i8_kernel(
         const int y = (int)(R - img * g.hp) - g.ph;
         rowinfo[rr] = (y >= 0 && y < g.h) ? (int)(((img * g.h + y) * g.w) * g.cw) : -1;
     }
+    // LDS offset of every channel block of a chunk relative to a pixel's window origin:
+    // block b = tap * ccw + word  ->  (dy*wp + dx)*ps + word*BPB
+    {
+        const int nblk = g.taps * ccw;
+        for (int b = tid; b < nsteps * E::BPS; b += NT) {
+            const uint32_t bb = (uint32_t)min(b, nblk - 1);
+            const uint32_t t = pl.div_ccw.div(bb);
+            const uint32_t wl = bb - t * ccw;
+            const uint32_t dy = g.div_kw.div(t);
+            const uint32_t dx = t - dy * g.kw;
+            xoff_tab[b] = (int)((dy * g.wp + dx) * pl.ps + wl * E::BPB);
+        }
+    }
 
     // LDS byte offset of each of this lane's pixel columns (window origin in the padded frame)
     int pbase[PW];
@@ -76,13 +171,20 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_i8_kernel(
         const uint32_t img = g.div_howo.div(m);
         const uint32_t pix = m - img * howo;
         const uint32_t oy = g.div_wo.div(pix), ox = pix - oy * g.wo;
-        pbase[j] = (((int)(img * g.hp + oy * g.sh) - r_lo) * g.wp + (int)ox * g.sw) * pl.ps + 16 * half;
+        pbase[j] = (((int)(img * g.hp + oy * g.sh) - r_lo) * g.wp + (int)ox * g.sw) * pl.ps +
+                   (E::BPS == 1 ? 16 * half : 0);
     }
-    int fblk[FW];
+    // weight records of this wave's filter blocks: record index = fblk * recs_per_fblock + step record
+    const int recs_per_fb = E::BPS == 1 ? g.taps * g.cw : (g.taps * g.cw + 1) / 2;
+    const v4i *wptr[FW];
 #pragma unroll
-    for (int i = 0; i < FW; ++i) fblk[i] = min(f0 / 32 + wf * FW + i, g.fblocks - 1);
+    for (int i = 0; i < FW; ++i) {
+        const int fb = min(f0 / 32 + wf * FW + i, g.fblocks - 1);
+        wptr[i] = wimg + (size_t)fb * recs_per_fb * 64 + lane;
+    }
+    const int tab_lane = (E::BPS == 2 ? half : 0);
 
-    v16i acc[FW][PW];
+    acc_t acc[FW][PW];
 #pragma unroll
     for (int i = 0; i < FW; ++i)
 #pragma unroll
@@ -90,66 +192,84 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_i8_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
-    const int ccw = pl.cc_words;
+    const int steps_per_tap = pl.tap_jump ? ccw / E::BPS : 0x7fffffff;
     for (int wbase = 0; wbase < g.cw; wbase += ccw) {
-        __syncthreads();   // rowinfo visible / previous chunk fully consumed
+        __syncthreads();   // tables visible / previous chunk fully consumed
         const int items = nrows * g.wp * ccw;
         for (int it = tid; it < items; it += NT) {
             const uint32_t px = pl.div_ccw.div((uint32_t)it);
             const int wl = it - (int)px * ccw;
             const uint32_t rr = pl.div_wp.div(px);
-            const int col = (int)(px - rr * g.wp);
-            const int xcol = col - g.pw;
+            const int xcol = (int)(px - rr * g.wp) - g.pw;
             const int rowbase = rowinfo[rr];
             const bool ok = rowbase >= 0 && xcol >= 0 && xcol < g.w;
-            uint4 lo = make_uint4(0, 0, 0, 0), hi = make_uint4(0, 0, 0, 0);
-            if (ok) {
-                const uint32_t bits = xbits[(size_t)rowbase + (size_t)xcol * g.cw + wbase + wl];
-                lo.x = widen4(bits & 15u);         lo.y = widen4((bits >> 4) & 15u);
-                lo.z = widen4((bits >> 8) & 15u);  lo.w = widen4((bits >> 12) & 15u);
-                hi.x = widen4((bits >> 16) & 15u); hi.y = widen4((bits >> 20) & 15u);
-                hi.z = widen4((bits >> 24) & 15u); hi.w = widen4(bits >> 28);
-                const int nch = g.c - (wbase + wl) * 32;   // channels present in this word
-                if (nch < 32) {                              // zero the channel padding
-                    uint32_t *d = reinterpret_cast<uint32_t *>(&lo);
-                    uint32_t *e = reinterpret_cast<uint32_t *>(&hi);
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int r0 = nch - 4 * q, r1 = nch - 16 - 4 * q;
-                        d[q] &= r0 >= 4 ? 0xFFFFFFFFu : (r0 <= 0 ? 0u : (1u << (8 * r0)) - 1u);
-                        e[q] &= r1 >= 4 ? 0xFFFFFFFFu : (r1 <= 0 ? 0u : (1u << (8 * r1)) - 1u);
-                    }
-                }
-            }
-            uint8_t *dst = lds + (size_t)px * pl.ps + wl * 32;
-            *reinterpret_cast<uint4 *>(dst) = lo;
-            *reinterpret_cast<uint4 *>(dst + 16) = hi;
+            uint32_t bits = 0;
+            if (ok) bits = xbits[(size_t)rowbase + (size_t)xcol * g.cw + wbase + wl];
+            E::widen_word(lds + (size_t)px * pl.ps + wl * E::BPB, bits, ok, g.c - (wbase + wl) * 32);
         }
         __syncthreads();
 
-        for (int dy = 0; dy < g.kh; ++dy)
-            for (int dx = 0; dx < g.kw; ++dx) {
-                const int tapoff = (dy * g.wp + dx) * pl.ps;
-                const int t = dy * g.kw + dx;
-                for (int ks = 0; ks < ccw; ++ks) {
-                    v4i wfr[FW], xfr[PW];
+        // ---- software-pipelined K loop over this chunk's steps --------------------------------
+        // record of step s: rec0 + s + (s / steps_per_tap) * tap_jump
+        // weight records are consumed in order: +1 per step, +tap_jump more when a chunk that
+        // holds only part of the channels moves to the next tap; the stream parks on the last
+        // record so the prefetches past the end stay in bounds
+        int w_rec = wbase / E::BPS, w_cnt = 0, w_left = nsteps;
+        auto load_w = [&](v4i (&dst)[FW]) {
 #pragma unroll
-                    for (int i = 0; i < FW; ++i)
-                        wfr[i] = wmfma[(((size_t)fblk[i] * g.taps + t) * g.cw + wbase + ks) * 64 + lane];
-#pragma unroll
-                    for (int j = 0; j < PW; ++j)
-                        xfr[j] = *reinterpret_cast<const v4i *>(lds + pbase[j] + tapoff + ks * 32);
-#pragma unroll
-                    for (int i = 0; i < FW; ++i)
-#pragma unroll
-                        for (int j = 0; j < PW; ++j)
-                            acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wfr[i], xfr[j], acc[i][j], 0, 0, 0);
-                }
+            for (int i = 0; i < FW; ++i) dst[i] = wptr[i][(size_t)w_rec * 64];
+            if (w_left > 1) {
+                --w_left; ++w_rec;
+                if (++w_cnt == steps_per_tap) { w_cnt = 0; w_rec += pl.tap_jump; }
             }
+        };
+        auto load_t = [&](int s) -> int { return xoff_tab[min(s, nsteps - 1) * E::BPS + tab_lane]; };
+        auto load_x = [&](v4i (&dst)[PW], int toff) {
+#pragma unroll
+            for (int j = 0; j < PW; ++j) dst[j] = *reinterpret_cast<const v4i *>(lds + pbase[j] + toff);
+        };
+        auto fma_all = [&](const v4i (&w)[FW], const v4i (&x)[PW]) {
+#pragma unroll
+            for (int j = 0; j < PW; ++j)
+#pragma unroll
+                for (int i = 0; i < FW; ++i) acc[i][j] = E::mfma(w[i], x[j], acc[i][j]);
+        };
+
+        v4i w0[FW], w1[FW], w2[FW], w3[FW], x0[PW], x1[PW];
+        int t1, t2;
+        load_w(w0); load_w(w1); load_w(w2);
+        load_x(x0, load_t(0));
+        t1 = load_t(1);
+        for (int s = 0; s < nsteps; s += 4) {
+            // step s
+            load_w(w3); t2 = load_t(s + 2); load_x(x1, t1);
+            fma_all(w0, x0);
+            if (s + 1 < nsteps) {
+                load_w(w0); t1 = load_t(s + 3); load_x(x0, t2);
+                fma_all(w1, x1);
+            }
+            if (s + 2 < nsteps) {
+                load_w(w1); t2 = load_t(s + 4); load_x(x1, t1);
+                fma_all(w2, x0);
+            }
+            if (s + 3 < nsteps) {
+                load_w(w2); t1 = load_t(s + 5); load_x(x0, t2);
+                fma_all(w3, x1);
+            }
+        }
     }
 
     // epilogue: out = float(dot) * K * alpha; result register v of a lane is filter row
-    // 8*(v/4) + 4*half + v%4 of the 32-filter block, pixel column l32.
+    // 8*(v/4) + 4*half + v%4 of the 32-filter block, pixel column l32.  alpha of the lane's
+    // filter rows is fetched once (clamped index, no branch), stores are predicated.
+    float al[FW][16];
+#pragma unroll
+    for (int i = 0; i < FW; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int k = f0 + (wf * FW + i) * 32 + 4 * half + 8 * (v >> 2) + (v & 3);
+            al[i][v] = alpha[min(k, g.k_out - 1)];
+        }
 #pragma unroll
     for (int j = 0; j < PW; ++j) {
         const uint32_t m = m0 + (uint32_t)((wp * PW + j) * 32 + l32);
@@ -160,14 +280,20 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_i8_kernel(
 #pragma unroll
         for (int i = 0; i < FW; ++i) {
             const int kb = f0 + (wf * FW + i) * 32 + 4 * half;
+            float *orow = out + ((size_t)img * g.k_out + kb) * howo + pix;
+            if (kb + 28 < g.k_out && !dot_out) {        // whole block of rows in range
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int k = kb + 8 * (v >> 2) + (v & 3);
-                if (k < g.k_out) {
-                    const int dot = acc[i][j][v];
-                    const size_t o = ((size_t)img * g.k_out + k) * howo + pix;
-                    out[o] = (float)dot * Km * alpha[k];
-                    if (dot_out) dot_out[o] = dot;
+                for (int v = 0; v < 16; ++v)
+                    orow[(size_t)(8 * (v >> 2) + (v & 3)) * howo] = (float)E::to_int(acc[i][j], v) * Km * al[i][v];
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int kr = 8 * (v >> 2) + (v & 3);
+                    if (kb + kr < g.k_out) {
+                        const int dot = E::to_int(acc[i][j], v);
+                        orow[(size_t)kr * howo] = (float)dot * Km * al[i][v];
+                        if (dot_out) dot_out[((size_t)img * g.k_out + kb + kr) * howo + pix] = dot;
+                    }
                 }
             }
         }
@@ -191,39 +317,60 @@ static int worst_rows(const ConvGeom &g, int PT)
 
 static const int LDS_LIMIT = 160 * 1024;
 
-static bool make_plan(const ConvGeom &g, int PT, int lds_budget, MfmaPlan *pl)
+static size_t plan_lds_bytes(const MfmaPlan &pl, int bps)
 {
+    return (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 + (size_t)(pl.nsteps * bps) * 4 + 16;
+}
+
+static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, MfmaPlan *pl)
+{
+    const int bps = fmt == 0 ? 1 : 2, bpb = fmt == 0 ? 32 : 16;
     const int rows = worst_rows(g, PT);
     for (int ccw = g.cw; ccw >= 1; --ccw) {
         if (g.cw % ccw) continue;
-        const long long ps = (long long)ccw * 32 + 16;
+        // 4-bit operands take two channel words per step: chunks must keep word pairs together
+        if (bps == 2 && ccw != g.cw && (ccw % 2)) continue;
+        const long long row_bytes = (long long)ccw * bpb;
+        const long long ps = row_bytes + ((row_bytes / 16) % 2 == 0 ? 16 : 0);
         const long long region = (long long)rows * g.wp * ps;
-        const long long total = region + (long long)rows * 4 + 16;
-        if (total > lds_budget && ccw > 1) continue;
-        if (total > LDS_LIMIT) return false;
-        if (region * 1 >= (1ll << 30)) return false;
         pl->cc_words = ccw;
         pl->ps = (int)ps;
         pl->max_rows = rows;
+        pl->nsteps = (g.taps * ccw + bps - 1) / bps;
+        pl->tap_jump = (ccw == g.cw) ? 0 : (g.cw - ccw) / bps;
+        if (region >= (1ll << 30)) continue;
         pl->region_bytes = (int)region;
+        const long long total = (long long)plan_lds_bytes(*pl, bps);
+        const bool last = (ccw == 1) || (bps == 2 && ccw == 2);
+        if (total > lds_budget && !last) continue;
+        if (total > LDS_LIMIT) return false;
         pl->div_wp = FastDiv::make((uint32_t)g.wp);
         pl->div_hp = FastDiv::make((uint32_t)g.hp);
         pl->div_ccw = FastDiv::make((uint32_t)ccw);
+        pl->div_cw = FastDiv::make((uint32_t)g.cw);
         return true;
     }
     return false;
 }
 
-template <int FW, int PW, int WF, int WP>
-static xnor_status launch_cfg(const uint32_t *xbits, const void *wmfma, const float *K,
+static int g_tile_override = 0;
+static int g_lds_budget = 64 * 1024;
+void set_mfma_tuning(int tile, int lds_budget)
+{
+    g_tile_override = tile;
+    if (lds_budget > 0) g_lds_budget = lds_budget;
+}
+
+template <int FMT, int FW, int PW, int WF, int WP>
+static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const float *K,
                               const float *alpha, float *out, int32_t *dot_out, const ConvGeom &g,
                               hipStream_t stream)
 {
     constexpr int FT = 32 * FW * WF, PT = 32 * PW * WP;
     MfmaPlan pl;
-    if (!make_plan(g, PT, 64 * 1024, &pl)) return XNOR_ERR_UNSUPPORTED;
-    const size_t lds = (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 + 16;
-    auto kern = conv_mfma_i8_kernel<FW, PW, WF, WP>;
+    if (!make_plan(g, PT, FMT, g_lds_budget, &pl)) return XNOR_ERR_UNSUPPORTED;
+    const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2);
+    auto kern = conv_mfma_kernel<FMT, FW, PW, WF, WP>;
     static bool attr_done = false;   // per instantiation
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -233,17 +380,42 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wmfma, const fl
     }
     dim3 grid((unsigned)((g.m_total + PT - 1) / PT), (unsigned)((g.k_out + FT - 1) / FT)), block(64 * WF * WP);
     if (grid.y > 65535u) return XNOR_ERR_UNSUPPORTED;
-    kern<<<grid, block, lds, stream>>>(xbits, reinterpret_cast<const v4i *>(wmfma), K, alpha, out, dot_out, g, pl);
+    kern<<<grid, block, lds, stream>>>(xbits, reinterpret_cast<const v4i *>(wimg), K, alpha, out, dot_out, g, pl);
     return hip_status(hipGetLastError());
 }
 
-xnor_status launch_conv_mfma_i8(const uint32_t *xbits, const void *wmfma, const float *K,
-                                const float *alpha, float *out, int32_t *dot_out,
-                                const ConvGeom &g, hipStream_t stream)
+template <int FMT>
+static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const float *K,
+                              const float *alpha, float *out, int32_t *dot_out, const ConvGeom &g,
+                              hipStream_t stream)
 {
-    if (g.k_out <= 64)
-        return launch_cfg<2, 2, 1, 4>(xbits, wmfma, K, alpha, out, dot_out, g, stream);
-    return launch_cfg<2, 2, 2, 2>(xbits, wmfma, K, alpha, out, dot_out, g, stream);
+    int tile = g_tile_override;
+    if (tile == 0) tile = (g.k_out <= 64) ? 2 : 1;
+#define XNOR_TILE(ID, FW, PW, WF, WP) \
+    case ID: return launch_cfg<FMT, FW, PW, WF, WP>(xbits, wimg, K, alpha, out, dot_out, g, stream)
+    switch (tile) {
+        XNOR_TILE(1, 2, 2, 2, 2);   // 128 filters x 128 pixels
+        XNOR_TILE(2, 2, 2, 1, 4);   //  64 x 256
+        XNOR_TILE(3, 2, 4, 2, 2);   // 128 x 256
+        XNOR_TILE(4, 2, 3, 4, 1);   // 256 x  96
+        XNOR_TILE(5, 2, 4, 4, 1);   // 256 x 128
+        XNOR_TILE(6, 2, 6, 4, 1);   // 256 x 192
+        XNOR_TILE(7, 4, 2, 2, 2);   // 256 x 128
+        XNOR_TILE(8, 2, 4, 1, 4);   //  64 x 512
+        XNOR_TILE(9, 4, 4, 2, 2);   // 256 x 256
+    default: return XNOR_ERR_UNSUPPORTED;
+    }
+#undef XNOR_TILE
+}
+
+xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, const float *K,
+                             const float *alpha, float *out, int32_t *dot_out,
+                             const ConvGeom &g, hipStream_t stream)
+{
+    const uint8_t *img = static_cast<const uint8_t *>(wmfma);
+    if (fmt == 0) return launch_fmt<0>(xbits, img, K, alpha, out, dot_out, g, stream);
+    img += wimg_i8_bytes(g.k_out, g.c, g.taps);
+    return launch_fmt<1>(xbits, img, K, alpha, out, dot_out, g, stream);
 }
 
 }  // namespace xnor

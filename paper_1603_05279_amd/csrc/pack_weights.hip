@@ -1,14 +1,19 @@
 // Weight binarisation (sec. 3.1): B = sign(W) packed to bits, alpha = ||W||_1 / n per filter.
-// Runs once per layer; at inference only B and alpha are kept.  Also writes the same signs as
-// int8 (+1/-1, 0 for channel or filter padding) in the operand order of the 32x32x32 int8
-// matrix instruction, so the convolution can fetch a whole operand as one contiguous KiB.
+// Runs once per layer; at inference only B and alpha are kept.  Also writes the same signs in
+// matrix-core operand order, so the convolution can fetch a whole 32-filter operand as one
+// contiguous KiB: once as int8 (+1/-1, 0 for channel or filter padding) for the 32x32x32 int8
+// instruction and once as 4-bit floats (E2M1 0x2/0xA/0x0) for the 32x32x64 f8f6f4 instruction.
 #include "xnor_internal.h"
 
 namespace xnor {
 
-// Matrix-core weight image: for filter block fb (32 filters), tap t, channel word wd there is a
-// 1 KiB record; lane l of a wave owns bytes [16*l, 16*l+16): filter fb*32 + (l & 31),
-// channels wd*32 + 16*(l >> 5) + 0..15.
+// int8 image: for filter block fb (32 filters), tap t, channel word wd there is a 1 KiB record
+// (index (fb*taps + t)*cw + wd); lane l of a wave owns bytes [16*l, 16*l+16): filter
+// fb*32 + (l & 31), channels wd*32 + 16*(l >> 5) + 0..15.
+// 4-bit image (after the int8 image): the (tap, word) blocks of a filter are numbered
+// b = t*cw + wd and taken two per record (record fb*ceil(taps*cw/2) + b/2); lane l owns the 32
+// channels of block 2*(b/2) + (l >> 5) as 32 nibbles, channel j in nibble j (low nibble first);
+// a block past the end is all zero.
 __global__ __launch_bounds__(256) void pack_weights_kernel(
     const float *__restrict__ w, uint32_t *__restrict__ wbits, float *__restrict__ alpha,
     int8_t *__restrict__ wmfma, int k_out, int c, int taps, int cw)
@@ -55,6 +60,26 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
             }
             const size_t rec = ((size_t)fb * taps + t) * cw + wd;
             *reinterpret_cast<uint4 *>(wmfma + rec * 1024 + (size_t)(row + 32 * half) * 16) = u.v;
+        }
+        int8_t *w4 = wmfma + wimg_i8_bytes(k_out, c, taps);
+        const int nblk = taps * cw, nrec = (nblk + 1) / 2;
+        for (int item = tid; item < nrec * 2; item += 256) {
+            const int half = item & 1, r = item >> 1;
+            const int b = 2 * r + half;
+            union { uint8_t b[16]; uint4 v; } u;
+            u.v = make_uint4(0, 0, 0, 0);
+            if (real && b < nblk) {
+                const int t = b / cw, wd = b - t * cw;
+#pragma unroll
+                for (int j = 0; j < 32; ++j) {
+                    const int ch = wd * 32 + j;
+                    uint32_t code = 0;
+                    if (ch < c) code = (wk[(size_t)ch * taps + t] >= 0.0f) ? 0x2u : 0xAu;
+                    u.b[j >> 1] |= (uint8_t)(code << (4 * (j & 1)));
+                }
+            }
+            const size_t rec = (size_t)fb * nrec + r;
+            *reinterpret_cast<uint4 *>(w4 + rec * 1024 + (size_t)(row + 32 * half) * 16) = u.v;
         }
     }
 }

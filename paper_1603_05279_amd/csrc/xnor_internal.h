@@ -30,7 +30,7 @@ struct ConvGeom {
     int hp, wp;        // padded input extent h+2ph, w+2pw
     int m_total;       // n*ho*wo output pixels
     int fblocks;       // ceil(k_out/32) filter blocks in the matrix-core weight image
-    FastDiv div_wo, div_howo;
+    FastDiv div_wo, div_howo, div_kw;
 };
 
 inline xnor_status hip_status(hipError_t e) { return e == hipSuccess ? XNOR_OK : XNOR_ERR_HIP; }
@@ -44,8 +44,20 @@ xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, v
 xnor_status launch_conv_popcount(const uint32_t *xbits, const uint32_t *wbits, const float *K,
                                  const float *alpha, float *out, int32_t *dot_out,
                                  const ConvGeom &g, hipStream_t stream);
-xnor_status launch_conv_mfma_i8(const uint32_t *xbits, const void *wmfma, const float *K,
-                                const float *alpha, float *out, int32_t *dot_out,
-                                const ConvGeom &g, hipStream_t stream);
+// fmt 0: int8 operands, fmt 1: 4-bit float operands (both images live in the wmfma buffer)
+xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, const float *K,
+                             const float *alpha, float *out, int32_t *dot_out,
+                             const ConvGeom &g, hipStream_t stream);
+void set_mfma_tuning(int tile, int lds_budget);
+
+// Sizes of the two matrix-core weight images (int8 first, 4-bit float second), 1 KiB records.
+__host__ __device__ inline size_t wimg_i8_bytes(int k_out, int c, int taps)
+{
+    return (size_t)((k_out + 31) / 32) * (size_t)taps * (size_t)((c + 31) / 32) * 1024u;
+}
+__host__ __device__ inline size_t wimg_f4_bytes(int k_out, int c, int taps)
+{
+    return (size_t)((k_out + 31) / 32) * (((size_t)taps * (size_t)((c + 31) / 32) + 1) / 2) * 1024u;
+}
 
 }  // namespace xnor

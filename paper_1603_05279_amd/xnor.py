@@ -11,10 +11,12 @@ import torch
 
 _LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libxnor.so")
 
-XNOR_ALGO_AUTO, XNOR_ALGO_POPCOUNT, XNOR_ALGO_MFMA_I8 = 0, 1, 2
-ALGOS = {"auto": XNOR_ALGO_AUTO, "popcount": XNOR_ALGO_POPCOUNT, "mfma_i8": XNOR_ALGO_MFMA_I8}
+XNOR_ALGO_AUTO, XNOR_ALGO_POPCOUNT, XNOR_ALGO_MFMA_I8, XNOR_ALGO_MFMA_F4 = 0, 1, 2, 3
+ALGOS = {"auto": XNOR_ALGO_AUTO, "popcount": XNOR_ALGO_POPCOUNT, "mfma_i8": XNOR_ALGO_MFMA_I8,
+         "mfma_f4": XNOR_ALGO_MFMA_F4}
 
 EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor_wmfma_bytes",
+           "xnor_set_tuning",
            "xnor_binarize_pack", "xnor_compute_K", "xnor_binactiv", "xnor_pack_weights",
            "xnor_conv2d", "xnor_linear"]
 
@@ -50,6 +52,8 @@ def lib():
         L.xnor_status_string.restype = ctypes.c_char_p
         L.xnor_wmfma_bytes.argtypes = [ip, ip, ip, ip]
         L.xnor_wmfma_bytes.restype = ctypes.c_size_t
+        L.xnor_set_tuning.argtypes = [ip, ip]
+        L.xnor_set_tuning.restype = ip
         L.xnor_binarize_pack.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp]
         L.xnor_binarize_pack.restype = ip
         L.xnor_compute_K.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(ConvDesc), vp]
@@ -76,6 +80,10 @@ def words_per_pixel(c):
 
 def wmfma_bytes(k_out, c, kh, kw):
     return int(lib().xnor_wmfma_bytes(k_out, c, kh, kw))
+
+
+def set_tuning(mfma_tile=0, lds_budget_bytes=0):
+    _check("xnor_set_tuning", lib().xnor_set_tuning(int(mfma_tile), int(lds_budget_bytes)))
 
 
 def make_desc(n, c, h_in, w_in, k_out, kh, kw, stride=(1, 1), pad=(0, 0)):

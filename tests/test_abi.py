@@ -28,8 +28,9 @@ def test_library_exports_every_declared_function():
 def test_small_queries():
     assert [xnor.words_per_pixel(c) for c in (1, 31, 32, 33, 96, 9216)] == [1, 1, 1, 2, 3, 288]
     assert xnor.words_per_pixel(0) == 0
-    assert xnor.wmfma_bytes(256, 96, 5, 5) == 8 * 25 * 3 * 1024
-    assert xnor.wmfma_bytes(33, 1, 1, 1) == 2 * 1024
+    # int8 image: one KiB per (32 filters, tap, word); 4-bit image: one KiB per two (tap, word) blocks
+    assert xnor.wmfma_bytes(256, 96, 5, 5) == 8 * 25 * 3 * 1024 + 8 * 38 * 1024
+    assert xnor.wmfma_bytes(33, 1, 1, 1) == 2 * 1024 + 2 * 1024
     assert xnor.wmfma_bytes(0, 1, 1, 1) == 0
     assert xnor.output_hw(xnor.make_desc(64, 96, 27, 27, 256, 5, 5, 1, 2)) == (27, 27)
     assert xnor.output_hw(xnor.make_desc(1, 5, 7, 6, 2, 2, 2, 2, 1)) == (4, 4)
@@ -60,5 +61,8 @@ def test_invalid_arguments_return_error_codes_without_launching():
     zero_stride = xnor.make_desc(1, 8, 3, 3, 4, 3, 3, 0, 0)
     assert L.xnor_binactiv(fake, None, None, fake, fake, fake, ctypes.byref(zero_stride), None) == ERR_SHAPE
     assert L.xnor_linear(fake, fake, None, fake, fake, fake, None, 0, 8, 8, 1, None) == ERR_SHAPE
+    assert L.xnor_conv2d(fake, fake, None, fake, fake, fake, None, ctypes.byref(good), 3, None) == ERR_NULL
+    assert L.xnor_set_tuning(99, 0) == ERR_UNSUP
+    assert L.xnor_set_tuning(0, 0) == 0
     with pytest.raises(xnor.XnorError):
         xnor.output_hw(big_filter)

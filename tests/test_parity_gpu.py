@@ -10,7 +10,7 @@ from tests.helpers import RTOL, ATOL, assert_block_matches_oracle, gpu_conv_bloc
 
 pytestmark = pytest.mark.gpu
 
-ALGOS = ["popcount", "mfma_i8"]
+ALGOS = ["popcount", "mfma_i8", "mfma_f4"]
 
 # n, c, h, w, k_out, kh, kw, stride, pad — several tiles, ragged tails, odd channel counts
 SMALL = [
