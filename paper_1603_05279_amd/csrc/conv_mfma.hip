@@ -24,6 +24,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
 struct MfmaPlan {
     int cc_words;     // channel words widened per chunk (divides cw)
@@ -110,9 +111,24 @@ template <> struct Enc<1> {                    // 4-bit float E2M1
     }
 };
 
+#ifdef XNOR_TIMELINE
+// Development build only: per-workgroup phase timestamps (100 MHz wall clock) into a caller buffer.
+__device__ long long *g_timeline = nullptr;
+__device__ int g_devflags = 0;
+__device__ int g_stagger_ticks = 0;     // 1: no weight loads, 2: no activation LDS reads, 4: no output stores
+#define XNOR_TL(slot)                                                                         \
+    do {                                                                                      \
+        if (threadIdx.x == 0 && g_timeline)                                                   \
+            g_timeline[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8 + (slot)] = wall_clock64(); \
+    } while (0)
+#else
+#define XNOR_TL(slot) do { } while (0)
+#endif
+
+// Accumulator tiles of up to 8 result blocks leave room for two waves per SIMD (256 registers each).
 template <int FMT, int FW, int PW, int WF, int WP>
-__global__ __launch_bounds__(64 * WF * WP) void conv_mfma_kernel(
-    const uint32_t *__restrict__ xbits, const v4i *__restrict__ wimg,
+__global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfma_kernel(
+    const uint32_t *__restrict__ xbits, const v4i *__restrict__ wimg, uint32_t wimg_bytes,
     const float *__restrict__ K, const float *__restrict__ alpha, float *__restrict__ out,
     int32_t *__restrict__ dot_out, ConvGeom g, MfmaPlan pl)
 {
@@ -125,6 +141,13 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_kernel(
     int *rowinfo = reinterpret_cast<int *>(lds + pl.region_bytes);
     int *xoff_tab = rowinfo + pl.max_rows;     // [nsteps * BPS + pad]
 
+#ifdef XNOR_DEV_STAGGER
+    if (blockIdx.x >= (gridDim.x + 1) / 2) {          // second half of the grid starts later
+        const long long t_end = wall_clock64() + g_stagger_ticks;
+        while (wall_clock64() < t_end) __builtin_amdgcn_s_sleep(8);
+    }
+#endif
+    XNOR_TL(0);
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int l32 = lane & 31, half = lane >> 5;
@@ -149,6 +172,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_kernel(
         const int y = (int)(R - img * g.hp) - g.ph;
         rowinfo[rr] = (y >= 0 && y < g.h) ? (int)(((img * g.h + y) * g.w) * g.cw) : -1;
     }
+    XNOR_TL(5);
     // LDS offset of every channel block of a chunk relative to a pixel's window origin:
     // block b = tap * ccw + word  ->  (dy*wp + dx)*ps + word*BPB
     {
@@ -163,6 +187,7 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_kernel(
         }
     }
 
+    XNOR_TL(6);
     // LDS byte offset of each of this lane's pixel columns (window origin in the padded frame)
     int pbase[PW];
 #pragma unroll
@@ -176,11 +201,17 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_kernel(
     }
     // weight records of this wave's filter blocks: record index = fblk * recs_per_fblock + step record
     const int recs_per_fb = E::BPS == 1 ? g.taps * g.cw : (g.taps * g.cw + 1) / 2;
-    const v4i *wptr[FW];
+    // Weight records are fetched with buffer loads: scalar record offset + the lane's 16-byte slot,
+    // so the K loop spends no vector registers or ALU work on weight addresses.
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<v4i *>(wimg), 0, (int)wimg_bytes, 0x00020000);
+    const int wlane = lane * 16;
+    const int zero_rec = (int)(wimg_bytes >> 10) - 1;      // the image ends with an all-zero record
+    int wrec0[FW];
 #pragma unroll
     for (int i = 0; i < FW; ++i) {
         const int fb = min(f0 / 32 + wf * FW + i, g.fblocks - 1);
-        wptr[i] = wimg + (size_t)fb * recs_per_fb * 64 + lane;
+        wrec0[i] = __builtin_amdgcn_readfirstlane(fb * recs_per_fb);
     }
     const int tab_lane = (E::BPS == 2 ? half : 0);
 
@@ -192,22 +223,38 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
 
+    XNOR_TL(7);
     const int steps_per_tap = pl.tap_jump ? ccw / E::BPS : 0x7fffffff;
     for (int wbase = 0; wbase < g.cw; wbase += ccw) {
         __syncthreads();   // tables visible / previous chunk fully consumed
+        if (wbase == 0) XNOR_TL(1);
         const int items = nrows * g.wp * ccw;
-        for (int it = tid; it < items; it += NT) {
-            const uint32_t px = pl.div_ccw.div((uint32_t)it);
-            const int wl = it - (int)px * ccw;
-            const uint32_t rr = pl.div_wp.div(px);
-            const int xcol = (int)(px - rr * g.wp) - g.pw;
-            const int rowbase = rowinfo[rr];
-            const bool ok = rowbase >= 0 && xcol >= 0 && xcol < g.w;
-            uint32_t bits = 0;
-            if (ok) bits = xbits[(size_t)rowbase + (size_t)xcol * g.cw + wbase + wl];
-            E::widen_word(lds + (size_t)px * pl.ps + wl * E::BPB, bits, ok, g.c - (wbase + wl) * 32);
+        constexpr int FB = 4;                  // items in flight per thread: loads first, then widening
+        for (int it0 = tid; it0 < items; it0 += NT * FB) {
+            uint32_t bits[FB];
+            int dst[FB], nch[FB];
+            bool ok[FB];
+#pragma unroll
+            for (int u = 0; u < FB; ++u) {
+                const int it = it0 + u * NT;
+                const uint32_t itc = (uint32_t)min(it, items - 1);
+                const uint32_t px = pl.div_ccw.div(itc);
+                const int wl = (int)(itc - px * ccw);
+                const uint32_t rr = pl.div_wp.div(px);
+                const int xcol = (int)(px - rr * g.wp) - g.pw;
+                const int rowbase = rowinfo[rr];
+                ok[u] = rowbase >= 0 && xcol >= 0 && xcol < g.w;
+                dst[u] = it < items ? (int)(px * pl.ps + wl * E::BPB) : -1;
+                nch[u] = g.c - (wbase + wl) * 32;
+                bits[u] = 0;
+                if (ok[u]) bits[u] = xbits[(size_t)rowbase + (size_t)xcol * g.cw + wbase + wl];
+            }
+#pragma unroll
+            for (int u = 0; u < FB; ++u)
+                if (dst[u] >= 0) E::widen_word(lds + dst[u], bits[u], ok[u], nch[u]);
         }
         __syncthreads();
+        if (wbase == 0) XNOR_TL(2);
 
         // ---- software-pipelined K loop over this chunk's steps --------------------------------
         // record of step s: rec0 + s + (s / steps_per_tap) * tap_jump
@@ -216,15 +263,28 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_kernel(
         // record so the prefetches past the end stay in bounds
         int w_rec = wbase / E::BPS, w_cnt = 0, w_left = nsteps;
         auto load_w = [&](v4i (&dst)[FW]) {
+            const int live = w_left > 0 ? 1 : 0;   // past the end: the all-zero record
+#ifdef XNOR_DEV_NOW
+            return;
+#endif
 #pragma unroll
-            for (int i = 0; i < FW; ++i) dst[i] = wptr[i][(size_t)w_rec * 64];
-            if (w_left > 1) {
-                --w_left; ++w_rec;
-                if (++w_cnt == steps_per_tap) { w_cnt = 0; w_rec += pl.tap_jump; }
+            for (int i = 0; i < FW; ++i) {
+                const int rec = live ? wrec0[i] + w_rec : zero_rec;
+                const v4u r = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, rec * 1024, 0);
+                dst[i] = v4i{(int)r[0], (int)r[1], (int)r[2], (int)r[3]};
             }
+            // branch-free bookkeeping (scalar selects), so the loop body stays one basic block
+            w_left -= live;
+            w_cnt += live;
+            const int wrap = w_cnt == steps_per_tap ? 1 : 0;
+            w_cnt = wrap ? 0 : w_cnt;
+            w_rec += live + (wrap ? pl.tap_jump : 0);
         };
         auto load_t = [&](int s) -> int { return xoff_tab[min(s, nsteps - 1) * E::BPS + tab_lane]; };
         auto load_x = [&](v4i (&dst)[PW], int toff) {
+#ifdef XNOR_DEV_NOX
+            return;
+#endif
 #pragma unroll
             for (int j = 0; j < PW; ++j) dst[j] = *reinterpret_cast<const v4i *>(lds + pbase[j] + toff);
         };
@@ -236,69 +296,103 @@ __global__ __launch_bounds__(64 * WF * WP) void conv_mfma_kernel(
         };
 
         v4i w0[FW], w1[FW], w2[FW], w3[FW], x0[PW], x1[PW];
+#if defined(XNOR_DEV_NOW) || defined(XNOR_DEV_NOX)
+        for (int i = 0; i < FW; ++i) w0[i] = w1[i] = w2[i] = w3[i] = v4i{lane, 1, 2, 3};
+        for (int j = 0; j < PW; ++j) x0[j] = x1[j] = v4i{3, 2, 1, lane};
+#endif
         int t1, t2;
         load_w(w0); load_w(w1); load_w(w2);
         load_x(x0, load_t(0));
         t1 = load_t(1);
+        // The step count is rounded up to a multiple of 4; the extra steps multiply by the zero
+        // record, so the unrolled body needs no branches and the prefetch depth never drops.
+        // The scheduling barriers pin the order written here (next operands requested, then the
+        // current step's matrix instructions), which the compiler otherwise regroups into one
+        // burst of loads followed by one burst of MFMAs with the LDS latency exposed.
+#define XNOR_STEP(WL, TN, TS, XN, TC, WC, XC)                         \
+        load_w(WL); TN = load_t(TS); load_x(XN, TC);                  \
+        fma_all(WC, XC);                                              \
+        /* interleave: one LDS read behind each of the first PW+1 MFMAs, then the FW weight loads */ \
+        _Pragma("unroll") for (int q = 0; q < PW + 1; ++q) {          \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        \
+        }                                                             \
+        _Pragma("unroll") for (int q = 0; q < FW; ++q) {              \
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);        \
+        }                                                             \
+        __builtin_amdgcn_sched_group_barrier(0x008, FW * PW - PW - 1 - FW, 0); \
+        __builtin_amdgcn_sched_barrier(0);
         for (int s = 0; s < nsteps; s += 4) {
-            // step s
-            load_w(w3); t2 = load_t(s + 2); load_x(x1, t1);
-            fma_all(w0, x0);
-            if (s + 1 < nsteps) {
-                load_w(w0); t1 = load_t(s + 3); load_x(x0, t2);
-                fma_all(w1, x1);
-            }
-            if (s + 2 < nsteps) {
-                load_w(w1); t2 = load_t(s + 4); load_x(x1, t1);
-                fma_all(w2, x0);
-            }
-            if (s + 3 < nsteps) {
-                load_w(w2); t1 = load_t(s + 5); load_x(x0, t2);
-                fma_all(w3, x1);
-            }
+            XNOR_STEP(w3, t2, s + 2, x1, t1, w0, x0)
+            XNOR_STEP(w0, t1, s + 3, x0, t2, w1, x1)
+            XNOR_STEP(w1, t2, s + 4, x1, t1, w2, x0)
+            XNOR_STEP(w2, t1, s + 5, x0, t2, w3, x1)
         }
+#undef XNOR_STEP
     }
 
+    XNOR_TL(3);
     // epilogue: out = float(dot) * K * alpha; result register v of a lane is filter row
     // 8*(v/4) + 4*half + v%4 of the 32-filter block, pixel column l32.  alpha of the lane's
     // filter rows is fetched once (clamped index, no branch), stores are predicated.
-    float al[FW][16];
-#pragma unroll
-    for (int i = 0; i < FW; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int k = f0 + (wf * FW + i) * 32 + 4 * half + 8 * (v >> 2) + (v & 3);
-            al[i][v] = alpha[min(k, g.k_out - 1)];
-        }
+#ifdef XNOR_DEV_NOST
+    XNOR_TL(4);
+    if (E::to_int(acc[0][0], 0) != 123456789) return;
+#endif
+    uint32_t pimg[PW], ppix[PW];
+    float Km[PW];
+    bool plive[PW];
 #pragma unroll
     for (int j = 0; j < PW; ++j) {
         const uint32_t m = m0 + (uint32_t)((wp * PW + j) * 32 + l32);
-        if (m >= (uint32_t)g.m_total) continue;
-        const uint32_t img = g.div_howo.div(m);
-        const uint32_t pix = m - img * howo;
-        const float Km = K[m];
+        plive[j] = m < (uint32_t)g.m_total;
+        const uint32_t mc = plive[j] ? m : (uint32_t)g.m_total - 1u;
+        pimg[j] = g.div_howo.div(mc);
+        ppix[j] = mc - pimg[j] * howo;
+        Km[j] = K[mc];
+    }
 #pragma unroll
-        for (int i = 0; i < FW; ++i) {
-            const int kb = f0 + (wf * FW + i) * 32 + 4 * half;
-            float *orow = out + ((size_t)img * g.k_out + kb) * howo + pix;
-            if (kb + 28 < g.k_out && !dot_out) {        // whole block of rows in range
+    for (int i = 0; i < FW; ++i) {
+        const int kb = f0 + (wf * FW + i) * 32 + 4 * half;
+        float al[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) al[v] = alpha[min(kb + 8 * (v >> 2) + (v & 3), g.k_out - 1)];
+        const bool whole = kb + 28 < g.k_out && !dot_out;      // all 16 rows in range
+#pragma unroll
+        for (int j = 0; j < PW; ++j) {
+            if (!plive[j]) continue;
+            float *orow = out + ((size_t)pimg[j] * g.k_out + kb) * howo + ppix[j];
+            if (whole) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    orow[(size_t)(8 * (v >> 2) + (v & 3)) * howo] = (float)E::to_int(acc[i][j], v) * Km * al[i][v];
+                    orow[(size_t)(8 * (v >> 2) + (v & 3)) * howo] = (float)E::to_int(acc[i][j], v) * Km[j] * al[v];
             } else {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const int kr = 8 * (v >> 2) + (v & 3);
                     if (kb + kr < g.k_out) {
                         const int dot = E::to_int(acc[i][j], v);
-                        orow[(size_t)kr * howo] = (float)dot * Km * al[i][v];
-                        if (dot_out) dot_out[((size_t)img * g.k_out + kb + kr) * howo + pix] = dot;
+                        orow[(size_t)kr * howo] = (float)dot * Km[j] * al[v];
+                        if (dot_out) dot_out[((size_t)pimg[j] * g.k_out + kb + kr) * howo + ppix[j]] = dot;
                     }
                 }
             }
         }
     }
+    XNOR_TL(4);
 }
+
+#ifdef XNOR_TIMELINE
+extern "C" int xnor_debug_flags(int flags)
+{
+    return hipMemcpyToSymbol(HIP_SYMBOL(xnor::g_stagger_ticks), &flags, sizeof(flags)) == hipSuccess ? 0 : -5;
+}
+extern "C" int xnor_debug_timeline(long long *buf)
+{
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_timeline), &buf, sizeof(buf)) == hipSuccess ? 0 : -5;
+}
+#endif
 
 // Padded input rows touched by the worst pixel tile of PT consecutive output pixels.
 static int worst_rows(const ConvGeom &g, int PT)
@@ -380,7 +474,10 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     }
     dim3 grid((unsigned)((g.m_total + PT - 1) / PT), (unsigned)((g.k_out + FT - 1) / FT)), block(64 * WF * WP);
     if (grid.y > 65535u) return XNOR_ERR_UNSUPPORTED;
-    kern<<<grid, block, lds, stream>>>(xbits, reinterpret_cast<const v4i *>(wimg), K, alpha, out, dot_out, g, pl);
+    const size_t img_bytes = FMT == 0 ? wimg_i8_bytes(g.k_out, g.c, g.taps) : wimg_f4_bytes(g.k_out, g.c, g.taps);
+    if (img_bytes > 0x7fffffffull) return XNOR_ERR_UNSUPPORTED;
+    kern<<<grid, block, lds, stream>>>(xbits, reinterpret_cast<const v4i *>(wimg), (uint32_t)img_bytes, K, alpha,
+                                       out, dot_out, g, pl);
     return hip_status(hipGetLastError());
 }
 

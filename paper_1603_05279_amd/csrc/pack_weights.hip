@@ -81,6 +81,10 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
             const size_t rec = (size_t)fb * nrec + r;
             *reinterpret_cast<uint4 *>(w4 + rec * 1024 + (size_t)(row + 32 * half) * 16) = u.v;
         }
+        if (k == 0 && tid < 128) {      // the trailing all-zero record of each image
+            int8_t *z = tid < 64 ? w4 - 1024 : w4 + wimg_f4_bytes(k_out, c, taps) - 1024;
+            *reinterpret_cast<uint4 *>(z + (size_t)(tid & 63) * 16) = make_uint4(0, 0, 0, 0);
+        }
     }
 }
 

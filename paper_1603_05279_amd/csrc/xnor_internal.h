@@ -50,14 +50,15 @@ xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, 
                              const ConvGeom &g, hipStream_t stream);
 void set_mfma_tuning(int tile, int lds_budget);
 
-// Sizes of the two matrix-core weight images (int8 first, 4-bit float second), 1 KiB records.
+// Sizes of the two matrix-core weight images (int8 first, 4-bit float second), 1 KiB records;
+// each image ends with one all-zero record that padded K-steps multiply by.
 __host__ __device__ inline size_t wimg_i8_bytes(int k_out, int c, int taps)
 {
-    return (size_t)((k_out + 31) / 32) * (size_t)taps * (size_t)((c + 31) / 32) * 1024u;
+    return ((size_t)((k_out + 31) / 32) * (size_t)taps * (size_t)((c + 31) / 32) + 1) * 1024u;
 }
 __host__ __device__ inline size_t wimg_f4_bytes(int k_out, int c, int taps)
 {
-    return (size_t)((k_out + 31) / 32) * (((size_t)taps * (size_t)((c + 31) / 32) + 1) / 2) * 1024u;
+    return ((size_t)((k_out + 31) / 32) * (((size_t)taps * (size_t)((c + 31) / 32) + 1) / 2) + 1) * 1024u;
 }
 
 }  // namespace xnor
