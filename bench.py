@@ -18,6 +18,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAKS = {  # MI355X published dense peaks
+    "mfma_f4": {"bound": "mfma", "peak": 10100.0, "unit": "TFLOP/s"},     # fp4 10.1 PFLOP/s, 2 flops per MAC
     "mfma_i8": {"bound": "mfma", "peak": 5000.0, "unit": "TOP/s"},        # int8 5.0 POP/s, 2 ops per MAC
     # vector ALU bitcount: 2 instructions (XOR, bitcount-accumulate) per 32 binary MACs:
     # 256 CUs x 64 lanes x 2.4 GHz x 16 MAC per lane-instruction
@@ -46,7 +47,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="alexnet_conv2",
                     choices=["tiny", "alexnet_conv2", "alexnet_conv345", "resnet18"])
-    ap.add_argument("--algo", default="auto", choices=["auto", "popcount", "mfma_i8"])
+    ap.add_argument("--algo", default="fastest", choices=["fastest", "popcount", "mfma_i8", "mfma_f4"],
+                    help="inner loop of the binary convolution; 'fastest' times all three and keeps the winner")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -62,7 +64,6 @@ def main():
     torch.cuda.set_device(0)
     layers = wl.config_layers(args.workload)
     inputs = [wl.conv_inputs(l, wl.config_seed(args.workload, i)) for i, l in enumerate(layers)]
-    algo = xnor.ALGOS[args.algo]
 
     # device state: inputs, packed weights, preallocated activation buffers
     dev = []
@@ -82,6 +83,25 @@ def main():
         torch.cuda.synchronize()
         pack_ms += e0.elapsed_time(e1)
         dev.append((x, sc, sf, pw, xnor.ConvBuffers(desc)))
+
+    def conv_only_ms(name, iters=10):
+        """Average conv-kernel time of one pass over all layers with inner loop `name` (HIP events)."""
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for it in range(iters + 2):
+            if it == 2:
+                e0.record()
+            for (x, sc, sf, pw, bufs) in dev:
+                xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, bufs.out, None, bufs.desc,
+                                 xnor.ALGOS[name])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters
+
+    for (x, sc, sf, pw, bufs) in dev:
+        xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, bufs.K, bufs.desc)
+    compare = {name: conv_only_ms(name) for name in ("popcount", "mfma_i8", "mfma_f4")}
+    used = min(compare, key=compare.get) if args.algo == "fastest" else args.algo
+    algo = xnor.ALGOS[used]
 
     def step(events=None):
         for i, (x, sc, sf, pw, bufs) in enumerate(dev):
@@ -109,18 +129,17 @@ def main():
     conv_ms = [sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in range(args.steps)) / args.steps
                for i in range(len(dev))]
     dom = max(range(len(dev)), key=lambda i: conv_ms[i])
-    used = "mfma_i8" if args.algo in ("auto", "mfma_i8") else "popcount"
     pk = PEAKS[used]
-    per_mac = 2.0 if used == "mfma_i8" else 1.0
+    per_mac = 1.0 if used == "popcount" else 2.0
     achieved = layers[dom].bit_macs * per_mac / (conv_ms[dom] * 1e-3) / 1e12
     out = {
         "metric": "binary conv throughput (Gbinop/s) + % of popcount/MFMA roofline",
         "value": macs / (dt / args.steps) / 1e9, "unit": "Gbinop/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "i8" if used == "mfma_i8" else "u32", "data": "synthetic",
+        "dtype": {"mfma_f4": "fp4", "mfma_i8": "i8", "popcount": "u32"}[used], "data": "synthetic",
         "config": {"workload": args.workload, "layers": [l.name for l in layers], "batch": layers[0].n,
-                   "algo": used, "step": "xnor_binactiv + xnor_conv2d per layer",
+                   "algo": used, "algo_conv_ms": compare, "step": "xnor_binactiv + xnor_conv2d per layer",
                    "conv_ms": conv_ms, "pack_weights_ms_once": pack_ms,
                    "conv_only_Gbinop_s": [l.bit_macs / (t * 1e-3) / 1e9 for l, t in zip(layers, conv_ms)]},
         "roofline": {"bound": pk["bound"], "achieved": achieved, "peak": pk["peak"], "unit": pk["unit"],

@@ -114,8 +114,6 @@ template <> struct Enc<1> {                    // 4-bit float E2M1
 #ifdef XNOR_TIMELINE
 // Development build only: per-workgroup phase timestamps (100 MHz wall clock) into a caller buffer.
 __device__ long long *g_timeline = nullptr;
-__device__ int g_devflags = 0;
-__device__ int g_stagger_ticks = 0;     // 1: no weight loads, 2: no activation LDS reads, 4: no output stores
 #define XNOR_TL(slot)                                                                         \
     do {                                                                                      \
         if (threadIdx.x == 0 && g_timeline)                                                   \
@@ -141,12 +139,6 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     int *rowinfo = reinterpret_cast<int *>(lds + pl.region_bytes);
     int *xoff_tab = rowinfo + pl.max_rows;     // [nsteps * BPS + pad]
 
-#ifdef XNOR_DEV_STAGGER
-    if (blockIdx.x >= (gridDim.x + 1) / 2) {          // second half of the grid starts later
-        const long long t_end = wall_clock64() + g_stagger_ticks;
-        while (wall_clock64() < t_end) __builtin_amdgcn_s_sleep(8);
-    }
-#endif
     XNOR_TL(0);
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
@@ -264,9 +256,6 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         int w_rec = wbase / E::BPS, w_cnt = 0, w_left = nsteps;
         auto load_w = [&](v4i (&dst)[FW]) {
             const int live = w_left > 0 ? 1 : 0;   // past the end: the all-zero record
-#ifdef XNOR_DEV_NOW
-            return;
-#endif
 #pragma unroll
             for (int i = 0; i < FW; ++i) {
                 const int rec = live ? wrec0[i] + w_rec : zero_rec;
@@ -282,9 +271,6 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         };
         auto load_t = [&](int s) -> int { return xoff_tab[min(s, nsteps - 1) * E::BPS + tab_lane]; };
         auto load_x = [&](v4i (&dst)[PW], int toff) {
-#ifdef XNOR_DEV_NOX
-            return;
-#endif
 #pragma unroll
             for (int j = 0; j < PW; ++j) dst[j] = *reinterpret_cast<const v4i *>(lds + pbase[j] + toff);
         };
@@ -296,10 +282,6 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         };
 
         v4i w0[FW], w1[FW], w2[FW], w3[FW], x0[PW], x1[PW];
-#if defined(XNOR_DEV_NOW) || defined(XNOR_DEV_NOX)
-        for (int i = 0; i < FW; ++i) w0[i] = w1[i] = w2[i] = w3[i] = v4i{lane, 1, 2, 3};
-        for (int j = 0; j < PW; ++j) x0[j] = x1[j] = v4i{3, 2, 1, lane};
-#endif
         int t1, t2;
         load_w(w0); load_w(w1); load_w(w2);
         load_x(x0, load_t(0));
@@ -336,10 +318,6 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     // epilogue: out = float(dot) * K * alpha; result register v of a lane is filter row
     // 8*(v/4) + 4*half + v%4 of the 32-filter block, pixel column l32.  alpha of the lane's
     // filter rows is fetched once (clamped index, no branch), stores are predicated.
-#ifdef XNOR_DEV_NOST
-    XNOR_TL(4);
-    if (E::to_int(acc[0][0], 0) != 123456789) return;
-#endif
     uint32_t pimg[PW], ppix[PW];
     float Km[PW];
     bool plive[PW];
@@ -384,10 +362,6 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
 }
 
 #ifdef XNOR_TIMELINE
-extern "C" int xnor_debug_flags(int flags)
-{
-    return hipMemcpyToSymbol(HIP_SYMBOL(xnor::g_stagger_ticks), &flags, sizeof(flags)) == hipSuccess ? 0 : -5;
-}
 extern "C" int xnor_debug_timeline(long long *buf)
 {
     return hipMemcpyToSymbol(HIP_SYMBOL(g_timeline), &buf, sizeof(buf)) == hipSuccess ? 0 : -5;
