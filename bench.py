@@ -1,7 +1,7 @@
 """Benchmark of the XNOR-Net binary convolution block on one MI355X.
 
 One step = one pass of the hot path over one batch resident in HBM:
-    xnor_binactiv (BatchNorm fold, sign + bit-pack, A, K)  ->  xnor_conv2d (binary dot + K*alpha).
+    xnor_binactiv (BatchNorm fold, sign + bit-pack, A)  ->  xnor_conv2d (binary dot, K from A, K*alpha).
 The weights are packed once before the timed region (at inference only B and alpha exist; the
 packing time is reported separately).  Prints ONE JSON line on stdout.
 
@@ -91,24 +91,24 @@ def main():
             if it == 2:
                 e0.record()
             for (x, sc, sf, pw, bufs) in dev:
-                xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, bufs.out, None, bufs.desc,
+                xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha, bufs.out, None, bufs.desc,
                                  xnor.ALGOS[name])
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / iters
 
     for (x, sc, sf, pw, bufs) in dev:
-        xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, bufs.K, bufs.desc)
+        xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, None, bufs.desc)
     compare = {name: conv_only_ms(name) for name in ("popcount", "mfma_i8", "mfma_f4")}
     used = min(compare, key=compare.get) if args.algo == "fastest" else args.algo
     algo = xnor.ALGOS[used]
 
     def step(events=None):
         for i, (x, sc, sf, pw, bufs) in enumerate(dev):
-            xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, bufs.K, bufs.desc)
+            xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, None, bufs.desc)
             if events is not None:
                 events[i][0].record()
-            xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, bufs.out, None, bufs.desc, algo)
+            xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha, bufs.out, None, bufs.desc, algo)
             if events is not None:
                 events[i][1].record()
 

@@ -105,7 +105,8 @@ int xnor_compute_K(const float *x, const float *bn_scale, const float *bn_shift,
 
 /*
  * The whole BinActiv layer in one pass over x: xbits, A and K as the two calls above produce them
- * (bit-identical), reading the float input once.
+ * (bit-identical), reading the float input once.  K may be NULL when the following xnor_conv2d is
+ * given A instead: it then derives K itself and the separate box-filter launch is saved.
  */
 int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
                   uint32_t *xbits, float *A, float *K, const xnor_conv_desc *d, void *hip_stream);
@@ -126,7 +127,11 @@ int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma
  * BinConv layer: out = float(dot) * K * alpha with
  * dot[n][k][oy][ox] = sum over in-bounds taps and channels of sign(I)*sign(W)
  *                   = n_valid - 2*bitcount(xbits XOR wbits)        (sec. 3.2).
- *   xbits, wbits, K, alpha  in   as produced above
+ *   xbits, wbits, alpha  in   as produced above
+ *   K        in   (nullable) float32 [n][h_out][w_out]
+ *   A        in   (nullable) float32 [n][h_in][w_in]; used only when K is NULL: the kernel then
+ *                 evaluates K = box filter of A per output pixel (same bits as xnor_compute_K).
+ *                 K and A must not both be NULL.
  *   wmfma    in   (nullable) from xnor_pack_weights; NULL forces XNOR_ALGO_POPCOUNT under AUTO and
  *                 is an XNOR_ERR_NULL under XNOR_ALGO_MFMA_*
  *   out      out  float32 [n][k_out][h_out][w_out]
@@ -134,7 +139,7 @@ int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma
  *   algo          an xnor_algo
  */
 int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
-                const float *K, const float *alpha, float *out, int32_t *dot_out,
+                const float *K, const float *A, const float *alpha, float *out, int32_t *dot_out,
                 const xnor_conv_desc *d, int algo, void *hip_stream);
 
 /*

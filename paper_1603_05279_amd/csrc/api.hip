@@ -116,14 +116,14 @@ int xnor_compute_K(const float *x, const float *bn_scale, const float *bn_shift,
 int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
                   uint32_t *xbits, float *A, float *K, const xnor_conv_desc *d, void *hip_stream)
 {
-    if (!x || !xbits || !A || !K) return XNOR_ERR_NULL;
+    if (!x || !xbits || !A) return XNOR_ERR_NULL;
     ConvGeom g;
     if (xnor_status s = make_geom(d, &g)) return s;
     if (!aligned16(x) || !aligned16(xbits) || !aligned16(A) || !aligned16(K)) return XNOR_ERR_ALIGN;
     if (xnor_status s = check_bn(bn_scale, bn_shift)) return s;
     hipStream_t st = (hipStream_t)hip_stream;
     if (xnor_status s = launch_binactiv(x, bn_scale, bn_shift, xbits, A, g.n, g.c, g.h * g.w, st)) return s;
-    return launch_boxfilter(A, K, g, st);
+    return K ? launch_boxfilter(A, K, g, st) : XNOR_OK;
 }
 
 int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
@@ -139,29 +139,29 @@ int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma
 }
 
 int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
-                const float *K, const float *alpha, float *out, int32_t *dot_out,
+                const float *K, const float *A, const float *alpha, float *out, int32_t *dot_out,
                 const xnor_conv_desc *d, int algo, void *hip_stream)
 {
-    if (!xbits || !wbits || !K || !alpha || !out) return XNOR_ERR_NULL;
+    if (!xbits || !wbits || (!K && !A) || !alpha || !out) return XNOR_ERR_NULL;
     ConvGeom g;
     if (xnor_status s = make_geom(d, &g)) return s;
-    if (!aligned16(xbits) || !aligned16(wbits) || !aligned16(wmfma) || !aligned16(K) ||
+    if (!aligned16(xbits) || !aligned16(wbits) || !aligned16(wmfma) || !aligned16(K) || !aligned16(A) ||
         !aligned16(alpha) || !aligned16(out) || !aligned16(dot_out))
         return XNOR_ERR_ALIGN;
     hipStream_t st = (hipStream_t)hip_stream;
     switch (algo) {
     case XNOR_ALGO_POPCOUNT:
-        return launch_conv_popcount(xbits, wbits, K, alpha, out, dot_out, g, st);
+        return launch_conv_popcount(xbits, wbits, K, A, alpha, out, dot_out, g, st);
     case XNOR_ALGO_MFMA_I8:
     case XNOR_ALGO_MFMA_F4:
         if (!wmfma) return XNOR_ERR_NULL;
-        return launch_conv_mfma(algo == XNOR_ALGO_MFMA_F4 ? 1 : 0, xbits, wmfma, K, alpha, out, dot_out, g, st);
+        return launch_conv_mfma(algo == XNOR_ALGO_MFMA_F4 ? 1 : 0, xbits, wmfma, K, A, alpha, out, dot_out, g, st);
     case XNOR_ALGO_AUTO: {
         if (wmfma) {
-            const xnor_status s = launch_conv_mfma(1, xbits, wmfma, K, alpha, out, dot_out, g, st);
+            const xnor_status s = launch_conv_mfma(1, xbits, wmfma, K, A, alpha, out, dot_out, g, st);
             if (s != XNOR_ERR_UNSUPPORTED) return s;
         }
-        return launch_conv_popcount(xbits, wbits, K, alpha, out, dot_out, g, st);
+        return launch_conv_popcount(xbits, wbits, K, A, alpha, out, dot_out, g, st);
     }
     default:
         return XNOR_ERR_UNSUPPORTED;
@@ -177,7 +177,7 @@ int xnor_linear(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
     d.n = batch; d.c = in_features; d.h_in = 1; d.w_in = 1;
     d.k_out = out_features; d.kh = 1; d.kw = 1;
     d.stride_h = 1; d.stride_w = 1; d.pad_h = 0; d.pad_w = 0;
-    return xnor_conv2d(xbits, wbits, wmfma, Krow, alpha, out, dot_out, &d, algo, hip_stream);
+    return xnor_conv2d(xbits, wbits, wmfma, Krow, nullptr, alpha, out, dot_out, &d, algo, hip_stream);
 }
 
 }  // extern "C"

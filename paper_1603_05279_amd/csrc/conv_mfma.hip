@@ -127,8 +127,8 @@ __device__ long long *g_timeline = nullptr;
 template <int FMT, int FW, int PW, int WF, int WP>
 __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfma_kernel(
     const uint32_t *__restrict__ xbits, const v4i *__restrict__ wimg, uint32_t wimg_bytes,
-    const float *__restrict__ K, const float *__restrict__ alpha, float *__restrict__ out,
-    int32_t *__restrict__ dot_out, ConvGeom g, MfmaPlan pl)
+    const float *__restrict__ K, const float *__restrict__ A, const float *__restrict__ alpha,
+    float *__restrict__ out, int32_t *__restrict__ dot_out, ConvGeom g, MfmaPlan pl)
 {
     typedef Enc<FMT> E;
     typedef typename E::acc_t acc_t;
@@ -137,7 +137,9 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     constexpr int PT = 32 * PW * WP;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     int *rowinfo = reinterpret_cast<int *>(lds + pl.region_bytes);
-    int *xoff_tab = rowinfo + pl.max_rows;     // [nsteps * BPS + pad]
+    int *xoff_tab = rowinfo + pl.max_rows;     // [nsteps * BPS]
+    float *a_lds = reinterpret_cast<float *>(xoff_tab + pl.nsteps * E::BPS);   // [max_rows * wp], halo = 0
+    float *ktile = a_lds + pl.max_rows * g.wp;                                   // [PT]
 
     XNOR_TL(0);
     const int tid = threadIdx.x;
@@ -162,7 +164,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         const uint32_t R = (uint32_t)(r_lo + rr);
         const uint32_t img = pl.div_hp.div(R);
         const int y = (int)(R - img * g.hp) - g.ph;
-        rowinfo[rr] = (y >= 0 && y < g.h) ? (int)(((img * g.h + y) * g.w) * g.cw) : -1;
+        rowinfo[rr] = (y >= 0 && y < g.h) ? (int)((img * g.h + y) * g.w) : -1;    // first pixel of the row
     }
     XNOR_TL(5);
     // LDS offset of every channel block of a chunk relative to a pixel's window origin:
@@ -239,14 +241,43 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
                 dst[u] = it < items ? (int)(px * pl.ps + wl * E::BPB) : -1;
                 nch[u] = g.c - (wbase + wl) * 32;
                 bits[u] = 0;
-                if (ok[u]) bits[u] = xbits[(size_t)rowbase + (size_t)xcol * g.cw + wbase + wl];
+                if (ok[u]) bits[u] = xbits[((size_t)rowbase + xcol) * g.cw + wbase + wl];
             }
 #pragma unroll
             for (int u = 0; u < FB; ++u)
                 if (dst[u] >= 0) E::widen_word(lds + dst[u], bits[u], ok[u], nch[u]);
         }
+        if (wbase == 0 && !K) {
+            // stage the matrix A of the same input rows (0 in the halo) for the K of this tile
+            for (int it = tid; it < nrows * g.wp; it += NT) {
+                const uint32_t rr = pl.div_wp.div((uint32_t)it);
+                const int xcol = it - (int)rr * g.wp - g.pw;
+                const int rowbase = rowinfo[rr];
+                const bool ok = rowbase >= 0 && xcol >= 0 && xcol < g.w;
+                a_lds[it] = ok ? A[(size_t)rowbase + xcol] : 0.0f;
+            }
+        }
         __syncthreads();
         if (wbase == 0) XNOR_TL(2);
+        if (wbase == 0 && !K) for (int kt = tid; kt < PT; kt += NT) {
+            // K of output pixel m0 + tid: the kh x kw taps of A in row-major order over the staged
+            // rows (halo entries add +0.0f, the same bits as skipping them), divided by kh*kw
+            const uint32_t m = min(m0 + (uint32_t)kt, (uint32_t)g.m_total - 1u);
+            const uint32_t img = g.div_howo.div(m);
+            const uint32_t pix = m - img * howo;
+            const uint32_t oy = g.div_wo.div(pix), ox = pix - oy * g.wo;
+            const float *ap = a_lds + ((int)(img * g.hp + oy * g.sh) - r_lo) * g.wp + (int)ox * g.sw;
+            float s = 0.0f;
+            for (int dy = 0; dy < g.kh; ++dy, ap += g.wp)
+                for (int dx0 = 0; dx0 < g.kw; dx0 += 4) {
+                    float a[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) a[u] = ap[min(dx0 + u, g.kw - 1)];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) s += dx0 + u < g.kw ? a[u] : 0.0f;
+                }
+            ktile[kt] = s / (float)(g.kh * g.kw);
+        }
 
         // ---- software-pipelined K loop over this chunk's steps --------------------------------
         // record of step s: rec0 + s + (s / steps_per_tap) * tap_jump
@@ -318,17 +349,19 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     // epilogue: out = float(dot) * K * alpha; result register v of a lane is filter row
     // 8*(v/4) + 4*half + v%4 of the 32-filter block, pixel column l32.  alpha of the lane's
     // filter rows is fetched once (clamped index, no branch), stores are predicated.
+    if (!K) __syncthreads();      // the K tile is complete
     uint32_t pimg[PW], ppix[PW];
     float Km[PW];
     bool plive[PW];
 #pragma unroll
     for (int j = 0; j < PW; ++j) {
-        const uint32_t m = m0 + (uint32_t)((wp * PW + j) * 32 + l32);
+        const int pl_idx = (wp * PW + j) * 32 + l32;
+        const uint32_t m = m0 + (uint32_t)pl_idx;
         plive[j] = m < (uint32_t)g.m_total;
         const uint32_t mc = plive[j] ? m : (uint32_t)g.m_total - 1u;
         pimg[j] = g.div_howo.div(mc);
         ppix[j] = mc - pimg[j] * howo;
-        Km[j] = K[mc];
+        Km[j] = K ? K[mc] : ktile[pl_idx];
     }
 #pragma unroll
     for (int i = 0; i < FW; ++i) {
@@ -385,9 +418,10 @@ static int worst_rows(const ConvGeom &g, int PT)
 
 static const int LDS_LIMIT = 160 * 1024;
 
-static size_t plan_lds_bytes(const MfmaPlan &pl, int bps)
+static size_t plan_lds_bytes(const MfmaPlan &pl, int bps, int wp, int PT)
 {
-    return (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 + (size_t)(pl.nsteps * bps) * 4 + 16;
+    return (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 + (size_t)(pl.nsteps * bps) * 4 +
+           (size_t)pl.max_rows * wp * 4 + (size_t)PT * 4 + 16;
 }
 
 static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, MfmaPlan *pl)
@@ -408,7 +442,7 @@ static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, MfmaPl
         pl->tap_jump = (ccw == g.cw) ? 0 : (g.cw - ccw) / bps;
         if (region >= (1ll << 30)) continue;
         pl->region_bytes = (int)region;
-        const long long total = (long long)plan_lds_bytes(*pl, bps);
+        const long long total = (long long)plan_lds_bytes(*pl, bps, g.wp, PT);
         const bool last = (ccw == 1) || (bps == 2 && ccw == 2);
         if (total > lds_budget && !last) continue;
         if (total > LDS_LIMIT) return false;
@@ -430,14 +464,14 @@ void set_mfma_tuning(int tile, int lds_budget)
 }
 
 template <int FMT, int FW, int PW, int WF, int WP>
-static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const float *K,
+static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const float *K, const float *A,
                               const float *alpha, float *out, int32_t *dot_out, const ConvGeom &g,
                               hipStream_t stream)
 {
     constexpr int FT = 32 * FW * WF, PT = 32 * PW * WP;
     MfmaPlan pl;
     if (!make_plan(g, PT, FMT, g_lds_budget, &pl)) return XNOR_ERR_UNSUPPORTED;
-    const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2);
+    const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2, g.wp, PT);
     auto kern = conv_mfma_kernel<FMT, FW, PW, WF, WP>;
     static bool attr_done = false;   // per instantiation
     if (!attr_done) {
@@ -450,20 +484,20 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     if (grid.y > 65535u) return XNOR_ERR_UNSUPPORTED;
     const size_t img_bytes = FMT == 0 ? wimg_i8_bytes(g.k_out, g.c, g.taps) : wimg_f4_bytes(g.k_out, g.c, g.taps);
     if (img_bytes > 0x7fffffffull) return XNOR_ERR_UNSUPPORTED;
-    kern<<<grid, block, lds, stream>>>(xbits, reinterpret_cast<const v4i *>(wimg), (uint32_t)img_bytes, K, alpha,
+    kern<<<grid, block, lds, stream>>>(xbits, reinterpret_cast<const v4i *>(wimg), (uint32_t)img_bytes, K, A, alpha,
                                        out, dot_out, g, pl);
     return hip_status(hipGetLastError());
 }
 
 template <int FMT>
-static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const float *K,
+static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const float *K, const float *A,
                               const float *alpha, float *out, int32_t *dot_out, const ConvGeom &g,
                               hipStream_t stream)
 {
     int tile = g_tile_override;
     if (tile == 0) tile = (g.k_out <= 64) ? 2 : 1;
 #define XNOR_TILE(ID, FW, PW, WF, WP) \
-    case ID: return launch_cfg<FMT, FW, PW, WF, WP>(xbits, wimg, K, alpha, out, dot_out, g, stream)
+    case ID: return launch_cfg<FMT, FW, PW, WF, WP>(xbits, wimg, K, A, alpha, out, dot_out, g, stream)
     switch (tile) {
         XNOR_TILE(1, 2, 2, 2, 2);   // 128 filters x 128 pixels
         XNOR_TILE(2, 2, 2, 1, 4);   //  64 x 256
@@ -479,14 +513,14 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
 #undef XNOR_TILE
 }
 
-xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, const float *K,
+xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
                              const float *alpha, float *out, int32_t *dot_out,
                              const ConvGeom &g, hipStream_t stream)
 {
     const uint8_t *img = static_cast<const uint8_t *>(wmfma);
-    if (fmt == 0) return launch_fmt<0>(xbits, img, K, alpha, out, dot_out, g, stream);
+    if (fmt == 0) return launch_fmt<0>(xbits, img, K, A, alpha, out, dot_out, g, stream);
     img += wimg_i8_bytes(g.k_out, g.c, g.taps);
-    return launch_fmt<1>(xbits, img, K, alpha, out, dot_out, g, stream);
+    return launch_fmt<1>(xbits, img, K, A, alpha, out, dot_out, g, stream);
 }
 
 }  // namespace xnor

@@ -12,8 +12,8 @@ namespace xnor {
 template <int F, int CH>   // F filters per thread, CH channel words per inner chunk (divides cw)
 __global__ __launch_bounds__(256) void conv_popcount_kernel(
     const uint32_t *__restrict__ xbits, const uint32_t *__restrict__ wbits,
-    const float *__restrict__ K, const float *__restrict__ alpha, float *__restrict__ out,
-    int32_t *__restrict__ dot_out, ConvGeom g)
+    const float *__restrict__ K, const float *__restrict__ A, const float *__restrict__ alpha,
+    float *__restrict__ out, int32_t *__restrict__ dot_out, ConvGeom g)
 {
     const uint32_t m = blockIdx.x * 256u + threadIdx.x;
     const bool live = m < (uint32_t)g.m_total;
@@ -54,7 +54,7 @@ __global__ __launch_bounds__(256) void conv_popcount_kernel(
     }
     if (!live) return;
     const int n_valid = g.c * valid_taps;
-    const float Km = K[m];
+    const float Km = K ? K[m] : box_K(A, g, m);
     const size_t plane = (size_t)g.ho * g.wo;
 #pragma unroll
     for (int f = 0; f < F; ++f) {
@@ -69,13 +69,13 @@ __global__ __launch_bounds__(256) void conv_popcount_kernel(
 }
 
 template <int F>
-static xnor_status launch_f(const uint32_t *xbits, const uint32_t *wbits, const float *K,
+static xnor_status launch_f(const uint32_t *xbits, const uint32_t *wbits, const float *K, const float *A,
                             const float *alpha, float *out, int32_t *dot_out, const ConvGeom &g,
                             hipStream_t stream)
 {
     dim3 grid((unsigned)((g.m_total + 255) / 256), (unsigned)((g.k_out + F - 1) / F)), block(256);
     if (grid.y > 65535u) return XNOR_ERR_UNSUPPORTED;
-#define XNOR_GO(CH) conv_popcount_kernel<F, CH><<<grid, block, 0, stream>>>(xbits, wbits, K, alpha, out, dot_out, g)
+#define XNOR_GO(CH) conv_popcount_kernel<F, CH><<<grid, block, 0, stream>>>(xbits, wbits, K, A, alpha, out, dot_out, g)
     if (g.cw % 8 == 0) XNOR_GO(8);
     else if (g.cw % 4 == 0) XNOR_GO(4);
     else if (g.cw % 3 == 0) XNOR_GO(3);
@@ -85,11 +85,11 @@ static xnor_status launch_f(const uint32_t *xbits, const uint32_t *wbits, const 
     return hip_status(hipGetLastError());
 }
 
-xnor_status launch_conv_popcount(const uint32_t *xbits, const uint32_t *wbits, const float *K,
+xnor_status launch_conv_popcount(const uint32_t *xbits, const uint32_t *wbits, const float *K, const float *A,
                                  const float *alpha, float *out, int32_t *dot_out,
                                  const ConvGeom &g, hipStream_t stream)
 {
-    return launch_f<32>(xbits, wbits, K, alpha, out, dot_out, g, stream);
+    return launch_f<32>(xbits, wbits, K, A, alpha, out, dot_out, g, stream);
 }
 
 }  // namespace xnor

@@ -6,19 +6,19 @@
 
 namespace xnor {
 
-// Exact unsigned division by a run-time constant: q = floor(x / d) for x*d < 2^32.
+// Exact unsigned division by a run-time constant: q = floor(x / d) for x*d < 2^32, branch-free:
+// q = mulhi(x, magic) + (x & pass) with magic = floor(2^32 / d) + 1, pass = 0 for d > 1 and
+// magic = 0, pass = ~0 for d == 1.
 struct FastDiv {
-    uint32_t magic;  // floor(2^32 / d) + 1, unused when d == 1
-    uint32_t d;
+    uint32_t magic;
+    uint32_t pass;
     __host__ static FastDiv make(uint32_t d) {
         FastDiv f;
-        f.d = d;
         f.magic = (d <= 1) ? 0u : (uint32_t)((0x100000000ull / d) + 1ull);
+        f.pass = (d <= 1) ? 0xFFFFFFFFu : 0u;
         return f;
     }
-    __device__ __forceinline__ uint32_t div(uint32_t x) const {
-        return d == 1 ? x : __umulhi(x, magic);
-    }
+    __device__ __forceinline__ uint32_t div(uint32_t x) const { return __umulhi(x, magic) + (x & pass); }
 };
 
 // Geometry handed to the convolution kernels (derived from xnor_conv_desc on the host).
@@ -33,6 +33,41 @@ struct ConvGeom {
     FastDiv div_wo, div_howo, div_kw;
 };
 
+// K of output pixel m (flattened image, row, column): the in-bounds taps of A summed in row-major
+// order, divided by kh*kw (sec. 3.2).  Shared by the stand-alone box filter and by the convolution
+// kernels when they derive K from A themselves, so both give identical bits.
+__device__ __forceinline__ float box_K(const float *__restrict__ A, const ConvGeom &g, uint32_t m)
+{
+    const uint32_t img = g.div_howo.div(m);
+    const uint32_t rem = m - img * (uint32_t)(g.ho * g.wo);
+    const uint32_t oy = g.div_wo.div(rem);
+    const uint32_t ox = rem - oy * (uint32_t)g.wo;
+    const float *Ai = A + (size_t)img * g.h * g.w;
+    // Taps are walked in row-major order, four columns at a time with their loads issued
+    // together.  An out-of-range tap loads a clamped address and adds +0.0f, which leaves the
+    // sum (>= +0) bit for bit as if it were skipped.
+    const int iy0 = (int)oy * g.sh - g.ph, ix0 = (int)ox * g.sw - g.pw;
+    float s = 0.0f;
+    for (int dy = 0; dy < g.kh; ++dy) {
+        const int iy = iy0 + dy;
+        const bool oky = (uint32_t)iy < (uint32_t)g.h;
+        const float *row = Ai + min(max(iy, 0), g.h - 1) * g.w;
+        for (int dx0 = 0; dx0 < g.kw; dx0 += 4) {
+            float a[4];
+            bool ok[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int ix = ix0 + dx0 + u;
+                ok[u] = oky && dx0 + u < g.kw && (uint32_t)ix < (uint32_t)g.w;
+                a[u] = row[min(max(ix, 0), g.w - 1)];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) s += ok[u] ? a[u] : 0.0f;
+        }
+    }
+    return s / (float)(g.kh * g.kw);
+}
+
 inline xnor_status hip_status(hipError_t e) { return e == hipSuccess ? XNOR_OK : XNOR_ERR_HIP; }
 
 // kernels' host launchers (each returns an xnor_status, enqueues on `stream`, never synchronises)
@@ -41,11 +76,12 @@ xnor_status launch_binactiv(const float *x, const float *bn_scale, const float *
 xnor_status launch_boxfilter(const float *A, float *K, const ConvGeom &g, hipStream_t stream);
 xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
                                 int k_out, int c, int taps, hipStream_t stream);
-xnor_status launch_conv_popcount(const uint32_t *xbits, const uint32_t *wbits, const float *K,
+// K may be NULL in the convolution launchers: the kernels then compute it from A on the fly.
+xnor_status launch_conv_popcount(const uint32_t *xbits, const uint32_t *wbits, const float *K, const float *A,
                                  const float *alpha, float *out, int32_t *dot_out,
                                  const ConvGeom &g, hipStream_t stream);
 // fmt 0: int8 operands, fmt 1: 4-bit float operands (both images live in the wmfma buffer)
-xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, const float *K,
+xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
                              const float *alpha, float *out, int32_t *dot_out,
                              const ConvGeom &g, hipStream_t stream);
 void set_mfma_tuning(int tile, int lds_budget);

@@ -62,7 +62,7 @@ def lib():
         L.xnor_binactiv.restype = ip
         L.xnor_pack_weights.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp]
         L.xnor_pack_weights.restype = ip
-        L.xnor_conv2d.argtypes = [vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(ConvDesc), ip, vp]
+        L.xnor_conv2d.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(ConvDesc), ip, vp]
         L.xnor_conv2d.restype = ip
         L.xnor_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, vp]
         L.xnor_linear.restype = ip
@@ -149,10 +149,10 @@ def xnor_pack_weights(w, wbits, alpha, wmfma, k_out, c, kh, kw, stream=None):
         _ptr(wmfma, torch.uint8), k_out, c, kh, kw, _stream(stream)))
 
 
-def xnor_conv2d(xbits, wbits, wmfma, K, alpha, out, dot_out, desc, algo=XNOR_ALGO_AUTO, stream=None):
+def xnor_conv2d(xbits, wbits, wmfma, K, A, alpha, out, dot_out, desc, algo=XNOR_ALGO_AUTO, stream=None):
     _check("xnor_conv2d", lib().xnor_conv2d(
         _ptr(xbits, torch.int32), _ptr(wbits, torch.int32), _ptr(wmfma, torch.uint8),
-        _ptr(K, torch.float32), _ptr(alpha, torch.float32), _ptr(out, torch.float32),
+        _ptr(K, torch.float32), _ptr(A, torch.float32), _ptr(alpha, torch.float32), _ptr(out, torch.float32),
         _ptr(dot_out, torch.int32), ctypes.byref(desc), int(algo), _stream(stream)))
 
 
@@ -196,8 +196,9 @@ class ConvBuffers:
 
 
 def binary_conv_block(x, bn_scale, bn_shift, weights, bufs, algo=XNOR_ALGO_AUTO, stream=None):
-    """BatchNorm -> BinActiv -> BinConv on preallocated buffers: two library calls."""
-    xnor_binactiv(x, bn_scale, bn_shift, bufs.xbits, bufs.A, bufs.K, bufs.desc, stream)
-    xnor_conv2d(bufs.xbits, weights.wbits, weights.wmfma, bufs.K, weights.alpha, bufs.out, bufs.dot,
+    """BatchNorm -> BinActiv -> BinConv on preallocated buffers: two library calls, two kernels
+    (the convolution derives K from A in its epilogue)."""
+    xnor_binactiv(x, bn_scale, bn_shift, bufs.xbits, bufs.A, None, bufs.desc, stream)
+    xnor_conv2d(bufs.xbits, weights.wbits, weights.wmfma, None, bufs.A, weights.alpha, bufs.out, bufs.dot,
                 bufs.desc, algo, stream)
     return bufs.out

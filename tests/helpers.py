@@ -41,12 +41,16 @@ def gpu_conv_block(x, w, stride, pad, bn_scale=None, bn_shift=None, algo="auto",
     bufs.out.fill_(float("nan"))
     bufs.dot.fill_(-(2 ** 31))
     if fused:
-        xnor.xnor_binactiv(xd, sc, sf, bufs.xbits, bufs.A, bufs.K, desc)
+        # production sequence: one BinActiv pass, the convolution derives K from A in its epilogue
+        xnor.xnor_binactiv(xd, sc, sf, bufs.xbits, bufs.A, None, desc)
+        xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha, bufs.out, bufs.dot, desc,
+                         xnor.ALGOS[algo])
+        xnor.xnor_compute_K(xd, sc, sf, torch.empty_like(bufs.A), bufs.K, desc)    # K alone, for checking
     else:
         xnor.xnor_binarize_pack(xd, sc, sf, bufs.xbits, n, c, h, wd)
         xnor.xnor_compute_K(xd, sc, sf, bufs.A, bufs.K, desc)
-    xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, bufs.out, bufs.dot, desc,
-                     xnor.ALGOS[algo])
+        xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, None, pw.alpha, bufs.out, bufs.dot, desc,
+                         xnor.ALGOS[algo])
     torch.cuda.synchronize()
     return {
         "xbits": bufs.xbits.cpu().numpy().view(np.uint32),

@@ -53,16 +53,17 @@ def test_invalid_arguments_return_error_codes_without_launching():
     assert L.xnor_compute_K(fake, None, None, fake, fake, None, None) == ERR_NULL
     assert L.xnor_pack_weights(fake, fake, None, None, 1, 1, 1, 1, None) == ERR_NULL
     assert L.xnor_pack_weights(fake, fake, fake, None, 1, -1, 1, 1, None) == ERR_SHAPE
-    assert L.xnor_conv2d(fake, fake, None, fake, fake, None, None, ctypes.byref(good), 0, None) == ERR_NULL
-    assert L.xnor_conv2d(fake, fake, None, fake, fake, fake, None, ctypes.byref(good), 2, None) == ERR_NULL  # mfma needs wmfma
-    assert L.xnor_conv2d(fake, fake, None, fake, fake, fake, None, ctypes.byref(good), 99, None) == ERR_UNSUP
-    assert L.xnor_conv2d(fake, fake, None, fake, fake, odd, None, ctypes.byref(good), 1, None) == ERR_ALIGN
+    assert L.xnor_conv2d(fake, fake, None, fake, None, fake, None, None, ctypes.byref(good), 0, None) == ERR_NULL
+    assert L.xnor_conv2d(fake, fake, None, None, None, fake, fake, None, ctypes.byref(good), 1, None) == ERR_NULL  # K or A
+    assert L.xnor_conv2d(fake, fake, None, fake, None, fake, fake, None, ctypes.byref(good), 2, None) == ERR_NULL  # mfma needs wmfma
+    assert L.xnor_conv2d(fake, fake, None, fake, None, fake, fake, None, ctypes.byref(good), 99, None) == ERR_UNSUP
+    assert L.xnor_conv2d(fake, fake, None, None, fake, fake, odd, None, ctypes.byref(good), 1, None) == ERR_ALIGN
     big_filter = xnor.make_desc(1, 8, 3, 3, 4, 5, 5, 1, 0)
-    assert L.xnor_conv2d(fake, fake, None, fake, fake, fake, None, ctypes.byref(big_filter), 1, None) == ERR_SHAPE
+    assert L.xnor_conv2d(fake, fake, None, fake, None, fake, fake, None, ctypes.byref(big_filter), 1, None) == ERR_SHAPE
     zero_stride = xnor.make_desc(1, 8, 3, 3, 4, 3, 3, 0, 0)
     assert L.xnor_binactiv(fake, None, None, fake, fake, fake, ctypes.byref(zero_stride), None) == ERR_SHAPE
     assert L.xnor_linear(fake, fake, None, fake, fake, fake, None, 0, 8, 8, 1, None) == ERR_SHAPE
-    assert L.xnor_conv2d(fake, fake, None, fake, fake, fake, None, ctypes.byref(good), 3, None) == ERR_NULL
+    assert L.xnor_conv2d(fake, fake, None, fake, None, fake, fake, None, ctypes.byref(good), 3, None) == ERR_NULL
     assert L.xnor_set_tuning(99, 0) == ERR_UNSUP
     assert L.xnor_set_tuning(0, 0) == 0
     with pytest.raises(xnor.XnorError):
