@@ -17,6 +17,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# command (scaled by a 256 MiB copy: reads x2.00, writes x1.00), see profiles/; None where not measured.
+MEASURED_TRAFFIC = {("alexnet_conv2", "mfma_f4"): 2901.1 * 1024 * 2.0 + 50796.4 * 1024}
+
 PEAKS = {  # MI355X published dense peaks
     "mfma_f4": {"bound": "mfma", "peak": 10100.0, "unit": "TFLOP/s"},     # fp4 10.1 PFLOP/s, 2 flops per MAC
     "mfma_i8": {"bound": "mfma", "peak": 5000.0, "unit": "TOP/s"},        # int8 5.0 POP/s, 2 ops per MAC
@@ -24,6 +28,16 @@ PEAKS = {  # MI355X published dense peaks
     # 256 CUs x 64 lanes x 2.4 GHz x 16 MAC per lane-instruction
     "popcount": {"bound": "alu", "peak": 256 * 64 * 2.4e9 * 16 / 1e12, "unit": "Tbinop/s"},
 }
+
+
+def algo_bytes(layer):
+    """Bytes one xnor_conv2d launch must move: packed activations, matrix-core weight image (fp4),
+    A, alpha and the float output."""
+    cw = (layer.c + 31) // 32
+    taps = layer.kh * layer.kw
+    wimg = ((layer.k_out + 31) // 32) * ((taps * cw + 1) // 2) * 1024
+    return (layer.n * layer.h * layer.w * (cw * 4 + 4) + wimg + layer.k_out * 4 +
+            layer.n * layer.k_out * layer.h_out * layer.w_out * 4)
 
 
 def cpu_baseline(layers, inputs):
@@ -50,6 +64,9 @@ def main():
     ap.add_argument("--algo", default="fastest", choices=["fastest", "popcount", "mfma_i8", "mfma_f4"],
                     help="inner loop of the binary convolution; 'fastest' times all three and keeps the winner")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy, so a rocprofv3 --pmc run of this command holds "
+                         "a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over the batch with no "
@@ -112,6 +129,13 @@ def main():
             if events is not None:
                 events[i][1].record()
 
+    if args.copy_calibration:
+        src = torch.empty(256 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -143,7 +167,9 @@ def main():
                    "conv_ms": conv_ms, "pack_weights_ms_once": pack_ms,
                    "conv_only_Gbinop_s": [l.bit_macs / (t * 1e-3) / 1e9 for l, t in zip(layers, conv_ms)]},
         "roofline": {"bound": pk["bound"], "achieved": achieved, "peak": pk["peak"], "unit": pk["unit"],
-                     "frac": achieved / pk["peak"], "traffic": None, "kernel": f"xnor_conv2d[{layers[dom].name}]"},
+                     "frac": achieved / pk["peak"],
+                     "traffic": MEASURED_TRAFFIC.get((args.workload, used)),
+                     "algorithmic_bytes": algo_bytes(layers[dom]), "kernel": f"xnor_conv2d[{layers[dom].name}]"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, inputs)
