@@ -79,7 +79,7 @@ size_t xnor_wmfma_bytes(int k_out, int c, int kh, int kw);
 
 /*
  * Benchmarking hook (host state, not thread-safe): mfma_tile 1..9 forces one workgroup tiling of
- * the matrix-core kernels, 0 restores the library's per-shape choice; lds_budget_bytes > 0 caps the
+ * the matrix-core kernels, 10 the persistent role-split kernel, 0 restores the library's per-shape choice; lds_budget_bytes > 0 caps the
  * LDS image of a workgroup (0 keeps the current cap).  Results never depend on it.
  */
 int xnor_set_tuning(int mfma_tile, int lds_budget_bytes);

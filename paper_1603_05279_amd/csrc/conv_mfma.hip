@@ -16,100 +16,9 @@
 // 32-filter operand, prefetched several K-steps ahead in registers.  Filters are the M operand
 // and pixels the N operand, so each lane of the result holds one pixel column: stores along a
 // filter plane are contiguous across lanes.
-#include "xnor_internal.h"
+#include "mfma_common.h"
 
 namespace xnor {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-typedef unsigned v4u __attribute__((ext_vector_type(4)));
-
-struct MfmaPlan {
-    int cc_words;     // channel words widened per chunk (divides cw)
-    int ps;           // bytes per pixel in LDS (an odd multiple of 16: conflict-free 16-byte reads)
-    int max_rows;     // padded input rows a pixel tile can touch
-    int region_bytes; // max_rows * wp * ps
-    int nsteps;       // K-steps per chunk
-    int tap_jump;     // weight records skipped when a chunk moves to the next tap
-    FastDiv div_wp, div_hp, div_ccw, div_cw;
-};
-
-template <int FMT> struct Enc;
-
-template <> struct Enc<0> {                    // int8
-    static constexpr int BPS = 1;              // channel words per K-step
-    static constexpr int BPB = 32;             // LDS bytes per pixel per channel word
-    typedef v16i acc_t;
-    static __device__ __forceinline__ acc_t mfma(v4i w, v4i x, acc_t c) {
-        return __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, c, 0, 0, 0);
-    }
-    static __device__ __forceinline__ int to_int(acc_t a, int v) { return a[v]; }
-    // 4 sign bits -> 4 int8: bit 1 -> 0x01, bit 0 -> 0xFF
-    static __device__ __forceinline__ uint32_t widen4(uint32_t nibble) {
-        const uint32_t t = __umul24(nibble, 0x00204081u) & 0x01010101u;     // bit i -> byte i
-        return __builtin_amdgcn_perm(0x000001FFu, 0x000001FFu, t);           // byte = {0xFF, 0x01}[t]
-    }
-    // one channel word -> 32 bytes at dst; channels >= nch are 0
-    static __device__ __forceinline__ void widen_word(uint8_t *dst, uint32_t bits, bool ok, int nch) {
-        uint4 lo = make_uint4(0, 0, 0, 0), hi = make_uint4(0, 0, 0, 0);
-        if (ok) {
-            lo.x = widen4(bits & 15u);         lo.y = widen4((bits >> 4) & 15u);
-            lo.z = widen4((bits >> 8) & 15u);  lo.w = widen4((bits >> 12) & 15u);
-            hi.x = widen4((bits >> 16) & 15u); hi.y = widen4((bits >> 20) & 15u);
-            hi.z = widen4((bits >> 24) & 15u); hi.w = widen4(bits >> 28);
-            if (nch < 32) {
-                uint32_t *d = reinterpret_cast<uint32_t *>(&lo);
-                uint32_t *e = reinterpret_cast<uint32_t *>(&hi);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int r0 = nch - 4 * q, r1 = nch - 16 - 4 * q;
-                    d[q] &= r0 >= 4 ? 0xFFFFFFFFu : (r0 <= 0 ? 0u : (1u << (8 * r0)) - 1u);
-                    e[q] &= r1 >= 4 ? 0xFFFFFFFFu : (r1 <= 0 ? 0u : (1u << (8 * r1)) - 1u);
-                }
-            }
-        }
-        *reinterpret_cast<uint4 *>(dst) = lo;
-        *reinterpret_cast<uint4 *>(dst + 16) = hi;
-    }
-};
-
-template <> struct Enc<1> {                    // 4-bit float E2M1
-    static constexpr int BPS = 2;
-    static constexpr int BPB = 16;
-    typedef v16f acc_t;
-    static __device__ __forceinline__ acc_t mfma(v4i w, v4i x, acc_t c) {
-        const v8i w8 = {w[0], w[1], w[2], w[3], 0, 0, 0, 0};
-        const v8i x8 = {x[0], x[1], x[2], x[3], 0, 0, 0, 0};
-        return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(w8, x8, c, 4, 4, 0, 127, 0, 127);
-    }
-    static __device__ __forceinline__ int to_int(acc_t a, int v) { return (int)a[v]; }
-    // 8 sign bits -> 8 nibbles: bit 1 -> 0x2 (+1.0), bit 0 -> 0xA (-1.0)
-    static __device__ __forceinline__ uint32_t widen8(uint32_t byte) {
-        uint32_t x = byte;                                   // bit i -> bit 4i by three shift-or steps
-        x = (x | (x << 12)) & 0x000F000Fu;
-        x = (x | (x << 6)) & 0x03030303u;
-        x = (x | (x << 3)) & 0x11111111u;
-        return 0xAAAAAAAAu ^ (x << 3);
-    }
-    static __device__ __forceinline__ void widen_word(uint8_t *dst, uint32_t bits, bool ok, int nch) {
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (ok) {
-            v.x = widen8(bits & 255u);         v.y = widen8((bits >> 8) & 255u);
-            v.z = widen8((bits >> 16) & 255u); v.w = widen8(bits >> 24);
-            if (nch < 32) {
-                uint32_t *d = reinterpret_cast<uint32_t *>(&v);
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int r0 = nch - 8 * q;
-                    d[q] &= r0 >= 8 ? 0xFFFFFFFFu : (r0 <= 0 ? 0u : (1u << (4 * r0)) - 1u);
-                }
-            }
-        }
-        *reinterpret_cast<uint4 *>(dst) = v;
-    }
-};
 
 #ifdef XNOR_TIMELINE
 // Development build only: per-workgroup phase timestamps (100 MHz wall clock) into a caller buffer.
@@ -281,68 +190,8 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
 
         // ---- software-pipelined K loop over this chunk's steps --------------------------------
         // record of step s: rec0 + s + (s / steps_per_tap) * tap_jump
-        // weight records are consumed in order: +1 per step, +tap_jump more when a chunk that
-        // holds only part of the channels moves to the next tap; the stream parks on the last
-        // record so the prefetches past the end stay in bounds
-        int w_rec = wbase / E::BPS, w_cnt = 0, w_left = nsteps;
-        auto load_w = [&](v4i (&dst)[FW]) {
-            const int live = w_left > 0 ? 1 : 0;   // past the end: the all-zero record
-#pragma unroll
-            for (int i = 0; i < FW; ++i) {
-                const int rec = live ? wrec0[i] + w_rec : zero_rec;
-                const v4u r = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, rec * 1024, 0);
-                dst[i] = v4i{(int)r[0], (int)r[1], (int)r[2], (int)r[3]};
-            }
-            // branch-free bookkeeping (scalar selects), so the loop body stays one basic block
-            w_left -= live;
-            w_cnt += live;
-            const int wrap = w_cnt == steps_per_tap ? 1 : 0;
-            w_cnt = wrap ? 0 : w_cnt;
-            w_rec += live + (wrap ? pl.tap_jump : 0);
-        };
-        auto load_t = [&](int s) -> int { return xoff_tab[min(s, nsteps - 1) * E::BPS + tab_lane]; };
-        auto load_x = [&](v4i (&dst)[PW], int toff) {
-#pragma unroll
-            for (int j = 0; j < PW; ++j) dst[j] = *reinterpret_cast<const v4i *>(lds + pbase[j] + toff);
-        };
-        auto fma_all = [&](const v4i (&w)[FW], const v4i (&x)[PW]) {
-#pragma unroll
-            for (int j = 0; j < PW; ++j)
-#pragma unroll
-                for (int i = 0; i < FW; ++i) acc[i][j] = E::mfma(w[i], x[j], acc[i][j]);
-        };
-
-        v4i w0[FW], w1[FW], w2[FW], w3[FW], x0[PW], x1[PW];
-        int t1, t2;
-        load_w(w0); load_w(w1); load_w(w2);
-        load_x(x0, load_t(0));
-        t1 = load_t(1);
-        // The step count is rounded up to a multiple of 4; the extra steps multiply by the zero
-        // record, so the unrolled body needs no branches and the prefetch depth never drops.
-        // The scheduling barriers pin the order written here (next operands requested, then the
-        // current step's matrix instructions), which the compiler otherwise regroups into one
-        // burst of loads followed by one burst of MFMAs with the LDS latency exposed.
-#define XNOR_STEP(WL, TN, TS, XN, TC, WC, XC)                         \
-        load_w(WL); TN = load_t(TS); load_x(XN, TC);                  \
-        fma_all(WC, XC);                                              \
-        /* interleave: one LDS read behind each of the first PW+1 MFMAs, then the FW weight loads */ \
-        _Pragma("unroll") for (int q = 0; q < PW + 1; ++q) {          \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);        \
-        }                                                             \
-        _Pragma("unroll") for (int q = 0; q < FW; ++q) {              \
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);        \
-            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);        \
-        }                                                             \
-        __builtin_amdgcn_sched_group_barrier(0x008, FW * PW - PW - 1 - FW, 0); \
-        __builtin_amdgcn_sched_barrier(0);
-        for (int s = 0; s < nsteps; s += 4) {
-            XNOR_STEP(w3, t2, s + 2, x1, t1, w0, x0)
-            XNOR_STEP(w0, t1, s + 3, x0, t2, w1, x1)
-            XNOR_STEP(w1, t2, s + 4, x1, t1, w2, x0)
-            XNOR_STEP(w2, t1, s + 5, x0, t2, w3, x1)
-        }
-#undef XNOR_STEP
+        mfma_kloop<E, FW, PW, 3, 1>(acc, lds, pbase, xoff_tab, tab_lane, wrsrc, wlane, wrec0, zero_rec,
+                              wbase / E::BPS, nsteps, steps_per_tap, pl.tap_jump);
     }
 
     XNOR_TL(3);
@@ -495,7 +344,7 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
                               hipStream_t stream)
 {
     int tile = g_tile_override;
-    if (tile == 0) tile = (g.k_out <= 64) ? 2 : 1;
+    if (tile == 0 || tile == 10) tile = (g.k_out <= 64) ? 2 : 1;
 #define XNOR_TILE(ID, FW, PW, WF, WP) \
     case ID: return launch_cfg<FMT, FW, PW, WF, WP>(xbits, wimg, K, A, alpha, out, dot_out, g, stream)
     switch (tile) {
@@ -517,6 +366,10 @@ xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, 
                              const float *alpha, float *out, int32_t *dot_out,
                              const ConvGeom &g, hipStream_t stream)
 {
+    if (g_tile_override == 10) {      // persistent kernel where its LDS plan fits, tiled kernel otherwise
+        const xnor_status s = launch_conv_mfma_pipe(fmt, xbits, wmfma, K, A, alpha, out, dot_out, g, stream);
+        if (s != XNOR_ERR_UNSUPPORTED) return s;
+    }
     const uint8_t *img = static_cast<const uint8_t *>(wmfma);
     if (fmt == 0) return launch_fmt<0>(xbits, img, K, A, alpha, out, dot_out, g, stream);
     img += wimg_i8_bytes(g.k_out, g.c, g.taps);

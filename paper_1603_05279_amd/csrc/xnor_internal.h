@@ -85,6 +85,10 @@ xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, 
                              const float *alpha, float *out, int32_t *dot_out,
                              const ConvGeom &g, hipStream_t stream);
 void set_mfma_tuning(int tile, int lds_budget);
+// persistent, role-split form of the same kernel (conv_mfma_pipe.hip)
+xnor_status launch_conv_mfma_pipe(int fmt, const uint32_t *xbits, const void *wmfma, const float *K,
+                                  const float *A, const float *alpha, float *out, int32_t *dot_out,
+                                  const ConvGeom &g, hipStream_t stream);
 
 // Sizes of the two matrix-core weight images (int8 first, 4-bit float second), 1 KiB records;
 // each image ends with one all-zero record that padded K-steps multiply by.

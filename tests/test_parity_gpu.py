@@ -10,7 +10,7 @@ from tests.helpers import RTOL, ATOL, assert_block_matches_oracle, gpu_conv_bloc
 
 pytestmark = pytest.mark.gpu
 
-ALGOS = ["popcount", "mfma_i8", "mfma_f4"]
+ALGOS = ["popcount", "mfma_i8", "mfma_f4", "mfma_i8_pipe", "mfma_f4_pipe"]
 
 # n, c, h, w, k_out, kh, kw, stride, pad — several tiles, ragged tails, odd channel counts
 SMALL = [
@@ -88,8 +88,12 @@ def test_linear_matches_oracle(algo):
     xnor.xnor_binactiv(xd.reshape(b, f, 1, 1), None, None, bufs.xbits, bufs.A, bufs.K, desc)
     out = torch.full((b, o), float("nan"), device="cuda")
     dot = torch.zeros((b, o), dtype=torch.int32, device="cuda")
-    xnor.xnor_linear(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, out, dot, b, f, o, xnor.ALGOS[algo])
+    pipe = algo.endswith("_pipe")
+    xnor.set_tuning(10 if pipe else 0)
+    xnor.xnor_linear(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, out, dot, b, f, o,
+                     xnor.ALGOS[algo[:-5] if pipe else algo])
     torch.cuda.synchronize()
+    xnor.set_tuning(0)
     assert np.array_equal(dot.cpu().numpy(), r["dot"])
     np.testing.assert_allclose(bufs.K.cpu().numpy().reshape(b), r["K"], rtol=RTOL, atol=ATOL)
     np.testing.assert_allclose(out.cpu().numpy(), r["out"], rtol=RTOL, atol=ATOL)
