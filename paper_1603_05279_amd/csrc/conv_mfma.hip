@@ -344,7 +344,22 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
                               hipStream_t stream)
 {
     int tile = g_tile_override;
-    if (tile == 0 || tile == 10) tile = (g.k_out <= 64) ? 2 : 1;
+    if (tile == 0 || tile == 10) {
+        // 128 x 128 (64 x 256 for few filters) keeps 3-4 workgroups per CU in different phases and
+        // measured best on every convolution layer; problems with few output tiles (fully
+        // connected layers: few "pixels", long K) take the largest smaller tile that still gives
+        // every CU a workgroup
+        tile = (g.k_out <= 64) ? 2 : 1;
+        auto wgs = [&](int ft, int pt) {
+            return (long long)((g.m_total + pt - 1) / pt) * ((g.k_out + ft - 1) / ft);
+        };
+        const int cus = 256;
+        if (wgs(tile == 1 ? 128 : 64, tile == 1 ? 128 : 256) < cus) {
+            if (wgs(64, 128) >= cus) tile = 11;
+            else if (wgs(128, 64) >= cus) tile = 13;
+            else tile = 14;       // 128 x 32 (measured ahead of 64 x 64 at equal workgroup count)
+        }
+    }
 #define XNOR_TILE(ID, FW, PW, WF, WP) \
     case ID: return launch_cfg<FMT, FW, PW, WF, WP>(xbits, wimg, K, A, alpha, out, dot_out, g, stream)
     switch (tile) {
@@ -357,6 +372,10 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
         XNOR_TILE(7, 4, 2, 2, 2);   // 256 x 128
         XNOR_TILE(8, 2, 4, 1, 4);   //  64 x 512
         XNOR_TILE(9, 4, 4, 2, 2);   // 256 x 256
+        XNOR_TILE(11, 1, 2, 2, 2);  //  64 x 128
+        XNOR_TILE(12, 1, 1, 2, 2);  //  64 x  64
+        XNOR_TILE(13, 1, 2, 4, 1);  // 128 x  64
+        XNOR_TILE(14, 1, 1, 4, 1);  // 128 x  32
     default: return XNOR_ERR_UNSUPPORTED;
     }
 #undef XNOR_TILE
