@@ -78,8 +78,8 @@ const char *xnor_status_string(int status);
 size_t xnor_wmfma_bytes(int k_out, int c, int kh, int kw);
 
 /*
- * Benchmarking hook (host state, not thread-safe): mfma_tile 1..9 forces one workgroup tiling of
- * the matrix-core kernels, 10 the persistent role-split kernel, 0 restores the library's per-shape choice; lds_budget_bytes > 0 caps the
+ * Benchmarking hook (host state, not thread-safe): mfma_tile 1..9 and 11..14 force one workgroup tiling
+ * of the matrix-core kernels, 10 the persistent role-split kernel, 0 restores the library's per-shape choice; lds_budget_bytes > 0 caps the
  * LDS image of a workgroup (0 keeps the current cap).  Results never depend on it.
  */
 int xnor_set_tuning(int mfma_tile, int lds_budget_bytes);
