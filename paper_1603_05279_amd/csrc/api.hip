@@ -77,7 +77,7 @@ size_t xnor_wmfma_bytes(int k_out, int c, int kh, int kw)
 {
     if (k_out <= 0 || c <= 0 || kh <= 0 || kw <= 0) return 0;
     if ((long long)kh * kw > 4096) return 0;
-    return wimg_i8_bytes(k_out, c, kh * kw) + wimg_f4_bytes(k_out, c, kh * kw);
+    return wimg_i8_bytes(k_out, c, kh * kw) + wimg_f4_bytes(k_out, c, kh * kw) + wimg_pop_bytes(k_out, c, kh * kw);
 }
 
 int xnor_set_tuning(int mfma_tile, int lds_budget_bytes)
@@ -151,7 +151,7 @@ int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
     hipStream_t st = (hipStream_t)hip_stream;
     switch (algo) {
     case XNOR_ALGO_POPCOUNT:
-        return launch_conv_popcount(xbits, wbits, K, A, alpha, out, dot_out, g, st);
+        return launch_conv_popcount(xbits, wbits, wmfma, K, A, alpha, out, dot_out, g, st);
     case XNOR_ALGO_MFMA_I8:
     case XNOR_ALGO_MFMA_F4:
         if (!wmfma) return XNOR_ERR_NULL;
@@ -161,7 +161,7 @@ int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
             const xnor_status s = launch_conv_mfma(1, xbits, wmfma, K, A, alpha, out, dot_out, g, st);
             if (s != XNOR_ERR_UNSUPPORTED) return s;
         }
-        return launch_conv_popcount(xbits, wbits, K, A, alpha, out, dot_out, g, st);
+        return launch_conv_popcount(xbits, wbits, wmfma, K, A, alpha, out, dot_out, g, st);
     }
     default:
         return XNOR_ERR_UNSUPPORTED;

@@ -81,6 +81,18 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
             const size_t rec = (size_t)fb * nrec + r;
             *reinterpret_cast<uint4 *>(w4 + rec * 1024 + (size_t)(row + 32 * half) * 16) = u.v;
         }
+        // scalar-path image: this filter's words, 32 filters interleaved per (tap, channel word)
+        uint32_t *wp = reinterpret_cast<uint32_t *>(w4 + wimg_f4_bytes(k_out, c, taps));
+        for (int item = tid; item < taps * cw; item += 256) {
+            const int t = item / cw, wd = item - t * cw;
+            uint32_t word = 0;
+            if (real) {
+                const int nch = min(32, c - wd * 32);
+                for (int j = 0; j < nch; ++j)
+                    word |= (wk[(size_t)(wd * 32 + j) * taps + t] >= 0.0f ? 1u : 0u) << j;
+            }
+            wp[(((size_t)fb * taps + t) * cw + wd) * 32 + row] = word;
+        }
         if (k == 0 && tid < 128) {      // the trailing all-zero record of each image
             int8_t *z = tid < 64 ? w4 - 1024 : w4 + wimg_f4_bytes(k_out, c, taps) - 1024;
             *reinterpret_cast<uint4 *>(z + (size_t)(tid & 63) * 16) = make_uint4(0, 0, 0, 0);

@@ -77,9 +77,18 @@ xnor_status launch_boxfilter(const float *A, float *K, const ConvGeom &g, hipStr
 xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
                                 int k_out, int c, int taps, hipStream_t stream);
 // K may be NULL in the convolution launchers: the kernels then compute it from A on the fly.
-xnor_status launch_conv_popcount(const uint32_t *xbits, const uint32_t *wbits, const float *K, const float *A,
+// wmfma may be NULL (then the canonical wbits order is used, at a lower rate)
+xnor_status launch_conv_popcount(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma, const float *K, const float *A,
                                  const float *alpha, float *out, int32_t *dot_out,
                                  const ConvGeom &g, hipStream_t stream);
+// Third image of the wmfma buffer (after the int8 and 4-bit images): the packed weight words in
+// scalar-path order, [filter block of 32][tap][channel word][32 filters], so that the 32 words a
+// wave needs for one (tap, channel word) are one aligned 128-byte scalar load.
+__host__ __device__ inline size_t wimg_pop_bytes(int k_out, int c, int taps)
+{
+    return (size_t)((k_out + 31) / 32) * (size_t)taps * (size_t)((c + 31) / 32) * 128u;
+}
+
 // fmt 0: int8 operands, fmt 1: 4-bit float operands (both images live in the wmfma buffer)
 xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
                              const float *alpha, float *out, int32_t *dot_out,

@@ -29,9 +29,9 @@ def test_small_queries():
     assert [xnor.words_per_pixel(c) for c in (1, 31, 32, 33, 96, 9216)] == [1, 1, 1, 2, 3, 288]
     assert xnor.words_per_pixel(0) == 0
     # int8 image: one KiB per (32 filters, tap, word); 4-bit image: one KiB per two (tap, word) blocks;
-    # each image ends with one all-zero KiB
-    assert xnor.wmfma_bytes(256, 96, 5, 5) == (8 * 25 * 3 + 1) * 1024 + (8 * 38 + 1) * 1024
-    assert xnor.wmfma_bytes(33, 1, 1, 1) == 3 * 1024 + 3 * 1024
+    # each image ends with one all-zero KiB; then the scalar-path word image, 128 bytes per (block, tap, word)
+    assert xnor.wmfma_bytes(256, 96, 5, 5) == (8 * 25 * 3 + 1) * 1024 + (8 * 38 + 1) * 1024 + 8 * 25 * 3 * 128
+    assert xnor.wmfma_bytes(33, 1, 1, 1) == 3 * 1024 + 3 * 1024 + 2 * 128
     assert xnor.wmfma_bytes(0, 1, 1, 1) == 0
     assert xnor.output_hw(xnor.make_desc(64, 96, 27, 27, 256, 5, 5, 1, 2)) == (27, 27)
     assert xnor.output_hw(xnor.make_desc(1, 5, 7, 6, 2, 2, 2, 2, 1)) == (4, 4)

@@ -66,6 +66,22 @@ def test_batchnorm_block_matches_oracle_and_identity_fold():
         assert np.array_equal(a[key], b[key]), key
 
 
+def test_popcount_without_prepared_weight_image():
+    """wmfma = NULL: the vector-ALU loop falls back to the canonical wbits order."""
+    x, wt = wl.random_conv_case(11, 2, 96, 9, 11, 40, 3, 3, with_zeros=True)
+    r = xo.binary_conv2d(x, wt, (1, 1), (1, 1))
+    desc = xnor.make_desc(2, 96, 9, 11, 40, 3, 3, 1, 1)
+    pw = xnor.PackedWeights(to_dev(wt), with_mfma=False)
+    bufs = xnor.ConvBuffers(desc, with_dot=True)
+    xnor.xnor_binactiv(to_dev(x), None, None, bufs.xbits, bufs.A, bufs.K, desc)
+    for algo in ("popcount", "auto"):
+        bufs.dot.zero_()
+        xnor.xnor_conv2d(bufs.xbits, pw.wbits, None, bufs.K, None, pw.alpha, bufs.out, bufs.dot, desc, xnor.ALGOS[algo])
+        torch.cuda.synchronize()
+        assert np.array_equal(bufs.dot.cpu().numpy(), r["dot"]), algo
+        np.testing.assert_allclose(bufs.out.cpu().numpy(), r["out"], rtol=RTOL, atol=ATOL)
+
+
 def test_runs_are_deterministic():
     x, wt = wl.random_conv_case(5, 3, 64, 10, 10, 64, 3, 3)
     a = gpu_conv_block(x, wt, (1, 1), (1, 1), algo="mfma_i8")
