@@ -250,21 +250,6 @@ extern "C" int xnor_debug_timeline(long long *buf)
 }
 #endif
 
-// Padded input rows touched by the worst pixel tile of PT consecutive output pixels.
-static int worst_rows(const ConvGeom &g, int PT)
-{
-    int worst = 0;
-    const int howo = g.ho * g.wo;
-    for (long long m0 = 0; m0 < g.m_total; m0 += PT) {
-        const long long m1 = (m0 + PT < g.m_total ? m0 + PT : g.m_total) - 1;
-        const int ia = (int)(m0 / howo), ib = (int)(m1 / howo);
-        const int oa = (int)(m0 % howo) / g.wo, ob = (int)(m1 % howo) / g.wo;
-        const int rows = (ib * g.hp + ob * g.sh + g.kh - 1) - (ia * g.hp + oa * g.sh) + 1;
-        if (rows > worst) worst = rows;
-    }
-    return worst;
-}
-
 static const int LDS_LIMIT = 160 * 1024;
 
 static size_t plan_lds_bytes(const MfmaPlan &pl, int bps, int wp, int PT)
@@ -276,7 +261,7 @@ static size_t plan_lds_bytes(const MfmaPlan &pl, int bps, int wp, int PT)
 static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, MfmaPlan *pl)
 {
     const int bps = fmt == 0 ? 1 : 2, bpb = fmt == 0 ? 32 : 16;
-    const int rows = worst_rows(g, PT);
+    const int rows = worst_region_rows(g, PT, PT);
     for (int ccw = g.cw; ccw >= 1; --ccw) {
         if (g.cw % ccw) continue;
         // 4-bit operands take two channel words per step: chunks must keep word pairs together
@@ -389,6 +374,8 @@ xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, 
         const xnor_status s = launch_conv_mfma_pipe(fmt, xbits, wmfma, K, A, alpha, out, dot_out, g, stream);
         if (s != XNOR_ERR_UNSUPPORTED) return s;
     }
+    // float accumulation of the 4-bit path is exact while every sum stays below 2^24
+    if (fmt != 0 && (long long)g.c * g.taps >= (1ll << 24)) return XNOR_ERR_UNSUPPORTED;
     const uint8_t *img = static_cast<const uint8_t *>(wmfma);
     if (fmt == 0) return launch_fmt<0>(xbits, img, K, A, alpha, out, dot_out, g, stream);
     img += wimg_i8_bytes(g.k_out, g.c, g.taps);

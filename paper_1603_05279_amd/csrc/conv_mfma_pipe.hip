@@ -332,28 +332,13 @@ extern "C" int xnor_debug_timeline_pipe(long long *buf)
 }
 #endif
 
-// Padded input rows touched by the worst run of PT output pixels starting at a multiple of 32.
-static int worst_rows32(const ConvGeom &g, int PT)
-{
-    int worst = 0;
-    const int howo = g.ho * g.wo;
-    for (long long m0 = 0; m0 < g.m_total; m0 += 32) {
-        const long long m1 = (m0 + PT < g.m_total ? m0 + PT : g.m_total) - 1;
-        const int ia = (int)(m0 / howo), ib = (int)(m1 / howo);
-        const int oa = (int)(m0 % howo) / g.wo, ob = (int)(m1 % howo) / g.wo;
-        const int rows = (ib * g.hp + ob * g.sh + g.kh - 1) - (ia * g.hp + oa * g.sh) + 1;
-        if (rows > worst) worst = rows;
-    }
-    return worst;
-}
-
 static const int PIPE_LDS_LIMIT = 160 * 1024;
 
 static bool make_pipe_plan(const ConvGeom &g, int fmt, int PT, int FG, PipePlan *pl, size_t *lds_bytes)
 {
     const int bps = fmt == 0 ? 1 : 2, bpb = fmt == 0 ? 32 : 16;
     if ((long long)g.c * g.taps >= 32768) return false;       // results travel as int16
-    const int rows = worst_rows32(g, PT);
+    const int rows = worst_region_rows(g, PT, 32);
     // result rows: PT int16 plus padding so the two half-waves (rows f and f+4) hit different banks
     int res_stride = PT * 2;
     while ((res_stride / 4) % 8 != 4) res_stride += 4;

@@ -20,6 +20,29 @@ struct MfmaPlan {
     FastDiv div_wp, div_hp, div_ccw, div_cw;
 };
 
+// Most padded input rows touched by any run of `run` consecutive (flattened) output pixels that
+// starts at a multiple of `step`.  The row span only depends on the start modulo the pixels of one
+// image, so one period of starts is enough (the host pays a few dozen iterations per launch).
+inline int worst_region_rows(const ConvGeom &g, int run, int step)
+{
+    const long long howo = (long long)g.ho * g.wo;
+    long long a = step, b = howo;
+    while (b) { const long long t = a % b; a = b; b = t; }      // gcd(step, howo)
+    const long long period = howo / a;
+    const long long starts = (g.m_total + step - 1) / step;
+    const long long n = starts < period ? starts : period;
+    int worst = 0;
+    for (long long i = 0; i < n; ++i) {
+        const long long m0 = i * step;
+        const long long m1 = (m0 + run < g.m_total ? m0 + run : g.m_total) - 1;
+        const int ia = (int)(m0 / howo), ib = (int)(m1 / howo);
+        const int oa = (int)((m0 % howo) / g.wo), ob = (int)((m1 % howo) / g.wo);
+        const int rows = (ib * g.hp + ob * g.sh + g.kh - 1) - (ia * g.hp + oa * g.sh) + 1;
+        if (rows > worst) worst = rows;
+    }
+    return worst;
+}
+
 template <int FMT> struct Enc;
 
 template <> struct Enc<0> {                    // int8
