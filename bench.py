@@ -19,7 +19,7 @@ if ROOT not in sys.path:
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (scaled by a 256 MiB copy: reads x2.00, writes x1.00), see profiles/; None where not measured.
-MEASURED_TRAFFIC = {("alexnet_conv2", "mfma_f4"): 2901.1 * 1024 * 2.0 + 50796.4 * 1024}
+MEASURED_TRAFFIC = {("alexnet_conv2", "mfma_f4"): 2914.6 * 1024 * 2.0 + 51698.7 * 1024}
 
 PEAKS = {  # MI355X published dense peaks
     "mfma_f4": {"bound": "mfma", "peak": 10100.0, "unit": "TFLOP/s"},     # fp4 10.1 PFLOP/s, 2 flops per MAC
@@ -158,7 +158,19 @@ def main():
     dom = max(range(len(dev)), key=lambda i: conv_ms[i])
     pk = PEAKS[used]
     per_mac = 1.0 if used == "popcount" else 2.0
-    achieved = layers[dom].bit_macs * per_mac / (conv_ms[dom] * 1e-3) / 1e12
+    sec = conv_ms[dom] * 1e-3
+    compute = {"bound": pk["bound"], "achieved": layers[dom].bit_macs * per_mac / sec / 1e12, "peak": pk["peak"],
+               "unit": pk["unit"]}
+    hbm = {"bound": "hbm", "achieved": algo_bytes(layers[dom]) / sec / 1e9, "peak": 8000.0, "unit": "GB/s"}
+    for r in (compute, hbm):
+        r["frac"] = r["achieved"] / r["peak"]
+    # the binding roof is the one whose floor time at the published peak is longer; at the same measured
+    # duration that is the one with the larger fraction.  The other one is reported next to it.
+    bind, other = (hbm, compute) if hbm["frac"] >= compute["frac"] else (compute, hbm)
+    roofline = dict(bind)
+    roofline.update({"traffic": MEASURED_TRAFFIC.get((args.workload, used)),
+                     "algorithmic_bytes": algo_bytes(layers[dom]),
+                     "kernel": f"xnor_conv2d[{layers[dom].name}]", "other_roof": other})
     out = {
         "metric": "binary conv throughput (Gbinop/s) + % of popcount/MFMA roofline",
         "value": macs / (dt / args.steps) / 1e9, "unit": "Gbinop/s",
@@ -169,12 +181,7 @@ def main():
                    "algo": used, "algo_conv_ms": compare, "step": "xnor_binactiv + xnor_conv2d per layer",
                    "conv_ms": conv_ms, "pack_weights_ms_once": pack_ms,
                    "conv_only_Gbinop_s": [l.bit_macs / (t * 1e-3) / 1e9 for l, t in zip(layers, conv_ms)]},
-        "roofline": {"bound": pk["bound"], "achieved": achieved, "peak": pk["peak"], "unit": pk["unit"],
-                     "frac": achieved / pk["peak"],
-                     "traffic": MEASURED_TRAFFIC.get((args.workload, used)),
-                     "algorithmic_bytes": algo_bytes(layers[dom]),
-                     "hbm_GBs": algo_bytes(layers[dom]) / (conv_ms[dom] * 1e-3) / 1e9,
-                     "hbm_frac": algo_bytes(layers[dom]) / (conv_ms[dom] * 1e-3) / 8e12, "kernel": f"xnor_conv2d[{layers[dom].name}]"},
+        "roofline": roofline,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, inputs)

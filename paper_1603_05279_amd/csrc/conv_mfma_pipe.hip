@@ -21,7 +21,7 @@ __device__ long long *g_timeline_pipe = nullptr;
 #define XNOR_TLP(slot, who)                                                                   \
     do {                                                                                      \
         if (threadIdx.x == (who) && g_timeline_pipe)                                          \
-            g_timeline_pipe[(size_t)blockIdx.x * 8 + (slot)] = wall_clock64();                \
+            g_timeline_pipe[(size_t)blockIdx.x * 16 + (slot)] = wall_clock64();                \
     } while (0)
 #else
 #define XNOR_TLP(slot, who) do { } while (0)
@@ -33,7 +33,7 @@ struct PipePlan {
     int fgroups;        // filter groups of FG filters
     int total_frags;    // ceil(m_total / 32)
     int res_stride;     // bytes per filter row of a result buffer
-    int off_x[2], off_res[2], off_alds[2], off_ktile[2], off_obase[2], off_xoff;   // LDS byte offsets
+    int off_x[2], off_res[2], off_alds[2], off_ktile[2], off_obase[2], off_xoff, off_alpha;   // LDS byte offsets
     FastDiv div_wp, div_hp, div_ccw;
 };
 
@@ -170,45 +170,49 @@ __global__ __launch_bounds__(512, 2) void conv_mfma_pipe_kernel(
             }
         }
     };
-    // out = float(dot) * K * alpha for output tile (T, fg), results read from result buffer rb
+    // out = float(dot) * K * alpha for output tile (T, fg), results read from result buffer rb.
+    // A lane takes four consecutive pixels of one filter row and writes them with one 16-byte
+    // store when they are four consecutive floats of the output (same image, inside the tile);
+    // a whole output tile is then a dozen store instructions per wave, all in flight at once.
+    // Everything a lane needs comes from LDS: a vector load in here would wait for the stores
+    // before it (loads and stores share one completion counter on this chip).
     auto drain = [&](int T, int fg, int rb) {
+        typedef float f4u __attribute__((ext_vector_type(4), aligned(4)));
+        typedef int i4u __attribute__((ext_vector_type(4), aligned(4)));
+        constexpr int PQ = PT / 4;                 // pixel quads per filter row
         const uint8_t *res = lds + pl.off_res[rb];
         const float *ktile = reinterpret_cast<const float *>(lds + pl.off_ktile[T & 1]);
         const unsigned long long *obase = reinterpret_cast<const unsigned long long *>(lds + pl.off_obase[T & 1]);
+        const float *alpha_lds = reinterpret_cast<const float *>(lds + pl.off_alpha);
         const int npx = (int)(tile_m1(T) - tile_m0(T));
         const int f0 = fg * FG;
         const int nf = min(FG, g.k_out - f0);
-        // Lanes run along the pixels of a filter row (contiguous float stores).  A service wave
-        // owns every fourth row; lane q of the wave fetches the alpha of the wave's q-th row once,
-        // the row loop then takes it with a lane read.  (Vector loads share their completion
-        // counter with the stores on this chip, so no vector load may sit inside the store loop.)
-        const int wv = __builtin_amdgcn_readfirstlane(htid >> 6);
-        const int my_rows = (nf - wv + 3) >> 2;                       // rows wv, wv+4, ...
-        const float al_lane = alpha[f0 + min(wv + 4 * lane, nf - 1)];
-        for (int pxb = 0; pxb < npx; pxb += 64) {
-            const int px = min(pxb + lane, npx - 1);
-            const bool live = pxb + lane < npx;
-            const float kpx = ktile[px];
-            const size_t ob = (size_t)obase[px] + (size_t)(f0 + wv) * howo;
-            const uint8_t *rcol = res + (size_t)wv * pl.res_stride + px * 2;
-            for (int q0 = 0; q0 < my_rows; q0 += 8) {
-                int dot[8];
+        const int items = nf * PQ;
+        for (int it = htid; it < items; it += NS_THREADS) {
+            const int row = it / PQ, px0 = (it - row * PQ) * 4;
+            if (px0 >= npx) continue;
+            const int2 d2 = *reinterpret_cast<const int2 *>(res + (size_t)row * pl.res_stride + px0 * 2);
+            const float4 k4 = *reinterpret_cast<const float4 *>(ktile + px0);
+            const float al = alpha_lds[f0 + row];
+            const int last = min(px0 + 3, npx - 1);
+            const unsigned long long ob0 = obase[px0], ob3 = obase[last];
+            const int dot[4] = {(int)(short)(d2.x & 0xffff), d2.x >> 16, (int)(short)(d2.y & 0xffff), d2.y >> 16};
+            const float kk[4] = {k4.x, k4.y, k4.z, k4.w};
+            float y[4];
 #pragma unroll
-                for (int u = 0; u < 8; ++u)        // 8 independent LDS reads in flight
-                    dot[u] = *reinterpret_cast<const int16_t *>(rcol + (size_t)min(q0 + u, my_rows - 1) * 4 * pl.res_stride);
+            for (int u = 0; u < 4; ++u) y[u] = (float)dot[u] * kk[u] * al;
+            const size_t frow = (size_t)(f0 + row) * howo;
+            if (px0 + 3 < npx && ob3 - ob0 == 3ull) {
+                *reinterpret_cast<f4u *>(out + ob0 + frow) = f4u{y[0], y[1], y[2], y[3]};
+                if (dot_out) *reinterpret_cast<i4u *>(dot_out + ob0 + frow) = i4u{dot[0], dot[1], dot[2], dot[3]};
+            } else {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) {
-                    const int q = q0 + u;
-                    if (q < my_rows) {             // uniform
-                        const float al = __builtin_bit_cast(
-                            float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, al_lane), q));
-                        const size_t o = ob + (size_t)q * 4 * howo;
-                        if (live) {
-                            out[o] = (float)dot[u] * kpx * al;
-                            if (dot_out) dot_out[o] = dot[u];
-                        }
+                for (int u = 0; u < 4; ++u)
+                    if (px0 + u < npx) {
+                        const size_t o = (size_t)obase[px0 + u] + frow;
+                        out[o] = y[u];
+                        if (dot_out) dot_out[o] = dot[u];
                     }
-                }
             }
         }
     };
@@ -224,6 +228,10 @@ __global__ __launch_bounds__(512, 2) void conv_mfma_pipe_kernel(
             const uint32_t dx = t - dy * g.kw;
             xoff_tab[b] = (int)((dy * g.wp + dx) * pl.ps + wl * E::BPB);
         }
+    }
+    {   // every filter's alpha, for the drains
+        float *alpha_lds = reinterpret_cast<float *>(lds + pl.off_alpha);
+        for (int f = tid; f < g.k_out; f += 512) alpha_lds[f] = alpha[f];
     }
     if (!matrix_role) {
         fill_x(0, 0, 0);
@@ -287,8 +295,12 @@ __global__ __launch_bounds__(512, 2) void conv_mfma_pipe_kernel(
                 const int fblk = min(fg * (FG / 32) + wf * FW + i, g.fblocks - 1);
                 wrec0[i] = __builtin_amdgcn_readfirstlane(fblk * recs_per_fb);
             }
-            mfma_kloop<E, FW, PW, 7, 1>(acc, lds + pl.off_x[xcur], pbase, xoff_tab, tab_lane, wrsrc, wlane, wrec0,
+            if (st == 0) XNOR_TLP(8, 0);
+            if (st == 1) XNOR_TLP(10, 0);
+            mfma_kloop<E, FW, PW, 5, 2>(acc, lds + pl.off_x[xcur], pbase, xoff_tab, tab_lane, wrsrc, wlane, wrec0,
                                   zero_rec, (ch * ccw) / E::BPS, pl.nsteps, steps_per_tap, pl.tap_jump);
+            if (st == 0) XNOR_TLP(9, 0);
+            if (st == 1) XNOR_TLP(11, 0);
             if (completes) {
                 // hand the integers to the service waves: res[filter row][pixel] as int16
                 uint8_t *res = lds + pl.off_res[rt & 1];
@@ -306,10 +318,14 @@ __global__ __launch_bounds__(512, 2) void conv_mfma_pipe_kernel(
                     }
             }
         } else {
-            if (refill) fill_x(Tn, chn, xcur ^ 1);
-            if (has_next && Tn != T) stage_a(Tn);
-            if (fg == 0 && ch == 0) make_pixel_tables(T);
+            // stores first: they complete on their own while the next stage is prepared
             if (pend_T >= 0) drain(pend_T, pend_fg, pend_rb);
+            if (st == 1) XNOR_TLP(12, 256);
+            if (refill) fill_x(Tn, chn, xcur ^ 1);
+            if (st == 0) XNOR_TLP(13, 256);
+            if (has_next && Tn != T) stage_a(Tn);
+            if (st == 0) XNOR_TLP(14, 256);
+            if (fg == 0 && ch == 0) make_pixel_tables(T);
         }
         if (st == 0) { XNOR_TLP(2, 0); XNOR_TLP(3, 256); }
         if (st == 1) { XNOR_TLP(4, 0); XNOR_TLP(5, 256); }
@@ -362,7 +378,8 @@ static bool make_pipe_plan(const ConvGeom &g, int fmt, int PT, int FG, PipePlan 
         pl->off_ktile[1] = (int)off; off += PT * 4;
         pl->off_obase[0] = (int)off; off += PT * 8;
         pl->off_obase[1] = (int)off; off += PT * 8;
-        pl->off_xoff = (int)off; off += (long long)nsteps * bps * 4 + 16;
+        pl->off_xoff = (int)off; off += ((long long)nsteps * bps * 4 + 31) / 16 * 16;
+        pl->off_alpha = (int)off; off += ((long long)g.k_out * 4 + 15) / 16 * 16;
         if (off > PIPE_LDS_LIMIT) continue;
         pl->cc_words = ccw;
         pl->ps = (int)ps;

@@ -120,13 +120,20 @@ template <> struct Enc<1> {                    // 4-bit float E2M1
 };
 
 
+constexpr int ring_lcm(int a, int b)
+{
+    int m = a;
+    while (m % b) m += a;
+    return m;
+}
+
 // One chunk's K loop of a wave: acc[i][j] += W(filter block i, step s) x X(pixel block j, step s)
 // for s = 0 .. nsteps-1.  Weight records are consumed in order: +1 per step, +tap_jump more when a
 // chunk that holds only part of the channels moves to the next tap; steps past the end multiply by
 // the all-zero weight record, so the unrolled body needs no branches and the prefetch depth never
 // drops.  Operands are requested DW steps (weights: buffer loads with a scalar offset, L2 latency)
 // and DX steps (activations: LDS, through the per-step offset table) ahead of their use and live in
-// register rings of DW+1 and DX+1 slots; the body is unrolled over one turn of the weight ring.
+// register rings of DW+1 and DX+1 slots; the body is unrolled until both rings are back at slot 0.
 // The scheduling barriers pin the order written here (next operands requested, then the current
 // step's matrix instructions interleaved with those requests), which the compiler otherwise
 // regroups into one burst of loads followed by one burst of MFMAs with the latencies exposed.
@@ -138,7 +145,8 @@ __device__ __forceinline__ void mfma_kloop(typename E::acc_t (&acc)[FW][PW], con
                                            int tap_jump)
 {
     constexpr int RW = DW + 1, RX = DX + 1;
-    static_assert((RW & (RW - 1)) == 0 && (RX & (RX - 1)) == 0 && RX <= RW, "ring sizes are powers of two");
+    constexpr int TURN = ring_lcm(RW, RX);     // sub-steps after which both rings are back at slot 0
+    static_assert(RX <= RW && TURN <= 8 && TURN % 2 == 0, "unrolled turn: even, at most 8 sub-steps");
     int w_rec = rec_start, w_cnt = 0, w_left = nsteps;
     auto load_w = [&](v4i (&dst)[FW]) {
         const int live = w_left > 0 ? 1 : 0;   // past the end: the all-zero record
@@ -174,28 +182,40 @@ __device__ __forceinline__ void mfma_kloop(typename E::acc_t (&acc)[FW][PW], con
 #pragma unroll
     for (int u = 0; u < DX; ++u) load_x(x[u], load_t(u));
     tq[0] = load_t(DX);
-    for (int s = 0; s < nsteps; s += RW) {
+    auto substep = [&](int s, int u) {
+        load_w(w[(u + DW) % RW]);                       // step s+u+DW
+        tq[(u + 1) & 1] = load_t(s + u + DX + 1);
+        load_x(x[(u + DX) % RX], tq[u & 1]);            // step s+u+DX, offset read one sub-step ago
+        fma_all(w[u % RW], x[u % RX]);
+        // one LDS read behind each of the first PW+1 MFMAs, then the FW weight loads
 #pragma unroll
-        for (int u = 0; u < RW; ++u) {
-            if (RW > 4 && u == RW / 2 && s + u >= nsteps) break;      // short last turn
-            load_w(w[(u + DW) % RW]);                       // step s+u+DW
-            tq[(u + 1) & 1] = load_t(s + u + DX + 1);
-            load_x(x[(u + DX) % RX], tq[u & 1]);            // step s+u+DX, offset read one sub-step ago
-            fma_all(w[u % RW], x[u % RX]);
-            // one LDS read behind each of the first PW+1 MFMAs, then the FW weight loads
-#pragma unroll
-            for (int q = 0; q < PW + 1; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            }
-#pragma unroll
-            for (int q = 0; q < FW; ++q) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
-            }
-            __builtin_amdgcn_sched_group_barrier(0x008, FW * PW - PW - 1 - FW, 0);
-            __builtin_amdgcn_sched_barrier(0);
+        for (int q = 0; q < PW + 1; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
+#pragma unroll
+        for (int q = 0; q < FW; ++q) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, FW * PW - PW - 1 - FW, 0);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    int s = 0;
+    for (; s + TURN <= nsteps; s += TURN) {             // whole turns: one basic block, no exits
+#pragma unroll
+        for (int u = 0; u < TURN; ++u) substep(s, u);
+    }
+    // the last, partial turn.  The accumulators are pinned before every exit test: otherwise the
+    // matrix instructions sink below the branches and run in one burst behind all the loads.
+#pragma unroll
+    for (int u = 0; u < TURN - 1; ++u) {
+        if (s + u >= nsteps) break;
+        substep(s, u);
+#pragma unroll
+        for (int i = 0; i < FW; ++i)
+#pragma unroll
+            for (int j = 0; j < PW; ++j) asm volatile("" : "+v"(acc[i][j]));
     }
 }
 
