@@ -30,14 +30,16 @@ PEAKS = {  # MI355X published dense peaks
 }
 
 
-def algo_bytes(layer):
+def algo_bytes(layer, fused=False):
     """Bytes one xnor_conv2d launch must move: packed activations, matrix-core weight image (fp4),
     A, alpha and the float output."""
     cw = (layer.c + 31) // 32
     taps = layer.kh * layer.kw
     wimg = ((layer.k_out + 31) // 32) * ((taps * cw + 1) // 2) * 1024
-    return (layer.n * layer.h * layer.w * (cw * 4 + 4) + wimg + layer.k_out * 4 +
-            layer.n * layer.k_out * layer.h_out * layer.w_out * 4)
+    m = layer.n * layer.h_out * layer.w_out
+    # result: the float tensor, or (fused epilogue) the next layer's sign words and A
+    result = m * ((layer.k_out + 31) // 32 * 4 + 4) if fused else m * layer.k_out * 4
+    return layer.n * layer.h * layer.w * (cw * 4 + 4) + wimg + layer.k_out * 4 + result
 
 
 def cpu_baseline(layers, inputs):
@@ -63,11 +65,17 @@ def main():
                     choices=["tiny", "alexnet_conv2", "alexnet_conv345", "resnet18"])
     ap.add_argument("--algo", default="fastest", choices=["fastest", "popcount", "mfma_i8", "mfma_f4"],
                     help="inner loop of the binary convolution; 'fastest' times all three and keeps the winner")
+    ap.add_argument("--chain", default="none", choices=["none", "layerwise", "fused"],
+                    help="alexnet_conv345 only: feed each layer the previous layer's output instead of its own "
+                         "synthetic input; 'layerwise' = xnor_binactiv + xnor_conv2d per layer, 'fused' = one "
+                         "xnor_binactiv, then xnor_conv2d_binactiv emits the next layer's bits and A directly")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy, so a rocprofv3 --pmc run of this command holds "
                          "a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
     args = ap.parse_args()
+    if args.chain != "none" and args.workload != "alexnet_conv345":
+        sys.exit("bench.py: --chain needs --workload alexnet_conv345 (the only workload whose layers feed each other)")
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over the batch with no "
                  "exchange step; see DESIGN.md). Run with --gpus 1.")
@@ -118,14 +126,30 @@ def main():
         xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, None, bufs.desc)
     compare = {name: conv_only_ms(name) for name in ("popcount", "mfma_i8", "mfma_f4")}
     used = min(compare, key=compare.get) if args.algo == "fastest" else args.algo
+    if args.chain == "fused" and used == "popcount":
+        sys.exit("bench.py: the fused epilogue exists in the matrix-core kernels only (--algo mfma_f4 or mfma_i8)")
     algo = xnor.ALGOS[used]
+
+    workspaces = [torch.empty((max(16, xnor.conv2d_binactiv_workspace_bytes(b.desc)),), dtype=torch.uint8,
+                              device="cuda") for (_, _, _, _, b) in dev] if args.chain == "fused" else None
 
     def step(events=None):
         for i, (x, sc, sf, pw, bufs) in enumerate(dev):
-            xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, None, bufs.desc)
+            last = i + 1 == len(dev)
+            if args.chain == "none":
+                xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, None, bufs.desc)
+            elif args.chain == "layerwise" or i == 0:
+                src = x if i == 0 else dev[i - 1][4].out
+                xnor.xnor_binactiv(src, sc, sf, bufs.xbits, bufs.A, None, bufs.desc)
             if events is not None:
                 events[i][0].record()
-            xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha, bufs.out, None, bufs.desc, algo)
+            if args.chain == "fused" and not last:
+                nxt = dev[i + 1]
+                xnor.xnor_conv2d_binactiv(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha, nxt[1], nxt[2],
+                                          nxt[4].xbits, nxt[4].A, None, workspaces[i], bufs.desc, algo)
+            else:
+                xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha, bufs.out, None, bufs.desc,
+                                 algo)
             if events is not None:
                 events[i][1].record()
 
@@ -161,7 +185,9 @@ def main():
     sec = conv_ms[dom] * 1e-3
     compute = {"bound": pk["bound"], "achieved": layers[dom].bit_macs * per_mac / sec / 1e12, "peak": pk["peak"],
                "unit": pk["unit"]}
-    hbm = {"bound": "hbm", "achieved": algo_bytes(layers[dom]) / sec / 1e9, "peak": 8000.0, "unit": "GB/s"}
+    dom_fused = args.chain == "fused" and dom + 1 < len(dev)
+    hbm = {"bound": "hbm", "achieved": algo_bytes(layers[dom], dom_fused) / sec / 1e9, "peak": 8000.0,
+           "unit": "GB/s"}
     for r in (compute, hbm):
         r["frac"] = r["achieved"] / r["peak"]
     # the binding roof is the one whose floor time at the published peak is longer; at the same measured
@@ -169,8 +195,9 @@ def main():
     bind, other = (hbm, compute) if hbm["frac"] >= compute["frac"] else (compute, hbm)
     roofline = dict(bind)
     roofline.update({"traffic": MEASURED_TRAFFIC.get((args.workload, used)),
-                     "algorithmic_bytes": algo_bytes(layers[dom]),
-                     "kernel": f"xnor_conv2d[{layers[dom].name}]", "other_roof": other})
+                     "algorithmic_bytes": algo_bytes(layers[dom], dom_fused),
+                     "kernel": f"{'xnor_conv2d_binactiv' if dom_fused else 'xnor_conv2d'}[{layers[dom].name}]",
+                     "other_roof": other})
     out = {
         "metric": "binary conv throughput (Gbinop/s) + % of popcount/MFMA roofline",
         "value": macs / (dt / args.steps) / 1e9, "unit": "Gbinop/s",
@@ -178,7 +205,10 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {"mfma_f4": "fp4", "mfma_i8": "i8", "popcount": "u32"}[used], "data": "synthetic",
         "config": {"workload": args.workload, "layers": [l.name for l in layers], "batch": layers[0].n,
-                   "algo": used, "algo_conv_ms": compare, "step": "xnor_binactiv + xnor_conv2d per layer",
+                   "algo": used, "algo_conv_ms": compare, "step": {"none": "xnor_binactiv + xnor_conv2d per layer, each layer on its own synthetic input",
+                            "layerwise": "xnor_binactiv + xnor_conv2d per layer, each layer on the previous output",
+                            "fused": "xnor_binactiv, then xnor_conv2d_binactiv per layer (plain xnor_conv2d last)"
+                            }[args.chain],
                    "conv_ms": conv_ms, "pack_weights_ms_once": pack_ms,
                    "conv_only_Gbinop_s": [l.bit_macs / (t * 1e-3) / 1e9 for l, t in zip(layers, conv_ms)]},
         "roofline": roofline,

@@ -143,6 +143,31 @@ int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
                 const xnor_conv_desc *d, int algo, void *hip_stream);
 
 /*
+ * BinConv of one block followed by the BatchNorm and BinActiv of the NEXT block (block order
+ * BatchNorm -> BinActiv -> BinConv of sec. 3.2, "Training XNOR-Networks": what consumes a BinConv output is
+ * the next block's normalisation and sign), without the float tensor travelling through memory:
+ *     y = float(dot) * K * alpha                          as xnor_conv2d
+ *     z = fmaf(y, bn_scale_next[k], bn_shift_next[k])     float32; z = y when both are NULL
+ *     xbits_next [n][h_out][w_out][ceil(k_out/32)]        bit k%32 of word k/32 = (z >= 0), tail bits 0
+ *     A_next     [n][h_out][w_out] = (1/k_out) sum_k |z|  (sec. 3.2, matrix A of the next block's input)
+ * xbits_next and A_next are what xnor_binactiv(out, bn_scale_next, bn_shift_next, ...) would produce from
+ * the output of xnor_conv2d: the bits are identical, A_next agrees to float rounding (the |z| are added in
+ * a different order).  The next layer then runs xnor_conv2d(xbits_next, ..., K = NULL, A = A_next, ...).
+ *   xbits, wbits, wmfma, K, A, alpha   in   as for xnor_conv2d (wmfma is required)
+ *   bn_scale_next, bn_shift_next       in   (nullable, both or neither) float32 [k_out]
+ *   out        out  (nullable) float32 [n][k_out][h_out][w_out]: y, for callers that also need the real output
+ *   workspace       device scratch of xnor_conv2d_binactiv_workspace_bytes(d) bytes (partial |z| sums of the
+ *                   filter tiles), contents undefined afterwards; may be NULL when that size is 0
+ *   algo            XNOR_ALGO_AUTO, XNOR_ALGO_MFMA_I8 or XNOR_ALGO_MFMA_F4 (XNOR_ERR_UNSUPPORTED otherwise)
+ */
+size_t xnor_conv2d_binactiv_workspace_bytes(const xnor_conv_desc *d);
+int xnor_conv2d_binactiv(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+                         const float *K, const float *A, const float *alpha,
+                         const float *bn_scale_next, const float *bn_shift_next,
+                         uint32_t *xbits_next, float *A_next, float *out, void *workspace,
+                         const xnor_conv_desc *d, int algo, void *hip_stream);
+
+/*
  * Fully connected layer = convolution whose filter covers the whole input (footnote of sec. 1).
  *   xbits [batch][Fw], wbits [out_features][Fw], Fw = ceil(in_features/32)
  *   Krow  [batch]  = mean_j |x[b][j]|  (xnor_compute_K / xnor_binactiv with c = in_features, 1x1)

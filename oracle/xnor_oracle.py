@@ -122,6 +122,15 @@ def binary_conv2d(x, W, stride=(1, 1), pad=(0, 0), bn_scale=None, bn_shift=None)
     return {"dot": d, "K": K, "alpha": a, "out": scale_output(d, K, a), "y": y}
 
 
+def binactiv(x, bn_scale=None, bn_shift=None):
+    """BatchNorm -> BinActiv of one block on a real tensor x [n][c][h][w] (block order of sec. 3.2):
+    returns (y, sign(y) as int8 +-1, A = channel mean of |y| in float64).  Applied to the float
+    output of a BinConv with the NEXT block's normalisation it is the definition of what the
+    library's fused convolution epilogue emits."""
+    y = batchnorm(x, bn_scale, bn_shift)
+    return y, sign(y), A_map(y)
+
+
 def binary_linear(x, W):
     """Fully connected layer as the convolution whose filter covers the whole input
     (footnote of sec. 1): x [batch][in_f], W [out_f][in_f].  Returns dict(dot, K, alpha, out)

@@ -168,6 +168,44 @@ int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
     }
 }
 
+size_t xnor_conv2d_binactiv_workspace_bytes(const xnor_conv_desc *d)
+{
+    ConvGeom g;
+    if (make_geom(d, &g) != XNOR_OK) return 0;
+    // up to 64 filters every workgroup tiling covers all of them: no partial sums
+    return g.k_out <= 64 ? 0 : (size_t)g.fblocks * (size_t)g.m_total * sizeof(float);
+}
+
+int xnor_conv2d_binactiv(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+                         const float *K, const float *A, const float *alpha,
+                         const float *bn_scale_next, const float *bn_shift_next,
+                         uint32_t *xbits_next, float *A_next, float *out, void *workspace,
+                         const xnor_conv_desc *d, int algo, void *hip_stream)
+{
+    if (!xbits || !wbits || (!K && !A) || !alpha || !xbits_next || !A_next) return XNOR_ERR_NULL;
+    ConvGeom g;
+    if (xnor_status s = make_geom(d, &g)) return s;
+    if (!workspace && g.k_out > 64) return XNOR_ERR_NULL;
+    if ((long long)g.m_total * g.fblocks > 0x7fffffffLL) return XNOR_ERR_SHAPE;
+    if (!aligned16(xbits) || !aligned16(wbits) || !aligned16(wmfma) || !aligned16(K) || !aligned16(A) ||
+        !aligned16(alpha) || !aligned16(xbits_next) || !aligned16(A_next) || !aligned16(out) ||
+        !aligned16(workspace))
+        return XNOR_ERR_ALIGN;
+    if (xnor_status s = check_bn(bn_scale_next, bn_shift_next)) return s;
+    if (algo != XNOR_ALGO_AUTO && algo != XNOR_ALGO_MFMA_I8 && algo != XNOR_ALGO_MFMA_F4)
+        return XNOR_ERR_UNSUPPORTED;      // the fused epilogue lives in the matrix-core kernels only
+    if (!wmfma) return XNOR_ERR_NULL;
+    FuseArgs fz;
+    fz.bn_scale = bn_scale_next; fz.bn_shift = bn_shift_next;
+    fz.xbits_next = xbits_next; fz.A_next = A_next; fz.workspace = static_cast<float *>(workspace);
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (algo != XNOR_ALGO_MFMA_I8) {
+        const xnor_status s = launch_conv_mfma(1, xbits, wmfma, K, A, alpha, out, nullptr, g, st, &fz);
+        if (s != XNOR_ERR_UNSUPPORTED || algo == XNOR_ALGO_MFMA_F4) return s;
+    }
+    return launch_conv_mfma(0, xbits, wmfma, K, A, alpha, out, nullptr, g, st, &fz);
+}
+
 int xnor_linear(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
                 const float *Krow, const float *alpha, float *out, int32_t *dot_out,
                 int batch, int in_features, int out_features, int algo, void *hip_stream)

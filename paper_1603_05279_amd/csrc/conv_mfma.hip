@@ -33,11 +33,11 @@ __device__ long long *g_timeline = nullptr;
 #endif
 
 // Accumulator tiles of up to 8 result blocks leave room for two waves per SIMD (256 registers each).
-template <int FMT, int FW, int PW, int WF, int WP>
+template <int FMT, int FW, int PW, int WF, int WP, bool FUSE>
 __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfma_kernel(
     const uint32_t *__restrict__ xbits, const v4i *__restrict__ wimg, uint32_t wimg_bytes,
     const float *__restrict__ K, const float *__restrict__ A, const float *__restrict__ alpha,
-    float *__restrict__ out, int32_t *__restrict__ dot_out, ConvGeom g, MfmaPlan pl)
+    float *__restrict__ out, int32_t *__restrict__ dot_out, ConvGeom g, MfmaPlan pl, FuseArgs fz)
 {
     typedef Enc<FMT> E;
     typedef typename E::acc_t acc_t;
@@ -49,6 +49,8 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     int *xoff_tab = rowinfo + pl.max_rows;     // [nsteps * BPS]
     float *a_lds = reinterpret_cast<float *>(xoff_tab + pl.nsteps * E::BPS);   // [max_rows * wp], halo = 0
     float *ktile = a_lds + pl.max_rows * g.wp;                                   // [PT]
+    float *asum_lds = ktile + PT;                                                // [WF][PT], fused epilogue only
+    uint32_t *wtile_lds = reinterpret_cast<uint32_t *>(asum_lds + WF * PT);      // [PT][FT/32], fused epilogue only
 
     XNOR_TL(0);
     const int tid = threadIdx.x;
@@ -212,6 +214,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         ppix[j] = mc - pimg[j] * howo;
         Km[j] = K ? K[mc] : ktile[pl_idx];
     }
+    if constexpr (!FUSE) {
 #pragma unroll
     for (int i = 0; i < FW; ++i) {
         const int kb = f0 + (wf * FW + i) * 32 + 4 * half;
@@ -226,7 +229,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
             if (whole) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v)
-                    orow[(size_t)(8 * (v >> 2) + (v & 3)) * howo] = (float)E::to_int(acc[i][j], v) * Km[j] * al[v];
+                    orow[(size_t)(8 * (v >> 2) + (v & 3)) * howo] = E::to_float(acc[i][j], v) * Km[j] * al[v];
             } else {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
@@ -240,6 +243,90 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
             }
         }
     }
+    } else {
+    // Fused epilogue: the next block's BatchNorm and BinActiv on y = float(dot) * K * alpha while it
+    // is still in registers.  A lane holds 16 of the 32 filter rows of a block for one pixel; the
+    // other 16 sit in the lane 32 further on, so one cross-half exchange completes the sign word
+    // and the |z| sum of the block.  Exchanges run for every lane (dead pixel columns carry
+    // clamped data); only the stores are predicated.
+    const bool has_bn = fz.bn_scale != nullptr;
+    const int cwn = g.fblocks;                    // words per pixel of the next layer's input
+    constexpr int WT = FT / 32;                   // words per pixel this workgroup produces
+    float asum[PW];
+#pragma unroll
+    for (int j = 0; j < PW; ++j) asum[j] = 0.0f;
+#pragma unroll
+    for (int i = 0; i < FW; ++i) {
+        const int fblk = f0 / 32 + wf * FW + i;
+        const int kb = fblk * 32 + 4 * half;
+        float al[16], bs[16], bb[16];
+        uint32_t bit[16];                         // the row's bit in the sign word, 0 past the last filter
+        const bool whole = kb + 28 < g.k_out;     // all 16 rows of this lane exist (uniform per half-wave pair)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int kr = 8 * (v >> 2) + (v & 3);             // row within this half's 16
+            const int kc = min(kb + kr, g.k_out - 1);
+            al[v] = alpha[kc];
+            bs[v] = has_bn ? fz.bn_scale[kc] : 1.0f;
+            bb[v] = has_bn ? fz.bn_shift[kc] : 0.0f;
+            bit[v] = kb + kr < g.k_out ? 1u << (kr + 4 * half) : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < PW; ++j) {
+            uint32_t word = 0;
+            float sabs = 0.0f;
+            if (whole) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float y = E::to_float(acc[i][j], v) * Km[j] * al[v];
+                    const float z = has_bn ? fmaf(y, bs[v], bb[v]) : y;
+                    word |= z >= 0.0f ? bit[v] : 0u;
+                    sabs += fabsf(z);
+                }
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const float y = E::to_float(acc[i][j], v) * Km[j] * al[v];
+                    const float z = has_bn ? fmaf(y, bs[v], bb[v]) : y;
+                    word |= z >= 0.0f ? bit[v] : 0u;
+                    sabs += bit[v] ? fabsf(z) : 0.0f;
+                }
+            }
+            if (out && plive[j]) {                // callers that also want the real tensor
+                float *orow = out + ((size_t)pimg[j] * g.k_out + kb) * howo + ppix[j];
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (bit[v]) orow[(size_t)(8 * (v >> 2) + (v & 3)) * howo] = E::to_float(acc[i][j], v) * Km[j] * al[v];
+            }
+            word |= (uint32_t)__shfl_xor((int)word, 32);
+            asum[j] += sabs + __shfl_xor(sabs, 32);
+            if (half == 0) wtile_lds[((wp * PW + j) * 32 + l32) * WT + wf * FW + i] = word;
+        }
+    }
+    // |z| summed over this workgroup's filters: waves along the filter axis combine through LDS in
+    // a fixed order.  Sign words leave through LDS too, so that consecutive threads write
+    // consecutive words of a pixel (the whole tile is one contiguous run when the workgroup holds
+    // every filter).
+    if (half == 0) {
+#pragma unroll
+        for (int j = 0; j < PW; ++j) asum_lds[wf * PT + (wp * PW + j) * 32 + l32] = asum[j];
+    }
+    __syncthreads();
+    for (int t = tid; t < PT * WT; t += NT) {
+        const uint32_t m = m0 + (uint32_t)(t / WT);
+        const int fblk = f0 / 32 + t % WT;
+        if (m < (uint32_t)g.m_total && fblk < cwn) fz.xbits_next[(size_t)m * cwn + fblk] = wtile_lds[t];
+    }
+    for (int t = tid; t < PT; t += NT) {
+        const uint32_t m = m0 + (uint32_t)t;
+        if (m >= (uint32_t)g.m_total) continue;
+        float sum = 0.0f;
+#pragma unroll
+        for (int q = 0; q < WF; ++q) sum += asum_lds[q * PT + t];
+        if (gridDim.y == 1) fz.A_next[m] = sum / (float)g.k_out;
+        else fz.workspace[(size_t)blockIdx.y * g.m_total + m] = sum;
+    }
+    }
     XNOR_TL(4);
 }
 
@@ -252,13 +339,14 @@ extern "C" int xnor_debug_timeline(long long *buf)
 
 static const int LDS_LIMIT = 160 * 1024;
 
-static size_t plan_lds_bytes(const MfmaPlan &pl, int bps, int wp, int PT)
+// fuse_rows: rows of PT words for the fused epilogue's |z| sums and sign words (0 without it)
+static size_t plan_lds_bytes(const MfmaPlan &pl, int bps, int wp, int PT, int fuse_rows)
 {
     return (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 + (size_t)(pl.nsteps * bps) * 4 +
-           (size_t)pl.max_rows * wp * 4 + (size_t)PT * 4 + 16;
+           (size_t)pl.max_rows * wp * 4 + (size_t)PT * 4 * (1 + fuse_rows) + 16;
 }
 
-static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, MfmaPlan *pl)
+static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fuse_rows, MfmaPlan *pl)
 {
     const int bps = fmt == 0 ? 1 : 2, bpb = fmt == 0 ? 32 : 16;
     const int rows = worst_region_rows(g, PT, PT);
@@ -276,7 +364,7 @@ static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, MfmaPl
         pl->tap_jump = (ccw == g.cw) ? 0 : (g.cw - ccw) / bps;
         if (region >= (1ll << 30)) continue;
         pl->region_bytes = (int)region;
-        const long long total = (long long)plan_lds_bytes(*pl, bps, g.wp, PT);
+        const long long total = (long long)plan_lds_bytes(*pl, bps, g.wp, PT, fuse_rows);
         const bool last = (ccw == 1) || (bps == 2 && ccw == 2);
         if (total > lds_budget && !last) continue;
         if (total > LDS_LIMIT) return false;
@@ -297,16 +385,28 @@ void set_mfma_tuning(int tile, int lds_budget)
     if (lds_budget > 0) g_lds_budget = lds_budget;
 }
 
-template <int FMT, int FW, int PW, int WF, int WP>
+// second kernel of the fused epilogue when the filters span several workgroups:
+// A_next[m] = (part[0][m] + part[1][m] + ...) / k_out, planes added in order
+__global__ __launch_bounds__(256) void sum_planes_kernel(const float *__restrict__ part, float *__restrict__ A_next,
+                                                        int m_total, int planes, float k_out)
+{
+    const int m = blockIdx.x * 256 + threadIdx.x;
+    if (m >= m_total) return;
+    float s = 0.0f;
+    for (int p = 0; p < planes; ++p) s += part[(size_t)p * m_total + m];
+    A_next[m] = s / k_out;
+}
+
+template <int FMT, int FW, int PW, int WF, int WP, bool FUSE>
 static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const float *K, const float *A,
                               const float *alpha, float *out, int32_t *dot_out, const ConvGeom &g,
-                              hipStream_t stream)
+                              hipStream_t stream, const FuseArgs *fz)
 {
     constexpr int FT = 32 * FW * WF, PT = 32 * PW * WP;
     MfmaPlan pl;
-    if (!make_plan(g, PT, FMT, g_lds_budget, &pl)) return XNOR_ERR_UNSUPPORTED;
-    const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2, g.wp, PT);
-    auto kern = conv_mfma_kernel<FMT, FW, PW, WF, WP>;
+    if (!make_plan(g, PT, FMT, g_lds_budget, FUSE ? WF + FT / 32 : 0, &pl)) return XNOR_ERR_UNSUPPORTED;
+    const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2, g.wp, PT, FUSE ? WF + FT / 32 : 0);
+    auto kern = conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE>;
     static bool attr_done = false;   // per instantiation
     if (!attr_done) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -319,14 +419,20 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     const size_t img_bytes = FMT == 0 ? wimg_i8_bytes(g.k_out, g.c, g.taps) : wimg_f4_bytes(g.k_out, g.c, g.taps);
     if (img_bytes > 0x7fffffffull) return XNOR_ERR_UNSUPPORTED;
     kern<<<grid, block, lds, stream>>>(xbits, reinterpret_cast<const v4i *>(wimg), (uint32_t)img_bytes, K, A, alpha,
-                                       out, dot_out, g, pl);
-    return hip_status(hipGetLastError());
+                                       out, dot_out, g, pl, FUSE ? *fz : FuseArgs{});
+    if (xnor_status s = hip_status(hipGetLastError())) return s;
+    if (FUSE && grid.y > 1) {
+        sum_planes_kernel<<<dim3((unsigned)((g.m_total + 255) / 256)), dim3(256), 0, stream>>>(
+            fz->workspace, fz->A_next, g.m_total, (int)grid.y, (float)g.k_out);
+        return hip_status(hipGetLastError());
+    }
+    return XNOR_OK;
 }
 
 template <int FMT>
 static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const float *K, const float *A,
                               const float *alpha, float *out, int32_t *dot_out, const ConvGeom &g,
-                              hipStream_t stream)
+                              hipStream_t stream, const FuseArgs *fz)
 {
     int tile = g_tile_override;
     if (tile == 0 || tile == 10) {
@@ -344,42 +450,53 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
             else if (wgs(128, 64) >= cus) tile = 13;
             else tile = 14;       // 128 x 32 (measured ahead of 64 x 64 at equal workgroup count)
         }
+        // fused epilogue: a workgroup that holds every filter writes whole sign words runs and the
+        // final A itself (no partial sums, no second kernel); measured ahead for 129..256 filters
+        if (fz && g_tile_override == 0 && g.k_out > 128 && g.k_out <= 256) tile = 4;
     }
-#define XNOR_TILE(ID, FW, PW, WF, WP) \
-    case ID: return launch_cfg<FMT, FW, PW, WF, WP>(xbits, wimg, K, A, alpha, out, dot_out, g, stream)
+    // the fused epilogue is built for the tiles marked F (the default choices and the wide-filter ones)
+#define XNOR_TILE(ID, FW, PW, WF, WP)                                                                     \
+    case ID:                                                                                              \
+        if (fz) return XNOR_ERR_UNSUPPORTED;                                                              \
+        return launch_cfg<FMT, FW, PW, WF, WP, false>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, nullptr)
+#define XNOR_TILE_F(ID, FW, PW, WF, WP)                                                                   \
+    case ID:                                                                                              \
+        if (fz) return launch_cfg<FMT, FW, PW, WF, WP, true>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, fz); \
+        return launch_cfg<FMT, FW, PW, WF, WP, false>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, nullptr)
     switch (tile) {
-        XNOR_TILE(1, 2, 2, 2, 2);   // 128 filters x 128 pixels
-        XNOR_TILE(2, 2, 2, 1, 4);   //  64 x 256
-        XNOR_TILE(3, 2, 4, 2, 2);   // 128 x 256
-        XNOR_TILE(4, 2, 3, 4, 1);   // 256 x  96
-        XNOR_TILE(5, 2, 4, 4, 1);   // 256 x 128
-        XNOR_TILE(6, 2, 6, 4, 1);   // 256 x 192
-        XNOR_TILE(7, 4, 2, 2, 2);   // 256 x 128
-        XNOR_TILE(8, 2, 4, 1, 4);   //  64 x 512
-        XNOR_TILE(9, 4, 4, 2, 2);   // 256 x 256
-        XNOR_TILE(11, 1, 2, 2, 2);  //  64 x 128
-        XNOR_TILE(12, 1, 1, 2, 2);  //  64 x  64
-        XNOR_TILE(13, 1, 2, 4, 1);  // 128 x  64
-        XNOR_TILE(14, 1, 1, 4, 1);  // 128 x  32
+        XNOR_TILE_F(1, 2, 2, 2, 2);   // 128 filters x 128 pixels
+        XNOR_TILE_F(2, 2, 2, 1, 4);   //  64 x 256
+        XNOR_TILE(3, 2, 4, 2, 2);     // 128 x 256
+        XNOR_TILE_F(4, 2, 3, 4, 1);   // 256 x  96
+        XNOR_TILE_F(5, 2, 4, 4, 1);   // 256 x 128
+        XNOR_TILE(6, 2, 6, 4, 1);     // 256 x 192
+        XNOR_TILE(7, 4, 2, 2, 2);     // 256 x 128
+        XNOR_TILE(8, 2, 4, 1, 4);     //  64 x 512
+        XNOR_TILE(9, 4, 4, 2, 2);     // 256 x 256
+        XNOR_TILE_F(11, 1, 2, 2, 2);  //  64 x 128
+        XNOR_TILE(12, 1, 1, 2, 2);    //  64 x  64
+        XNOR_TILE_F(13, 1, 2, 4, 1);  // 128 x  64
+        XNOR_TILE_F(14, 1, 1, 4, 1);  // 128 x  32
     default: return XNOR_ERR_UNSUPPORTED;
     }
 #undef XNOR_TILE
+#undef XNOR_TILE_F
 }
 
 xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
                              const float *alpha, float *out, int32_t *dot_out,
-                             const ConvGeom &g, hipStream_t stream)
+                             const ConvGeom &g, hipStream_t stream, const FuseArgs *fz)
 {
-    if (g_tile_override == 10) {      // persistent kernel where its LDS plan fits, tiled kernel otherwise
+    if (g_tile_override == 10 && !fz) {      // persistent kernel where its LDS plan fits, tiled kernel otherwise
         const xnor_status s = launch_conv_mfma_pipe(fmt, xbits, wmfma, K, A, alpha, out, dot_out, g, stream);
         if (s != XNOR_ERR_UNSUPPORTED) return s;
     }
     // float accumulation of the 4-bit path is exact while every sum stays below 2^24
     if (fmt != 0 && (long long)g.c * g.taps >= (1ll << 24)) return XNOR_ERR_UNSUPPORTED;
     const uint8_t *img = static_cast<const uint8_t *>(wmfma);
-    if (fmt == 0) return launch_fmt<0>(xbits, img, K, A, alpha, out, dot_out, g, stream);
+    if (fmt == 0) return launch_fmt<0>(xbits, img, K, A, alpha, out, dot_out, g, stream, fz);
     img += wimg_i8_bytes(g.k_out, g.c, g.taps);
-    return launch_fmt<1>(xbits, img, K, A, alpha, out, dot_out, g, stream);
+    return launch_fmt<1>(xbits, img, K, A, alpha, out, dot_out, g, stream, fz);
 }
 
 }  // namespace xnor

@@ -53,6 +53,7 @@ template <> struct Enc<0> {                    // int8
         return __builtin_amdgcn_mfma_i32_32x32x32_i8(w, x, c, 0, 0, 0);
     }
     static __device__ __forceinline__ int to_int(acc_t a, int v) { return a[v]; }
+    static __device__ __forceinline__ float to_float(acc_t a, int v) { return (float)a[v]; }
     // 4 sign bits -> 4 int8: bit 1 -> 0x01, bit 0 -> 0xFF
     static __device__ __forceinline__ uint32_t widen4(uint32_t nibble) {
         const uint32_t t = __umul24(nibble, 0x00204081u) & 0x01010101u;     // bit i -> byte i
@@ -93,6 +94,7 @@ template <> struct Enc<1> {                    // 4-bit float E2M1
         return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(w8, x8, c, 4, 4, 0, 127, 0, 127);
     }
     static __device__ __forceinline__ int to_int(acc_t a, int v) { return (int)a[v]; }
+    static __device__ __forceinline__ float to_float(acc_t a, int v) { return a[v]; }   // an exact integer already
     // 8 sign bits -> 8 nibbles: bit 1 -> 0x2 (+1.0), bit 0 -> 0xA (-1.0)
     static __device__ __forceinline__ uint32_t widen8(uint32_t byte) {
         uint32_t x = byte;                                   // bit i -> bit 4i by three shift-or steps

@@ -89,10 +89,23 @@ __host__ __device__ inline size_t wimg_pop_bytes(int k_out, int c, int taps)
     return (size_t)((k_out + 31) / 32) * (size_t)taps * (size_t)((c + 31) / 32) * 128u;
 }
 
-// fmt 0: int8 operands, fmt 1: 4-bit float operands (both images live in the wmfma buffer)
+// Next block's BatchNorm + BinActiv applied in the convolution's epilogue (block order of sec. 3.2):
+// z = fmaf(y, bn_scale[k], bn_shift[k]) (z = y without normalisation), sign bits of z packed over the
+// filters into xbits_next[pixel][ceil(k_out/32)], A_next[pixel] = sum_k |z| / k_out.  A workgroup sums
+// |z| over its own filters; when the filters span several workgroups the partial sums go to
+// `workspace` ([filter tile][pixel]) and a second small kernel adds them in order.
+struct FuseArgs {
+    const float *bn_scale, *bn_shift;   // per filter, both NULL or both set
+    uint32_t *xbits_next;
+    float *A_next;
+    float *workspace;                   // >= ceil(k_out/32) * m_total floats
+};
+
+// fmt 0: int8 operands, fmt 1: 4-bit float operands (both images live in the wmfma buffer).
+// fz != NULL selects the fused epilogue above; `out` may then be NULL.
 xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
                              const float *alpha, float *out, int32_t *dot_out,
-                             const ConvGeom &g, hipStream_t stream);
+                             const ConvGeom &g, hipStream_t stream, const FuseArgs *fz = nullptr);
 void set_mfma_tuning(int tile, int lds_budget);
 // persistent, role-split form of the same kernel (conv_mfma_pipe.hip)
 xnor_status launch_conv_mfma_pipe(int fmt, const uint32_t *xbits, const void *wmfma, const float *K,

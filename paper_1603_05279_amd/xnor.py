@@ -18,7 +18,8 @@ ALGOS = {"auto": XNOR_ALGO_AUTO, "popcount": XNOR_ALGO_POPCOUNT, "mfma_i8": XNOR
 EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor_wmfma_bytes",
            "xnor_set_tuning",
            "xnor_binarize_pack", "xnor_compute_K", "xnor_binactiv", "xnor_pack_weights",
-           "xnor_conv2d", "xnor_linear"]
+           "xnor_conv2d", "xnor_linear",
+           "xnor_conv2d_binactiv_workspace_bytes", "xnor_conv2d_binactiv"]
 
 
 class XnorError(RuntimeError):
@@ -66,6 +67,10 @@ def lib():
         L.xnor_conv2d.restype = ip
         L.xnor_linear.argtypes = [vp, vp, vp, vp, vp, vp, vp, ip, ip, ip, ip, vp]
         L.xnor_linear.restype = ip
+        L.xnor_conv2d_binactiv_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc)]
+        L.xnor_conv2d_binactiv_workspace_bytes.restype = ctypes.c_size_t
+        L.xnor_conv2d_binactiv.argtypes = [vp] * 12 + [ctypes.POINTER(ConvDesc), ip, vp]
+        L.xnor_conv2d_binactiv.restype = ip
         _lib = L
     return _lib
 
@@ -162,6 +167,20 @@ def xnor_linear(xbits, wbits, wmfma, Krow, alpha, out, dot_out, batch, in_featur
         _ptr(xbits, torch.int32), _ptr(wbits, torch.int32), _ptr(wmfma, torch.uint8),
         _ptr(Krow, torch.float32), _ptr(alpha, torch.float32), _ptr(out, torch.float32),
         _ptr(dot_out, torch.int32), batch, in_features, out_features, int(algo), _stream(stream)))
+
+
+def conv2d_binactiv_workspace_bytes(desc):
+    return int(lib().xnor_conv2d_binactiv_workspace_bytes(ctypes.byref(desc)))
+
+
+def xnor_conv2d_binactiv(xbits, wbits, wmfma, K, A, alpha, bn_scale_next, bn_shift_next, xbits_next, A_next,
+                         out, workspace, desc, algo=XNOR_ALGO_AUTO, stream=None):
+    _check("xnor_conv2d_binactiv", lib().xnor_conv2d_binactiv(
+        _ptr(xbits, torch.int32), _ptr(wbits, torch.int32), _ptr(wmfma, torch.uint8),
+        _ptr(K, torch.float32), _ptr(A, torch.float32), _ptr(alpha, torch.float32),
+        _ptr(bn_scale_next, torch.float32), _ptr(bn_shift_next, torch.float32),
+        _ptr(xbits_next, torch.int32), _ptr(A_next, torch.float32), _ptr(out, torch.float32),
+        _ptr(workspace, torch.uint8), ctypes.byref(desc), int(algo), _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------

@@ -272,6 +272,29 @@ def test_batchnorm_moves_the_sign_threshold():
     assert xo.sign(xo.batchnorm(x, s, t)).reshape(-1).tolist() == [-1, -1, 1, 1]
 
 
+def test_binactiv_of_a_block_output_has_a_closed_form_from_the_integers():
+    # Without normalisation in between, the next block binarises out = dot*K*alpha with K, alpha > 0:
+    # the sign is that of the integer (0 -> +1) and A = K * mean_k(|dot_k| * alpha_k) per pixel.
+    rng = np.random.default_rng(23)
+    x = rng.standard_normal((2, 5, 6, 7)).astype(np.float32)
+    w = rng.standard_normal((6, 5, 3, 3)).astype(np.float32)
+    r = xo.binary_conv2d(x, w, (1, 1), (1, 1))
+    y, s, A = xo.binactiv(r["out"])
+    assert np.array_equal(y, r["out"])
+    assert (r["K"] > 0).all() and (r["alpha"] > 0).all()
+    assert np.array_equal(s, np.where(r["dot"] >= 0, 1, -1).astype(np.int8))
+    A_ints = r["K"] * (np.abs(r["dot"]).astype(np.float64) * r["alpha"][None, :, None, None]).mean(axis=1)
+    np.testing.assert_allclose(A, A_ints, rtol=1e-6)
+    # with normalisation the threshold moves: z >= 0  <=>  out >= -shift/scale (scale > 0)
+    scale = rng.uniform(0.5, 1.5, 6).astype(np.float32)
+    shift = (0.2 * rng.standard_normal(6)).astype(np.float32)
+    z, sz, Az = xo.binactiv(r["out"], scale, shift)
+    thr = (-shift.astype(np.float64) / scale.astype(np.float64))[None, :, None, None]
+    clear = np.abs(r["out"] - thr) > 1e-5          # away from the threshold the closed form decides
+    assert np.array_equal(sz[clear], np.where(r["out"] >= thr, 1, -1).astype(np.int8)[clear])
+    np.testing.assert_allclose(Az, np.abs(z.astype(np.float64)).mean(axis=1), rtol=1e-12)
+
+
 # ----------------------------------------------------------- op-count model (sec. 4.1)
 def test_speedup_model_matches_printed_value():
     rows = [l.split() for l in open(os.path.join(GOLDEN, "speedup_model.txt")) if l.strip() and not l.startswith("#")]
