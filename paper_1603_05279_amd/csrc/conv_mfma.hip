@@ -452,6 +452,8 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
         }
         // fused epilogue: a workgroup that holds every filter writes whole sign words runs and the
         // final A itself (no partial sums, no second kernel); measured ahead for 129..256 filters
+        // (all-filter tiles for 384 and 512 filters, 3x2 and 4x2 blocks per wave, measured behind the
+        // default with its second launch)
         if (fz && g_tile_override == 0 && g.k_out > 128 && g.k_out <= 256) tile = 4;
     }
     // the fused epilogue is built for the tiles marked F (the default choices and the wide-filter ones)
