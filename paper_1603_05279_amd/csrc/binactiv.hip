@@ -15,15 +15,22 @@ template <bool WRITE_BITS, bool WRITE_A, bool BN>
 __global__ __launch_bounds__(256) void binactiv_kernel(
     const float *__restrict__ x, const float *__restrict__ bn_scale,
     const float *__restrict__ bn_shift, uint32_t *__restrict__ xbits, float *__restrict__ A,
-    int c, int hw, int cw, int tiles_per_image)
+    int c, int hw, int cw, int tiles_per_image, int nblocks)
 {
+    // Workgroups are dealt to the 8 XCDs round-robin by index.  Neighbouring pixel tiles share the
+    // cache lines that straddle their boundary (channel rows are not line aligned), so within
+    // every window of 64 tiles each XCD takes a run of 8 consecutive ones: the shared line is then
+    // a hit in that XCD's own L2, while all XCDs still stream through the same region of memory.
+    // The last, incomplete window keeps the plain order (runs would load the XCDs unevenly there).
+    const unsigned b = blockIdx.x, win = (b >> 6) << 6;
+    const int blk = (int)(win + 64u <= (unsigned)nblocks ? win + ((b & 7u) << 3) + ((b >> 3) & 7u) : b);
     extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
     float(*part)[64] = reinterpret_cast<float(*)[64]>(smem);            // [4][64]
     uint8_t *wbytes = smem + 4 * 64 * sizeof(float);                    // [64 px][cw words][4 bytes]
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
-    const int img = blockIdx.x / tiles_per_image;
-    const int tile = blockIdx.x - img * tiles_per_image;
+    const int img = blk / tiles_per_image;
+    const int tile = blk - img * tiles_per_image;
     const int p0 = tile * 64;
     const int p = p0 + lane;
     const bool live = p < hw;
@@ -122,11 +129,11 @@ xnor_status launch_binactiv(const float *x, const float *bn_scale, const float *
     }
     const int tiles = (hw + 63) / 64;
     const long long blocks = (long long)n * tiles;
-    if (blocks > 0x7fffffffLL) return XNOR_ERR_SHAPE;
+    if (blocks > 0x7ffffff0LL) return XNOR_ERR_SHAPE;
     const size_t lds = 4 * 64 * sizeof(float) + (size_t)64 * cw * 4;
     if (lds > 64 * 1024) return XNOR_ERR_UNSUPPORTED;       // more than ~500k channels per pixel
     dim3 grid((unsigned)blocks), block(256);
-#define XNOR_BA(B, AA, N) binactiv_kernel<B, AA, N><<<grid, block, lds, stream>>>(x, bn_scale, bn_shift, xbits, A, c, hw, cw, tiles)
+#define XNOR_BA(B, AA, N) binactiv_kernel<B, AA, N><<<grid, block, lds, stream>>>(x, bn_scale, bn_shift, xbits, A, c, hw, cw, tiles, (int)blocks)
     const bool bn = bn_scale != nullptr;
     if (xbits && A) { if (bn) XNOR_BA(true, true, true); else XNOR_BA(true, true, false); }
     else if (xbits) { if (bn) XNOR_BA(true, false, true); else XNOR_BA(true, false, false); }

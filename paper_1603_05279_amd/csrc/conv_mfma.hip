@@ -52,12 +52,20 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     float *asum_lds = ktile + PT;                                                // [WF][PT], fused epilogue only
     uint32_t *wtile_lds = reinterpret_cast<uint32_t *>(asum_lds + WF * PT);      // [PT][FT/32], fused epilogue only
 
+    // Workgroups go to the 8 XCDs round-robin by index; within every window of 64 pixel tiles each
+    // XCD takes a run of 8 consecutive ones, so that the output lines two neighbouring tiles both
+    // write in part (and the input rows they share) meet in one XCD's L2.
+    // (the last, incomplete window keeps the plain order: runs would load the XCDs unevenly there)
+    const uint32_t bx = blockIdx.x;
+    const uint32_t win = (bx >> 6) << 6;
+    const uint32_t ptile = win + 64u <= (uint32_t)pl.ptiles ? win + ((bx & 7u) << 3) + ((bx >> 3) & 7u) : bx;
+    if (ptile >= (uint32_t)pl.ptiles) return;
     XNOR_TL(0);
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int l32 = lane & 31, half = lane >> 5;
     const int wf = wave % WF, wp = wave / WF;
-    const uint32_t m0 = blockIdx.x * (uint32_t)PT;
+    const uint32_t m0 = ptile * (uint32_t)PT;
     const int f0 = blockIdx.y * FT;
     const uint32_t howo = (uint32_t)(g.ho * g.wo);
     const int ccw = pl.cc_words;
@@ -414,7 +422,8 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
             return XNOR_ERR_HIP;
         attr_done = true;
     }
-    dim3 grid((unsigned)((g.m_total + PT - 1) / PT), (unsigned)((g.k_out + FT - 1) / FT)), block(64 * WF * WP);
+    pl.ptiles = (g.m_total + PT - 1) / PT;
+    dim3 grid((unsigned)pl.ptiles, (unsigned)((g.k_out + FT - 1) / FT)), block(64 * WF * WP);
     if (grid.y > 65535u) return XNOR_ERR_UNSUPPORTED;
     const size_t img_bytes = FMT == 0 ? wimg_i8_bytes(g.k_out, g.c, g.taps) : wimg_f4_bytes(g.k_out, g.c, g.taps);
     if (img_bytes > 0x7fffffffull) return XNOR_ERR_UNSUPPORTED;

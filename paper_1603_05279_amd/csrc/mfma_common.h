@@ -17,6 +17,7 @@ struct MfmaPlan {
     int region_bytes; // max_rows * wp * ps
     int nsteps;       // K-steps per chunk
     int tap_jump;     // weight records skipped when a chunk moves to the next tap
+    int ptiles;       // pixel tiles of the launch (the grid is padded beyond it)
     FastDiv div_wp, div_hp, div_ccw, div_cw;
 };
 
