@@ -33,7 +33,7 @@ __device__ long long *g_timeline = nullptr;
 #endif
 
 // Accumulator tiles of up to 8 result blocks leave room for two waves per SIMD (256 registers each).
-template <int FMT, int FW, int PW, int WF, int WP, bool FUSE>
+template <int FMT, int FW, int PW, int WF, int WP, bool FUSE, bool LINEAR>
 __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfma_kernel(
     const uint32_t *__restrict__ xbits, const v4i *__restrict__ wimg, uint32_t wimg_bytes,
     const float *__restrict__ K, const float *__restrict__ A, const float *__restrict__ alpha,
@@ -46,8 +46,8 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     constexpr int PT = 32 * PW * WP;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     int *rowinfo = reinterpret_cast<int *>(lds + pl.region_bytes);
-    int *xoff_tab = rowinfo + pl.max_rows;     // [nsteps * BPS]
-    float *a_lds = reinterpret_cast<float *>(xoff_tab + pl.nsteps * E::BPS);   // [max_rows * wp], halo = 0
+    int *xoff_tab = rowinfo + pl.max_rows;     // [(nsteps + KLOOP_TABLE_PAD) * BPS]
+    float *a_lds = reinterpret_cast<float *>(xoff_tab + (pl.nsteps + KLOOP_TABLE_PAD) * E::BPS);   // [max_rows * wp], halo = 0
     float *ktile = a_lds + pl.max_rows * g.wp;                                   // [PT]
     float *asum_lds = ktile + PT;                                                // [WF][PT], fused epilogue only
     uint32_t *wtile_lds = reinterpret_cast<uint32_t *>(asum_lds + WF * PT);      // [PT][FT/32], fused epilogue only
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     // block b = tap * ccw + word  ->  (dy*wp + dx)*ps + word*BPB
     {
         const int nblk = g.taps * ccw;
-        for (int b = tid; b < nsteps * E::BPS; b += NT) {
+        for (int b = tid; b < (nsteps + KLOOP_TABLE_PAD) * E::BPS; b += NT) {     // padding repeats the last block
             const uint32_t bb = (uint32_t)min(b, nblk - 1);
             const uint32_t t = pl.div_ccw.div(bb);
             const uint32_t wl = bb - t * ccw;
@@ -200,8 +200,13 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
 
         // ---- software-pipelined K loop over this chunk's steps --------------------------------
         // record of step s: rec0 + s + (s / steps_per_tap) * tap_jump
-        mfma_kloop<E, FW, PW, 3, 1>(acc, lds, pbase, xoff_tab, tab_lane, wrsrc, wlane, wrec0, zero_rec,
-                              wbase / E::BPS, nsteps, steps_per_tap, pl.tap_jump);
+        if constexpr (LINEAR) {      // the chunk holds every channel word: consecutive records
+            WStreamLinear<FW> ws(wimg, wrec0, 0, nsteps, wlane);
+            mfma_kloop<E, FW, PW, 5, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps);
+        } else {
+            WStreamChunked<FW> ws(wrsrc, wrec0, zero_rec, wbase / E::BPS, nsteps, steps_per_tap, pl.tap_jump, wlane);
+            mfma_kloop<E, FW, PW, 5, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps);
+        }
     }
 
     XNOR_TL(3);
@@ -350,7 +355,7 @@ static const int LDS_LIMIT = 160 * 1024;
 // fuse_rows: rows of PT words for the fused epilogue's |z| sums and sign words (0 without it)
 static size_t plan_lds_bytes(const MfmaPlan &pl, int bps, int wp, int PT, int fuse_rows)
 {
-    return (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 + (size_t)(pl.nsteps * bps) * 4 +
+    return (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 + (size_t)((pl.nsteps + KLOOP_TABLE_PAD) * bps) * 4 +
            (size_t)pl.max_rows * wp * 4 + (size_t)PT * 4 * (1 + fuse_rows) + 16;
 }
 
@@ -414,13 +419,16 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     MfmaPlan pl;
     if (!make_plan(g, PT, FMT, g_lds_budget, FUSE ? WF + FT / 32 : 0, &pl)) return XNOR_ERR_UNSUPPORTED;
     const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2, g.wp, PT, FUSE ? WF + FT / 32 : 0);
-    auto kern = conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE>;
-    static bool attr_done = false;   // per instantiation
-    if (!attr_done) {
+    // two builds of every tiling: weight records consecutive (one chunk holds all channel words) or not
+    const bool linear = pl.tap_jump == 0;
+    auto kern = linear ? conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, true>
+                       : conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, false>;
+    static bool attr_done[2] = {false, false};   // per instantiation
+    if (!attr_done[linear]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT) != hipSuccess)
             return XNOR_ERR_HIP;
-        attr_done = true;
+        attr_done[linear] = true;
     }
     pl.ptiles = (g.m_total + PT - 1) / PT;
     dim3 grid((unsigned)pl.ptiles, (unsigned)((g.k_out + FT - 1) / FT)), block(64 * WF * WP);

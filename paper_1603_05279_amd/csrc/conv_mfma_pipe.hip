@@ -37,7 +37,7 @@ struct PipePlan {
     FastDiv div_wp, div_hp, div_ccw;
 };
 
-template <int FMT, int FW, int PW, int WF>
+template <int FMT, int FW, int PW, int WF, bool LINEAR>
 __global__ __launch_bounds__(512, 2) void conv_mfma_pipe_kernel(
     const uint32_t *__restrict__ xbits, const v4i *__restrict__ wimg, uint32_t wimg_bytes,
     const float *__restrict__ K, const float *__restrict__ A, const float *__restrict__ alpha,
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(512, 2) void conv_mfma_pipe_kernel(
     // ---------------------------------------------------------------- prologue
     {   // LDS offset of every channel block of a chunk relative to a pixel's window origin
         const int nblk = g.taps * ccw;
-        for (int b = tid; b < pl.nsteps * E::BPS; b += 512) {
+        for (int b = tid; b < (pl.nsteps + KLOOP_TABLE_PAD) * E::BPS; b += 512) {
             const uint32_t bb = (uint32_t)min(b, nblk - 1);
             const uint32_t t = pl.div_ccw.div(bb);
             const uint32_t wl = bb - t * ccw;
@@ -297,8 +297,14 @@ __global__ __launch_bounds__(512, 2) void conv_mfma_pipe_kernel(
             }
             if (st == 0) XNOR_TLP(8, 0);
             if (st == 1) XNOR_TLP(10, 0);
-            mfma_kloop<E, FW, PW, 5, 2>(acc, lds + pl.off_x[xcur], pbase, xoff_tab, tab_lane, wrsrc, wlane, wrec0,
-                                  zero_rec, (ch * ccw) / E::BPS, pl.nsteps, steps_per_tap, pl.tap_jump);
+            if constexpr (LINEAR) {
+                WStreamLinear<FW> ws(wimg, wrec0, 0, pl.nsteps, wlane);
+                mfma_kloop<E, FW, PW, 5, 2>(acc, lds + pl.off_x[xcur], pbase, xoff_tab, tab_lane, ws, pl.nsteps);
+            } else {
+                WStreamChunked<FW> ws(wrsrc, wrec0, zero_rec, (ch * ccw) / E::BPS, pl.nsteps, steps_per_tap,
+                                      pl.tap_jump, wlane);
+                mfma_kloop<E, FW, PW, 5, 2>(acc, lds + pl.off_x[xcur], pbase, xoff_tab, tab_lane, ws, pl.nsteps);
+            }
             if (st == 0) XNOR_TLP(9, 0);
             if (st == 1) XNOR_TLP(11, 0);
             if (completes) {
@@ -378,7 +384,7 @@ static bool make_pipe_plan(const ConvGeom &g, int fmt, int PT, int FG, PipePlan 
         pl->off_ktile[1] = (int)off; off += PT * 4;
         pl->off_obase[0] = (int)off; off += PT * 8;
         pl->off_obase[1] = (int)off; off += PT * 8;
-        pl->off_xoff = (int)off; off += ((long long)nsteps * bps * 4 + 31) / 16 * 16;
+        pl->off_xoff = (int)off; off += ((long long)(nsteps + KLOOP_TABLE_PAD) * bps * 4 + 31) / 16 * 16;
         pl->off_alpha = (int)off; off += ((long long)g.k_out * 4 + 15) / 16 * 16;
         if (off > PIPE_LDS_LIMIT) continue;
         pl->cc_words = ccw;
@@ -423,13 +429,14 @@ static xnor_status launch_pipe_cfg(const uint32_t *xbits, const void *wimg, size
     PipePlan pl;
     size_t lds = 0;
     if (!make_pipe_plan(g, FMT, PT, FG, &pl, &lds)) return XNOR_ERR_UNSUPPORTED;
-    auto kern = conv_mfma_pipe_kernel<FMT, FW, PW, WF>;
-    static bool attr_done = false;
-    if (!attr_done) {
+    const bool linear = pl.tap_jump == 0;
+    auto kern = linear ? conv_mfma_pipe_kernel<FMT, FW, PW, WF, true> : conv_mfma_pipe_kernel<FMT, FW, PW, WF, false>;
+    static bool attr_done[2] = {false, false};
+    if (!attr_done[linear]) {
         if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, PIPE_LDS_LIMIT) != hipSuccess)
             return XNOR_ERR_HIP;
-        attr_done = true;
+        attr_done[linear] = true;
     }
     const int wgs = min(cu_count(), pl.total_frags);
     kern<<<dim3((unsigned)wgs), dim3(512), lds, stream>>>(xbits, reinterpret_cast<const v4i *>(wimg),

@@ -130,43 +130,93 @@ constexpr int ring_lcm(int a, int b)
     return m;
 }
 
-// One chunk's K loop of a wave: acc[i][j] += W(filter block i, step s) x X(pixel block j, step s)
-// for s = 0 .. nsteps-1.  Weight records are consumed in order: +1 per step, +tap_jump more when a
-// chunk that holds only part of the channels moves to the next tap; steps past the end multiply by
-// the all-zero weight record, so the unrolled body needs no branches and the prefetch depth never
-// drops.  Operands are requested DW steps (weights: buffer loads with a scalar offset, L2 latency)
-// and DX steps (activations: LDS, through the per-step offset table) ahead of their use and live in
-// register rings of DW+1 and DX+1 slots; the body is unrolled until both rings are back at slot 0.
-// The scheduling barriers pin the order written here (next operands requested, then the current
-// step's matrix instructions interleaved with those requests), which the compiler otherwise
-// regroups into one burst of loads followed by one burst of MFMAs with the latencies exposed.
-template <class E, int FW, int PW, int DW, int DX>
-__device__ __forceinline__ void mfma_kloop(typename E::acc_t (&acc)[FW][PW], const uint8_t *lds_x,
-                                           const int (&pbase)[PW], const int *xoff_tab, int tab_lane,
-                                           __amdgpu_buffer_rsrc_t wrsrc, int wlane, const int (&wrec0)[FW],
-                                           int zero_rec, int rec_start, int nsteps, int steps_per_tap,
-                                           int tap_jump)
-{
-    constexpr int RW = DW + 1, RX = DX + 1;
-    constexpr int TURN = ring_lcm(RW, RX);     // sub-steps after which both rings are back at slot 0
-    static_assert(RX <= RW && TURN <= 8 && TURN % 2 == 0, "unrolled turn: even, at most 8 sub-steps");
-    int w_rec = rec_start, w_cnt = 0, w_left = nsteps;
-    auto load_w = [&](v4i (&dst)[FW]) {
-        const int live = w_left > 0 ? 1 : 0;   // past the end: the all-zero record
+// Steps the offset table is padded by beyond the last K-step (copies of the last entry): operand
+// prefetches run ahead of the loop's end by at most one turn plus the activation depth.
+constexpr int KLOOP_TABLE_PAD = 12;
+
+// Weight record stream of a chunk that holds every channel word: the records of a filter block are
+// consecutive, so each block gets its own buffer resource covering exactly nsteps records and one
+// scalar offset advances by 1 KiB per step.  Requests past the end fall outside the resource and
+// return zeros by the buffer bounds check: no bookkeeping in the loop.
+template <int FW> struct WStreamLinear {
+    __amdgpu_buffer_rsrc_t rsrc[FW];
+    int soff, wlane;
+    __device__ __forceinline__ WStreamLinear(const v4i *wimg, const int (&wrec0)[FW], int rec_start, int nsteps,
+                                             int wlane_)
+        : soff(0), wlane(wlane_)
+    {
+#pragma unroll
+        for (int i = 0; i < FW; ++i)
+            rsrc[i] = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<v4i *>(wimg + (size_t)(wrec0[i] + rec_start) * 64), 0, nsteps * 1024, 0x00020000);
+    }
+    __device__ __forceinline__ void load(v4i (&dst)[FW])
+    {
+#pragma unroll
+        for (int i = 0; i < FW; ++i) {
+            const v4u r = __builtin_amdgcn_raw_buffer_load_b128(rsrc[i], wlane, soff, 0);
+            dst[i] = v4i{(int)r[0], (int)r[1], (int)r[2], (int)r[3]};
+        }
+        soff += 1024;
+    }
+};
+
+// Weight record stream of a chunk that holds part of the channel words: +1 record per step and
+// +tap_jump more when the chunk moves to the next tap; steps past the end read the all-zero record.
+// Branch-free scalar bookkeeping, so the loop body stays one basic block.
+template <int FW> struct WStreamChunked {
+    __amdgpu_buffer_rsrc_t rsrc;
+    int wrec0[FW];
+    int wlane, zero_rec, w_rec, w_cnt, w_left, steps_per_tap, tap_jump;
+    __device__ __forceinline__ WStreamChunked(__amdgpu_buffer_rsrc_t rsrc_, const int (&wrec0_)[FW], int zero_rec_,
+                                              int rec_start, int nsteps, int steps_per_tap_, int tap_jump_,
+                                              int wlane_)
+        : rsrc(rsrc_), wlane(wlane_), zero_rec(zero_rec_), w_rec(rec_start), w_cnt(0), w_left(nsteps),
+          steps_per_tap(steps_per_tap_), tap_jump(tap_jump_)
+    {
+#pragma unroll
+        for (int i = 0; i < FW; ++i) wrec0[i] = wrec0_[i];
+    }
+    __device__ __forceinline__ void load(v4i (&dst)[FW])
+    {
+        const int live = w_left > 0 ? 1 : 0;
 #pragma unroll
         for (int i = 0; i < FW; ++i) {
             const int rec = live ? wrec0[i] + w_rec : zero_rec;
-            const v4u r = __builtin_amdgcn_raw_buffer_load_b128(wrsrc, wlane, rec * 1024, 0);
+            const v4u r = __builtin_amdgcn_raw_buffer_load_b128(rsrc, wlane, rec * 1024, 0);
             dst[i] = v4i{(int)r[0], (int)r[1], (int)r[2], (int)r[3]};
         }
-        // branch-free bookkeeping (scalar selects), so the loop body stays one basic block
         w_left -= live;
         w_cnt += live;
         const int wrap = w_cnt == steps_per_tap ? 1 : 0;
         w_cnt = wrap ? 0 : w_cnt;
         w_rec += live + (wrap ? tap_jump : 0);
-    };
-    auto load_t = [&](int s) -> int { return xoff_tab[min(s, nsteps - 1) * E::BPS + tab_lane]; };
+    }
+};
+
+// One chunk's K loop of a wave: acc[i][j] += W(filter block i, step s) x X(pixel block j, step s)
+// for s = 0 .. nsteps-1, weights from the stream `ws` (one of the two above), activations from LDS
+// through the per-step offset table (padded by KLOOP_TABLE_PAD steps).  Operands are requested DW
+// steps (weights: buffer loads with a scalar offset, L2 latency) and DX steps (activations) ahead
+// of their use and live in register rings of DW+1 and DX+1 slots; the body is unrolled until both
+// rings are back at slot 0.  A wave issues one instruction every four cycles, so everything that is
+// not a matrix instruction competes with them for issue slots: the loop carries no address or
+// bounds arithmetic beyond one scalar add and PW vector adds per step.
+// The scheduling barriers pin the order written here (next operands requested, then the current
+// step's matrix instructions interleaved with those requests), which the compiler otherwise
+// regroups into one burst of loads followed by one burst of MFMAs with the latencies exposed.
+template <class E, int FW, int PW, int DW, int DX, class WS>
+__device__ __forceinline__ void mfma_kloop(typename E::acc_t (&acc)[FW][PW], const uint8_t *lds_x,
+                                           const int (&pbase)[PW], const int *xoff_tab, int tab_lane, WS &ws,
+                                           int nsteps)
+{
+    constexpr int RW = DW + 1, RX = DX + 1;
+    constexpr int TURN = ring_lcm(RW, RX);     // sub-steps after which both rings are back at slot 0
+    static_assert(RX <= RW && TURN <= 8 && TURN % 2 == 0, "unrolled turn: even, at most 8 sub-steps");
+    static_assert(TURN + DX + 2 <= KLOOP_TABLE_PAD, "offset table padding");
+    auto load_w = [&](v4i (&dst)[FW]) { ws.load(dst); };
+    const int *tab = xoff_tab + tab_lane;
+    auto load_t = [&](int s) -> int { return tab[s * E::BPS]; };
     auto load_x = [&](v4i (&dst)[PW], int toff) {
 #pragma unroll
         for (int j = 0; j < PW; ++j) dst[j] = *reinterpret_cast<const v4i *>(lds_x + pbase[j] + toff);
