@@ -44,6 +44,10 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     constexpr int NT = 64 * WF * WP;
     constexpr int FT = 32 * FW * WF;
     constexpr int PT = 32 * PW * WP;
+    // Weight prefetch depth.  Five steps pay off on long K loops; the 64-filter tiles serve layers
+    // with short K loops and many workgroups, and the fused epilogue needs registers of its own:
+    // there three steps keep more waves resident.
+    constexpr int DW = (FUSE || FT <= 64) ? 3 : 5;
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     int *rowinfo = reinterpret_cast<int *>(lds + pl.region_bytes);
     int *xoff_tab = rowinfo + pl.max_rows;     // [(nsteps + KLOOP_TABLE_PAD) * BPS]
@@ -202,10 +206,10 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         // record of step s: rec0 + s + (s / steps_per_tap) * tap_jump
         if constexpr (LINEAR) {      // the chunk holds every channel word: consecutive records
             WStreamLinear<FW> ws(wimg, wrec0, 0, nsteps, wlane);
-            mfma_kloop<E, FW, PW, 5, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps);
+            mfma_kloop<E, FW, PW, DW, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps);
         } else {
             WStreamChunked<FW> ws(wrsrc, wrec0, zero_rec, wbase / E::BPS, nsteps, steps_per_tap, pl.tap_jump, wlane);
-            mfma_kloop<E, FW, PW, 5, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps);
+            mfma_kloop<E, FW, PW, DW, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps);
         }
     }
 
@@ -227,6 +231,37 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         ppix[j] = mc - pimg[j] * howo;
         Km[j] = K ? K[mc] : ktile[pl_idx];
     }
+    // Float (and optional integer) results leave through buffer stores: the resource starts at the
+    // tile's first image, a lane's vector offset names its pixel (plus its half-wave's four rows),
+    // the filter row is a scalar offset, so a store needs no per-lane address arithmetic.  Dead
+    // pixel columns and rows past the last filter get an offset beyond the resource, which the
+    // buffer bounds check discards.  (The host refuses shapes whose tile span exceeds 2 GiB.)
+    const size_t img_elems = (size_t)g.k_out * howo;
+    const uint32_t span = (uint32_t)min((size_t)(g.n - (int)img_a) * img_elems * 4, (size_t)0x7ffffff0);
+    const uint32_t OOB = 0x80000000u;
+    uint32_t voff[PW];
+#pragma unroll
+    for (int j = 0; j < PW; ++j)
+        voff[j] = plive[j] ? (uint32_t)(((pimg[j] - img_a) * (uint32_t)img_elems + ppix[j] + 4u * half * howo) * 4u) : OOB;
+    const int wf_s = __builtin_amdgcn_readfirstlane(wf);
+    auto store_rows = [&](auto *dst, int i, int j, auto value_of) {
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(dst + (size_t)img_a * img_elems, 0, (int)span, 0x00020000);
+        const int row0 = f0 + (wf_s * FW + i) * 32;                 // wave-uniform
+        if (row0 + 32 <= g.k_out) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                __builtin_amdgcn_raw_buffer_store_b32(value_of(v), rs, (int)voff[j],
+                                                      (row0 + 8 * (v >> 2) + (v & 3)) * (int)howo * 4, 0);
+        } else {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int row = row0 + 8 * (v >> 2) + (v & 3);
+                const bool fin = row + 4 * half < g.k_out;
+                __builtin_amdgcn_raw_buffer_store_b32(value_of(v), rs, (int)(fin ? voff[j] : OOB),
+                                                      min(row, g.k_out - 1) * (int)howo * 4, 0);
+            }
+        }
+    };
     if constexpr (!FUSE) {
 #pragma unroll
     for (int i = 0; i < FW; ++i) {
@@ -234,26 +269,12 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         float al[16];
 #pragma unroll
         for (int v = 0; v < 16; ++v) al[v] = alpha[min(kb + 8 * (v >> 2) + (v & 3), g.k_out - 1)];
-        const bool whole = kb + 28 < g.k_out && !dot_out;      // all 16 rows in range
 #pragma unroll
         for (int j = 0; j < PW; ++j) {
-            if (!plive[j]) continue;
-            float *orow = out + ((size_t)pimg[j] * g.k_out + kb) * howo + ppix[j];
-            if (whole) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    orow[(size_t)(8 * (v >> 2) + (v & 3)) * howo] = E::to_float(acc[i][j], v) * Km[j] * al[v];
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int kr = 8 * (v >> 2) + (v & 3);
-                    if (kb + kr < g.k_out) {
-                        const int dot = E::to_int(acc[i][j], v);
-                        orow[(size_t)kr * howo] = (float)dot * Km[j] * al[v];
-                        if (dot_out) dot_out[((size_t)pimg[j] * g.k_out + kb + kr) * howo + ppix[j]] = dot;
-                    }
-                }
-            }
+            store_rows(out, i, j, [&](int v) {
+                return __builtin_bit_cast(uint32_t, E::to_float(acc[i][j], v) * Km[j] * al[v]);
+            });
+            if (dot_out) store_rows(dot_out, i, j, [&](int v) { return (uint32_t)E::to_int(acc[i][j], v); });
         }
     }
     } else {
@@ -273,19 +294,18 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         const int fblk = f0 / 32 + wf * FW + i;
         const int kb = fblk * 32 + 4 * half;
         float al[16], bs[16], bb[16];
-        uint32_t bit[16];                         // the row's bit in the sign word, 0 past the last filter
         const bool whole = kb + 28 < g.k_out;     // all 16 rows of this lane exist (uniform per half-wave pair)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int kr = 8 * (v >> 2) + (v & 3);             // row within this half's 16
-            const int kc = min(kb + kr, g.k_out - 1);
+            const int kc = min(kb + 8 * (v >> 2) + (v & 3), g.k_out - 1);
             al[v] = alpha[kc];
             bs[v] = has_bn ? fz.bn_scale[kc] : 1.0f;
             bb[v] = has_bn ? fz.bn_shift[kc] : 0.0f;
-            bit[v] = kb + kr < g.k_out ? 1u << (kr + 4 * half) : 0u;
         }
 #pragma unroll
         for (int j = 0; j < PW; ++j) {
+            // sign word built at the rows' positions for half 0 (compile-time masks), moved to this
+            // half's rows by one shift at the end
             uint32_t word = 0;
             float sabs = 0.0f;
             if (whole) {
@@ -293,28 +313,30 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
                 for (int v = 0; v < 16; ++v) {
                     const float y = E::to_float(acc[i][j], v) * Km[j] * al[v];
                     const float z = has_bn ? fmaf(y, bs[v], bb[v]) : y;
-                    word |= z >= 0.0f ? bit[v] : 0u;
+                    word |= z >= 0.0f ? 1u << (8 * (v >> 2) + (v & 3)) : 0u;
                     sabs += fabsf(z);
                 }
             } else {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
+                    const int kr = 8 * (v >> 2) + (v & 3);
+                    const bool fin = kb + kr < g.k_out;             // rows past the last filter: bit 0, no |z|
                     const float y = E::to_float(acc[i][j], v) * Km[j] * al[v];
                     const float z = has_bn ? fmaf(y, bs[v], bb[v]) : y;
-                    word |= z >= 0.0f ? bit[v] : 0u;
-                    sabs += bit[v] ? fabsf(z) : 0.0f;
+                    word |= (fin && z >= 0.0f) ? 1u << kr : 0u;
+                    sabs += fin ? fabsf(z) : 0.0f;
                 }
             }
-            if (out && plive[j]) {                // callers that also want the real tensor
-                float *orow = out + ((size_t)pimg[j] * g.k_out + kb) * howo + ppix[j];
-#pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    if (bit[v]) orow[(size_t)(8 * (v >> 2) + (v & 3)) * howo] = E::to_float(acc[i][j], v) * Km[j] * al[v];
-            }
+            word <<= 4 * half;
+            if (out)                              // callers that also want the real tensor
+                store_rows(out, i, j, [&](int v) {
+                    return __builtin_bit_cast(uint32_t, E::to_float(acc[i][j], v) * Km[j] * al[v]);
+                });
             word |= (uint32_t)__shfl_xor((int)word, 32);
             asum[j] += sabs + __shfl_xor(sabs, 32);
             if (half == 0) wtile_lds[((wp * PW + j) * 32 + l32) * WT + wf * FW + i] = word;
         }
+        __builtin_amdgcn_sched_barrier(0);        // one block's alpha / scale / shift live at a time
     }
     // |z| summed over this workgroup's filters: waves along the filter axis combine through LDS in
     // a fixed order.  Sign words leave through LDS too, so that consecutive threads write
@@ -416,6 +438,9 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
                               hipStream_t stream, const FuseArgs *fz)
 {
     constexpr int FT = 32 * FW * WF, PT = 32 * PW * WP;
+    // results are stored through a buffer resource with 32-bit offsets from the tile's first image
+    const long long howo = (long long)g.ho * g.wo;
+    if ((PT / howo + 2) * g.k_out * howo * 4 >= 0x7ffffff0LL) return XNOR_ERR_UNSUPPORTED;
     MfmaPlan pl;
     if (!make_plan(g, PT, FMT, g_lds_budget, FUSE ? WF + FT / 32 : 0, &pl)) return XNOR_ERR_UNSUPPORTED;
     const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2, g.wp, PT, FUSE ? WF + FT / 32 : 0);
@@ -453,25 +478,28 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
 {
     int tile = g_tile_override;
     if (tile == 0 || tile == 10) {
-        // 128 x 128 (64 x 256 for few filters) keeps 3-4 workgroups per CU in different phases and
-        // measured best on every convolution layer; problems with few output tiles (fully
-        // connected layers: few "pixels", long K) take the largest smaller tile that still gives
-        // every CU a workgroup
-        tile = (g.k_out <= 64) ? 2 : 1;
+        // Measured rules (fp4, all benchmark layers).  Up to 128 filters: 64 x 128 (fused epilogue: 64 x 256
+        // or 128 x 128, so that one workgroup holds every filter).  129..256 filters: a tile that holds
+        // every filter (weights stream through L1 once per pixel tile, the fused epilogue needs no
+        // partial sums), 256 x 96 or 256 x 128, whichever leaves fewer CUs idle in its last round of
+        // workgroups.  More filters: 128 x 128.  Problems with few output tiles (fully connected
+        // layers: few "pixels", long K) take the largest smaller tile that still gives every CU a
+        // workgroup.
         auto wgs = [&](int ft, int pt) {
             return (long long)((g.m_total + pt - 1) / pt) * ((g.k_out + ft - 1) / ft);
         };
         const int cus = 256;
-        if (wgs(tile == 1 ? 128 : 64, tile == 1 ? 128 : 256) < cus) {
+        auto waste = [&](long long w) { return (double)((w + cus - 1) / cus * cus) / (double)w; };
+        if (g.k_out <= 128) tile = !fz ? 11 : g.k_out <= 64 ? 2 : 1;
+        else if (g.k_out <= 256) tile = waste(wgs(256, 96)) <= waste(wgs(256, 128)) ? 4 : 5;
+        else tile = 1;
+        const long long w0 = tile == 11 ? wgs(64, 128) : tile == 2 ? wgs(64, 256) : tile == 4 ? wgs(256, 96)
+                             : tile == 5 ? wgs(256, 128) : wgs(128, 128);
+        if (w0 < 200) {
             if (wgs(64, 128) >= cus) tile = 11;
             else if (wgs(128, 64) >= cus) tile = 13;
             else tile = 14;       // 128 x 32 (measured ahead of 64 x 64 at equal workgroup count)
         }
-        // fused epilogue: a workgroup that holds every filter writes whole sign words runs and the
-        // final A itself (no partial sums, no second kernel); measured ahead for 129..256 filters
-        // (all-filter tiles for 384 and 512 filters, 3x2 and 4x2 blocks per wave, measured behind the
-        // default with its second launch)
-        if (fz && g_tile_override == 0 && g.k_out > 128 && g.k_out <= 256) tile = 4;
     }
     // the fused epilogue is built for the tiles marked F (the default choices and the wide-filter ones)
 #define XNOR_TILE(ID, FW, PW, WF, WP)                                                                     \

@@ -135,15 +135,17 @@ constexpr int ring_lcm(int a, int b)
 constexpr int KLOOP_TABLE_PAD = 12;
 
 // Weight record stream of a chunk that holds every channel word: the records of a filter block are
-// consecutive, so each block gets its own buffer resource covering exactly nsteps records and one
-// scalar offset advances by 1 KiB per step.  Requests past the end fall outside the resource and
-// return zeros by the buffer bounds check: no bookkeeping in the loop.
+// consecutive, so each block gets its own buffer resource covering exactly nsteps records and the
+// lane's offset advances by 1 KiB per step.  Prefetches past the end (never multiplied) fall outside
+// the resource and are answered with zeros by the buffer bounds check instead of touching memory;
+// the check covers the vector offset only, which is why the step lives there and not in the scalar
+// offset.  No other bookkeeping in the loop.
 template <int FW> struct WStreamLinear {
     __amdgpu_buffer_rsrc_t rsrc[FW];
-    int soff, wlane;
+    int voff;
     __device__ __forceinline__ WStreamLinear(const v4i *wimg, const int (&wrec0)[FW], int rec_start, int nsteps,
-                                             int wlane_)
-        : soff(0), wlane(wlane_)
+                                             int wlane)
+        : voff(wlane)
     {
 #pragma unroll
         for (int i = 0; i < FW; ++i)
@@ -154,10 +156,10 @@ template <int FW> struct WStreamLinear {
     {
 #pragma unroll
         for (int i = 0; i < FW; ++i) {
-            const v4u r = __builtin_amdgcn_raw_buffer_load_b128(rsrc[i], wlane, soff, 0);
+            const v4u r = __builtin_amdgcn_raw_buffer_load_b128(rsrc[i], voff, 0, 0);
             dst[i] = v4i{(int)r[0], (int)r[1], (int)r[2], (int)r[3]};
         }
-        soff += 1024;
+        voff += 1024;
     }
 };
 
@@ -201,7 +203,7 @@ template <int FW> struct WStreamChunked {
 // of their use and live in register rings of DW+1 and DX+1 slots; the body is unrolled until both
 // rings are back at slot 0.  A wave issues one instruction every four cycles, so everything that is
 // not a matrix instruction competes with them for issue slots: the loop carries no address or
-// bounds arithmetic beyond one scalar add and PW vector adds per step.
+// bounds arithmetic beyond PW + 1 vector adds per step.
 // The scheduling barriers pin the order written here (next operands requested, then the current
 // step's matrix instructions interleaved with those requests), which the compiler otherwise
 // regroups into one burst of loads followed by one burst of MFMAs with the latencies exposed.
