@@ -55,6 +55,8 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     float *ktile = a_lds + pl.max_rows * g.wp;                                   // [PT]
     float *asum_lds = ktile + PT;                                                // [WF][PT], fused epilogue only
     uint32_t *wtile_lds = reinterpret_cast<uint32_t *>(asum_lds + WF * PT);      // [PT][FT/32], fused epilogue only
+    // sign byte -> operand bytes table, after everything else (16-byte aligned by the plan)
+    const uint8_t *lut = lds + pl.lut_offset;
 
     // Workgroups go to the 8 XCDs round-robin by index; within every window of 64 pixel tiles each
     // XCD takes a run of 8 consecutive ones, so that the output lines two neighbouring tiles both
@@ -83,6 +85,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     const int r_hi = (int)(img_b * g.hp + oy_b * g.sh) + g.kh - 1;
     const int nrows = r_hi - r_lo + 1;
 
+    E::build_lut(lds + pl.lut_offset, tid, NT);
     for (int rr = tid; rr < nrows; rr += NT) {
         const uint32_t R = (uint32_t)(r_lo + rr);
         const uint32_t img = pl.div_hp.div(R);
@@ -168,7 +171,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
             }
 #pragma unroll
             for (int u = 0; u < FB; ++u)
-                if (dst[u] >= 0) E::widen_word(lds + dst[u], bits[u], ok[u], nch[u]);
+                if (dst[u] >= 0) E::widen_word_lut(lds + dst[u], lut, bits[u], ok[u], nch[u]);
         }
         if (wbase == 0 && !K) {
             // stage the matrix A of the same input rows (0 in the halo) for the K of this tile
@@ -377,8 +380,14 @@ static const int LDS_LIMIT = 160 * 1024;
 // fuse_rows: rows of PT words for the fused epilogue's |z| sums and sign words (0 without it)
 static size_t plan_lds_bytes(const MfmaPlan &pl, int bps, int wp, int PT, int fuse_rows)
 {
-    return (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 + (size_t)((pl.nsteps + KLOOP_TABLE_PAD) * bps) * 4 +
-           (size_t)pl.max_rows * wp * 4 + (size_t)PT * 4 * (1 + fuse_rows) + 16;
+    const size_t rest = (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 +
+                        (size_t)((pl.nsteps + KLOOP_TABLE_PAD) * bps) * 4 + (size_t)pl.max_rows * wp * 4 +
+                        (size_t)PT * 4 * (1 + fuse_rows) + 16;
+    return (rest + 15) / 16 * 16 + (bps == 1 ? 512 * 8 : 512 * 4);       // + the widening table
+}
+static int plan_lut_offset(const MfmaPlan &pl, int bps, int wp, int PT, int fuse_rows)
+{
+    return (int)(plan_lds_bytes(pl, bps, wp, PT, fuse_rows) - (bps == 1 ? 512 * 8 : 512 * 4));
 }
 
 static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fuse_rows, MfmaPlan *pl)
@@ -444,6 +453,7 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     MfmaPlan pl;
     if (!make_plan(g, PT, FMT, g_lds_budget, FUSE ? WF + FT / 32 : 0, &pl)) return XNOR_ERR_UNSUPPORTED;
     const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2, g.wp, PT, FUSE ? WF + FT / 32 : 0);
+    pl.lut_offset = plan_lut_offset(pl, FMT == 0 ? 1 : 2, g.wp, PT, FUSE ? WF + FT / 32 : 0);
     // two builds of every tiling: weight records consecutive (one chunk holds all channel words) or not
     const bool linear = pl.tap_jump == 0;
     auto kern = linear ? conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, true>

@@ -18,6 +18,7 @@ struct MfmaPlan {
     int nsteps;       // K-steps per chunk
     int tap_jump;     // weight records skipped when a chunk moves to the next tap
     int ptiles;       // pixel tiles of the launch (the grid is padded beyond it)
+    int lut_offset;   // LDS byte offset of the sign-byte widening table
     FastDiv div_wp, div_hp, div_ccw, div_cw;
 };
 
@@ -82,6 +83,36 @@ template <> struct Enc<0> {                    // int8
         *reinterpret_cast<uint4 *>(dst) = lo;
         *reinterpret_cast<uint4 *>(dst + 16) = hi;
     }
+    // The same through a table in LDS: entry b (8 bytes) = the 8 operand bytes of sign byte b,
+    // entries 256..511 are zero (selected for positions outside the image).  Three instructions
+    // per sign byte instead of a dozen: the widening is instruction-issue bound.
+    static constexpr int LUT_BYTES = 512 * 8;
+    static __device__ __forceinline__ void build_lut(uint8_t *lut, int tid, int nthreads) {
+        uint2 *t = reinterpret_cast<uint2 *>(lut);
+        for (int b = tid; b < 512; b += nthreads)
+            t[b] = b < 256 ? make_uint2(widen4(b & 15u), widen4((uint32_t)b >> 4)) : make_uint2(0, 0);
+    }
+    static __device__ __forceinline__ void widen_word_lut(uint8_t *dst, const uint8_t *lut, uint32_t bits, bool ok,
+                                                          int nch) {
+        const uint8_t *base = lut + (ok ? 0 : 256 * 8);
+        const uint2 a = *reinterpret_cast<const uint2 *>(base + (bits & 255u) * 8);
+        const uint2 b = *reinterpret_cast<const uint2 *>(base + ((bits >> 8) & 255u) * 8);
+        const uint2 c = *reinterpret_cast<const uint2 *>(base + ((bits >> 16) & 255u) * 8);
+        const uint2 d = *reinterpret_cast<const uint2 *>(base + (bits >> 24) * 8);
+        uint4 lo = make_uint4(a.x, a.y, b.x, b.y), hi = make_uint4(c.x, c.y, d.x, d.y);
+        if (nch < 32) {
+            uint32_t *p = reinterpret_cast<uint32_t *>(&lo);
+            uint32_t *q = reinterpret_cast<uint32_t *>(&hi);
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const int r0 = nch - 4 * w, r1 = nch - 16 - 4 * w;
+                p[w] &= r0 >= 4 ? 0xFFFFFFFFu : (r0 <= 0 ? 0u : (1u << (8 * r0)) - 1u);
+                q[w] &= r1 >= 4 ? 0xFFFFFFFFu : (r1 <= 0 ? 0u : (1u << (8 * r1)) - 1u);
+            }
+        }
+        *reinterpret_cast<uint4 *>(dst) = lo;
+        *reinterpret_cast<uint4 *>(dst + 16) = hi;
+    }
 };
 
 template <> struct Enc<1> {                    // 4-bit float E2M1
@@ -116,6 +147,30 @@ template <> struct Enc<1> {                    // 4-bit float E2M1
                     const int r0 = nch - 8 * q;
                     d[q] &= r0 >= 8 ? 0xFFFFFFFFu : (r0 <= 0 ? 0u : (1u << (4 * r0)) - 1u);
                 }
+            }
+        }
+        *reinterpret_cast<uint4 *>(dst) = v;
+    }
+    // table form (see the int8 encoding): entry b (4 bytes) = the 8 nibbles of sign byte b
+    static constexpr int LUT_BYTES = 512 * 4;
+    static __device__ __forceinline__ void build_lut(uint8_t *lut, int tid, int nthreads) {
+        uint32_t *t = reinterpret_cast<uint32_t *>(lut);
+        for (int b = tid; b < 512; b += nthreads) t[b] = b < 256 ? widen8((uint32_t)b) : 0u;
+    }
+    static __device__ __forceinline__ void widen_word_lut(uint8_t *dst, const uint8_t *lut, uint32_t bits, bool ok,
+                                                          int nch) {
+        const uint8_t *base = lut + (ok ? 0 : 256 * 4);
+        uint4 v;
+        v.x = *reinterpret_cast<const uint32_t *>(base + (bits & 255u) * 4);
+        v.y = *reinterpret_cast<const uint32_t *>(base + ((bits >> 8) & 255u) * 4);
+        v.z = *reinterpret_cast<const uint32_t *>(base + ((bits >> 16) & 255u) * 4);
+        v.w = *reinterpret_cast<const uint32_t *>(base + (bits >> 24) * 4);
+        if (nch < 32) {
+            uint32_t *d = reinterpret_cast<uint32_t *>(&v);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int r0 = nch - 8 * q;
+                d[q] &= r0 >= 8 ? 0xFFFFFFFFu : (r0 <= 0 ? 0u : (1u << (4 * r0)) - 1u);
             }
         }
         *reinterpret_cast<uint4 *>(dst) = v;
