@@ -86,6 +86,17 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     const int nrows = r_hi - r_lo + 1;
 
     E::build_lut(lds + pl.lut_offset, tid, NT);
+    // alpha (fused epilogue: also scale and shift) of this workgroup's filters, staged once behind the
+    // widening table ([FT] each); filters past the last one repeat it and are masked later
+    float *par_lds = reinterpret_cast<float *>(lds + pl.lut_offset + E::LUT_BYTES);
+    for (int t = tid; t < FT; t += NT) {
+        const int kc = min((int)blockIdx.y * FT + t, g.k_out - 1);
+        par_lds[t] = alpha[kc];
+        if constexpr (FUSE) {
+            par_lds[FT + t] = fz.bn_scale ? fz.bn_scale[kc] : 1.0f;
+            par_lds[2 * FT + t] = fz.bn_scale ? fz.bn_shift[kc] : 0.0f;
+        }
+    }
     for (int rr = tid; rr < nrows; rr += NT) {
         const uint32_t R = (uint32_t)(r_lo + rr);
         const uint32_t img = pl.div_hp.div(R);
@@ -268,10 +279,12 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     if constexpr (!FUSE) {
 #pragma unroll
     for (int i = 0; i < FW; ++i) {
-        const int kb = f0 + (wf * FW + i) * 32 + 4 * half;
         float al[16];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) al[v] = alpha[min(kb + 8 * (v >> 2) + (v & 3), g.k_out - 1)];
+        for (int q = 0; q < 4; ++q) {           // rows 8q + 4*half .. +3 of the block: one 16-byte read
+            const float4 a4 = *reinterpret_cast<const float4 *>(par_lds + (wf * FW + i) * 32 + 8 * q + 4 * half);
+            al[4 * q] = a4.x; al[4 * q + 1] = a4.y; al[4 * q + 2] = a4.z; al[4 * q + 3] = a4.w;
+        }
 #pragma unroll
         for (int j = 0; j < PW; ++j) {
             store_rows(out, i, j, [&](int v) {
@@ -286,7 +299,6 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     // other 16 sit in the lane 32 further on, so one cross-half exchange completes the sign word
     // and the |z| sum of the block.  Exchanges run for every lane (dead pixel columns carry
     // clamped data); only the stores are predicated.
-    const bool has_bn = fz.bn_scale != nullptr;
     const int cwn = g.fblocks;                    // words per pixel of the next layer's input
     constexpr int WT = FT / 32;                   // words per pixel this workgroup produces
     float asum[PW];
@@ -299,11 +311,14 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         float al[16], bs[16], bb[16];
         const bool whole = kb + 28 < g.k_out;     // all 16 rows of this lane exist (uniform per half-wave pair)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int kc = min(kb + 8 * (v >> 2) + (v & 3), g.k_out - 1);
-            al[v] = alpha[kc];
-            bs[v] = has_bn ? fz.bn_scale[kc] : 1.0f;
-            bb[v] = has_bn ? fz.bn_shift[kc] : 0.0f;
+        for (int q = 0; q < 4; ++q) {           // rows 8q + 4*half .. +3 of the block: one 16-byte read each
+            const int t = (wf * FW + i) * 32 + 8 * q + 4 * half;
+            const float4 a4 = *reinterpret_cast<const float4 *>(par_lds + t);
+            const float4 s4 = *reinterpret_cast<const float4 *>(par_lds + FT + t);
+            const float4 b4 = *reinterpret_cast<const float4 *>(par_lds + 2 * FT + t);
+            al[4 * q] = a4.x; al[4 * q + 1] = a4.y; al[4 * q + 2] = a4.z; al[4 * q + 3] = a4.w;
+            bs[4 * q] = s4.x; bs[4 * q + 1] = s4.y; bs[4 * q + 2] = s4.z; bs[4 * q + 3] = s4.w;
+            bb[4 * q] = b4.x; bb[4 * q + 1] = b4.y; bb[4 * q + 2] = b4.z; bb[4 * q + 3] = b4.w;
         }
 #pragma unroll
         for (int j = 0; j < PW; ++j) {
@@ -315,7 +330,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const float y = E::to_float(acc[i][j], v) * Km[j] * al[v];
-                    const float z = has_bn ? fmaf(y, bs[v], bb[v]) : y;
+                    const float z = fmaf(y, bs[v], bb[v]);          // scale 1, shift 0 without normalisation: z == y
                     word |= z >= 0.0f ? 1u << (8 * (v >> 2) + (v & 3)) : 0u;
                     sabs += fabsf(z);
                 }
@@ -325,7 +340,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
                     const int kr = 8 * (v >> 2) + (v & 3);
                     const bool fin = kb + kr < g.k_out;             // rows past the last filter: bit 0, no |z|
                     const float y = E::to_float(acc[i][j], v) * Km[j] * al[v];
-                    const float z = has_bn ? fmaf(y, bs[v], bb[v]) : y;
+                    const float z = fmaf(y, bs[v], bb[v]);          // scale 1, shift 0 without normalisation: z == y
                     word |= (fin && z >= 0.0f) ? 1u << kr : 0u;
                     sabs += fin ? fabsf(z) : 0.0f;
                 }
@@ -378,19 +393,20 @@ extern "C" int xnor_debug_timeline(long long *buf)
 static const int LDS_LIMIT = 160 * 1024;
 
 // fuse_rows: rows of PT words for the fused epilogue's |z| sums and sign words (0 without it)
-static size_t plan_lds_bytes(const MfmaPlan &pl, int bps, int wp, int PT, int fuse_rows)
+// par_bytes: alpha (fused epilogue: also scale and shift) of the workgroup's filters
+static size_t plan_lds_bytes(const MfmaPlan &pl, int bps, int wp, int PT, int fuse_rows, int par_bytes)
 {
     const size_t rest = (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 +
                         (size_t)((pl.nsteps + KLOOP_TABLE_PAD) * bps) * 4 + (size_t)pl.max_rows * wp * 4 +
                         (size_t)PT * 4 * (1 + fuse_rows) + 16;
-    return (rest + 15) / 16 * 16 + (bps == 1 ? 512 * 8 : 512 * 4);       // + the widening table
+    return (rest + 15) / 16 * 16 + (bps == 1 ? 512 * 8 : 512 * 4) + par_bytes;       // + the widening table
 }
-static int plan_lut_offset(const MfmaPlan &pl, int bps, int wp, int PT, int fuse_rows)
+static int plan_lut_offset(const MfmaPlan &pl, int bps, int wp, int PT, int fuse_rows, int par_bytes)
 {
-    return (int)(plan_lds_bytes(pl, bps, wp, PT, fuse_rows) - (bps == 1 ? 512 * 8 : 512 * 4));
+    return (int)(plan_lds_bytes(pl, bps, wp, PT, fuse_rows, par_bytes) - (bps == 1 ? 512 * 8 : 512 * 4) - par_bytes);
 }
 
-static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fuse_rows, MfmaPlan *pl)
+static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fuse_rows, int par_bytes, MfmaPlan *pl)
 {
     const int bps = fmt == 0 ? 1 : 2, bpb = fmt == 0 ? 32 : 16;
     const int rows = worst_region_rows(g, PT, PT);
@@ -408,7 +424,7 @@ static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fu
         pl->tap_jump = (ccw == g.cw) ? 0 : (g.cw - ccw) / bps;
         if (region >= (1ll << 30)) continue;
         pl->region_bytes = (int)region;
-        const long long total = (long long)plan_lds_bytes(*pl, bps, g.wp, PT, fuse_rows);
+        const long long total = (long long)plan_lds_bytes(*pl, bps, g.wp, PT, fuse_rows, par_bytes);
         const bool last = (ccw == 1) || (bps == 2 && ccw == 2);
         if (total > lds_budget && !last) continue;
         if (total > LDS_LIMIT) return false;
@@ -451,9 +467,10 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     const long long howo = (long long)g.ho * g.wo;
     if ((PT / howo + 2) * g.k_out * howo * 4 >= 0x7ffffff0LL) return XNOR_ERR_UNSUPPORTED;
     MfmaPlan pl;
-    if (!make_plan(g, PT, FMT, g_lds_budget, FUSE ? WF + FT / 32 : 0, &pl)) return XNOR_ERR_UNSUPPORTED;
-    const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2, g.wp, PT, FUSE ? WF + FT / 32 : 0);
-    pl.lut_offset = plan_lut_offset(pl, FMT == 0 ? 1 : 2, g.wp, PT, FUSE ? WF + FT / 32 : 0);
+    constexpr int FROWS = FUSE ? WF + FT / 32 : 0, PARB = (FUSE ? 3 : 1) * FT * 4;
+    if (!make_plan(g, PT, FMT, g_lds_budget, FROWS, PARB, &pl)) return XNOR_ERR_UNSUPPORTED;
+    const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2, g.wp, PT, FROWS, PARB);
+    pl.lut_offset = plan_lut_offset(pl, FMT == 0 ? 1 : 2, g.wp, PT, FROWS, PARB);
     // two builds of every tiling: weight records consecutive (one chunk holds all channel words) or not
     const bool linear = pl.tap_jump == 0;
     auto kern = linear ? conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, true>
