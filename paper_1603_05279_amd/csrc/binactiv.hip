@@ -28,7 +28,9 @@ __global__ __launch_bounds__(256) void binactiv_kernel(
     float(*part)[64] = reinterpret_cast<float(*)[64]>(smem);            // [4][64]
     uint8_t *wbytes = smem + 4 * 64 * sizeof(float);                    // [64 px][cw words][4 bytes]
     const int tid = threadIdx.x;
-    const int wave = tid >> 6, lane = tid & 63;
+    // the wave index as a scalar: channel indices derived from it are then scalar too, and the
+    // per-channel scale and shift come through the scalar cache instead of 64-lane loads
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
     const int img = blk / tiles_per_image;
     const int tile = blk - img * tiles_per_image;
     const int p0 = tile * 64;
