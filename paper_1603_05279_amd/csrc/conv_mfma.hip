@@ -58,21 +58,35 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     // sign byte -> operand bytes table, after everything else (16-byte aligned by the plan)
     const uint8_t *lut = lds + pl.lut_offset;
 
-    // Workgroups go to the 8 XCDs round-robin by index; within every window of 64 pixel tiles each
-    // XCD takes a run of 8 consecutive ones, so that the output lines two neighbouring tiles both
-    // write in part (and the input rows they share) meet in one XCD's L2.
-    // (the last, incomplete window keeps the plain order: runs would load the XCDs unevenly there)
-    const uint32_t bx = blockIdx.x;
-    const uint32_t win = (bx >> 6) << 6;
-    const uint32_t ptile = win + 64u <= (uint32_t)pl.ptiles ? win + ((bx & 7u) << 3) + ((bx >> 3) & 7u) : bx;
-    if (ptile >= (uint32_t)pl.ptiles) return;
+    // Workgroups go to the 8 XCDs round-robin by (linear) index, and every XCD has its own L2.
+    //  - Usual case (activations outweigh weights): within every window of 64 pixel tiles each XCD
+    //    takes a run of 8 consecutive ones, so that the output lines two neighbouring tiles both
+    //    write in part (and the input rows they share) meet in one XCD's L2.  The last, incomplete
+    //    window keeps the plain order: runs would load the XCDs unevenly there.
+    //  - Weight-heavy problems (fully connected layers): all pixel tiles of one filter tile go to
+    //    one XCD, so that each XCD fetches only its own filter tiles' weights from HBM instead of
+    //    all eight fetching everything.  1-D grid: XCD = index % 8, filter tile = 8 * (slot /
+    //    ptiles) + XCD, pixel tile = slot % ptiles, slot = index / 8.
+    uint32_t ptile, ftile;
+    if (pl.wmajor) {
+        const uint32_t xcd = blockIdx.x & 7u, slot = blockIdx.x >> 3;
+        ftile = (slot / (uint32_t)pl.ptiles) * 8u + xcd;
+        ptile = slot % (uint32_t)pl.ptiles;
+        if (ftile >= (uint32_t)pl.ftiles) return;
+    } else {
+        const uint32_t bx = blockIdx.x;
+        const uint32_t win = (bx >> 6) << 6;
+        ptile = win + 64u <= (uint32_t)pl.ptiles ? win + ((bx & 7u) << 3) + ((bx >> 3) & 7u) : bx;
+        ftile = blockIdx.y;
+        if (ptile >= (uint32_t)pl.ptiles) return;
+    }
     XNOR_TL(0);
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int l32 = lane & 31, half = lane >> 5;
     const int wf = wave % WF, wp = wave / WF;
     const uint32_t m0 = ptile * (uint32_t)PT;
-    const int f0 = blockIdx.y * FT;
+    const int f0 = (int)ftile * FT;
     const uint32_t howo = (uint32_t)(g.ho * g.wo);
     const int ccw = pl.cc_words;
     const int nsteps = pl.nsteps;
@@ -90,7 +104,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     // widening table ([FT] each); filters past the last one repeat it and are masked later
     float *par_lds = reinterpret_cast<float *>(lds + pl.lut_offset + E::LUT_BYTES);
     for (int t = tid; t < FT; t += NT) {
-        const int kc = min((int)blockIdx.y * FT + t, g.k_out - 1);
+        const int kc = min(f0 + t, g.k_out - 1);
         par_lds[t] = alpha[kc];
         if constexpr (FUSE) {
             par_lds[FT + t] = fz.bn_scale ? fz.bn_scale[kc] : 1.0f;
@@ -219,7 +233,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         // ---- software-pipelined K loop over this chunk's steps --------------------------------
         // record of step s: rec0 + s + (s / steps_per_tap) * tap_jump
         if constexpr (LINEAR) {      // the chunk holds every channel word: consecutive records
-            WStreamLinear<FW> ws(wimg, wrec0, 0, nsteps, wlane);
+            WStreamLinear<FW> ws(wimg, wrec0, wbase / E::BPS, nsteps, wlane);
             mfma_kloop<E, FW, PW, DW, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps);
         } else {
             WStreamChunked<FW> ws(wrsrc, wrec0, zero_rec, wbase / E::BPS, nsteps, steps_per_tap, pl.tap_jump, wlane);
@@ -376,8 +390,8 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         float sum = 0.0f;
 #pragma unroll
         for (int q = 0; q < WF; ++q) sum += asum_lds[q * PT + t];
-        if (gridDim.y == 1) fz.A_next[m] = sum / (float)g.k_out;
-        else fz.workspace[(size_t)blockIdx.y * g.m_total + m] = sum;
+        if (pl.ftiles == 1) fz.A_next[m] = sum / (float)g.k_out;
+        else fz.workspace[(size_t)ftile * g.m_total + m] = sum;
     }
     }
     XNOR_TL(4);
@@ -426,7 +440,10 @@ static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fu
         pl->region_bytes = (int)region;
         const long long total = (long long)plan_lds_bytes(*pl, bps, g.wp, PT, fuse_rows, par_bytes);
         const bool last = (ccw == 1) || (bps == 2 && ccw == 2);
-        if (total > lds_budget && !last) continue;
+        // one chunk with all channel words keeps the weight records consecutive (the K loop without
+        // bookkeeping) and saves the refills: worth up to half the CU's LDS (two workgroups per CU)
+        const long long budget = ccw == g.cw ? (lds_budget > 80 * 1024 ? lds_budget : 80 * 1024) : lds_budget;
+        if (total > budget && !last) continue;
         if (total > LDS_LIMIT) return false;
         pl->div_wp = FastDiv::make((uint32_t)g.wp);
         pl->div_hp = FastDiv::make((uint32_t)g.hp);
@@ -472,7 +489,8 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2, g.wp, PT, FROWS, PARB);
     pl.lut_offset = plan_lut_offset(pl, FMT == 0 ? 1 : 2, g.wp, PT, FROWS, PARB);
     // two builds of every tiling: weight records consecutive (one chunk holds all channel words) or not
-    const bool linear = pl.tap_jump == 0;
+    // (a chunk of a 1x1 filter is a run of consecutive records too)
+    const bool linear = pl.tap_jump == 0 || g.taps == 1;
     auto kern = linear ? conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, true>
                        : conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, false>;
     static bool attr_done[2] = {false, false};   // per instantiation
@@ -483,16 +501,24 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
         attr_done[linear] = true;
     }
     pl.ptiles = (g.m_total + PT - 1) / PT;
-    dim3 grid((unsigned)pl.ptiles, (unsigned)((g.k_out + FT - 1) / FT)), block(64 * WF * WP);
+    pl.ftiles = (g.k_out + FT - 1) / FT;
+    // weight-heavy: the weight image outweighs the packed activations and there are filter tiles to spread
+    pl.wmajor = pl.ftiles >= 8 && (long long)g.k_out * g.taps * g.c > 4LL * g.n * g.h * g.w * g.c;
+    dim3 grid((unsigned)pl.ptiles, (unsigned)pl.ftiles), block(64 * WF * WP);
+    if (pl.wmajor) {
+        const long long wg = (long long)((pl.ftiles + 7) / 8) * pl.ptiles * 8;
+        if (wg > 0x7fffffffLL) return XNOR_ERR_UNSUPPORTED;
+        grid = dim3((unsigned)wg, 1u);
+    }
     if (grid.y > 65535u) return XNOR_ERR_UNSUPPORTED;
     const size_t img_bytes = FMT == 0 ? wimg_i8_bytes(g.k_out, g.c, g.taps) : wimg_f4_bytes(g.k_out, g.c, g.taps);
     if (img_bytes > 0x7fffffffull) return XNOR_ERR_UNSUPPORTED;
     kern<<<grid, block, lds, stream>>>(xbits, reinterpret_cast<const v4i *>(wimg), (uint32_t)img_bytes, K, A, alpha,
                                        out, dot_out, g, pl, FUSE ? *fz : FuseArgs{});
     if (xnor_status s = hip_status(hipGetLastError())) return s;
-    if (FUSE && grid.y > 1) {
+    if (FUSE && pl.ftiles > 1) {
         sum_planes_kernel<<<dim3((unsigned)((g.m_total + 255) / 256)), dim3(256), 0, stream>>>(
-            fz->workspace, fz->A_next, g.m_total, (int)grid.y, (float)g.k_out);
+            fz->workspace, fz->A_next, g.m_total, pl.ftiles, (float)g.k_out);
         return hip_status(hipGetLastError());
     }
     return XNOR_OK;

@@ -19,6 +19,8 @@ struct MfmaPlan {
     int tap_jump;     // weight records skipped when a chunk moves to the next tap
     int ptiles;       // pixel tiles of the launch (the grid is padded beyond it)
     int lut_offset;   // LDS byte offset of the sign-byte widening table
+    int ftiles;       // filter tiles of the launch
+    int wmajor;       // 1: 1-D grid that keeps the pixel tiles of a filter tile on one XCD
     FastDiv div_wp, div_hp, div_ccw, div_cw;
 };
 
