@@ -56,6 +56,98 @@ def cpu_baseline(layers, inputs):
             "sample": f"full workload ({len(layers)} layer(s), batch {layers[0].n}), {dt:.2f} s wall"}
 
 
+def report(args):
+    """Per-layer table over all five configurations (markdown on stdout): median of `--steps` HIP-event
+    timed launches after warm-up (L2 not flushed between launches), for the convolution alone with each
+    inner loop, BinActiv alone, and the whole block; throughput, algorithmic GB/s and roofline fractions
+    of the fastest loop; the weight packing once; the CPU oracle on the same inputs."""
+    import statistics
+
+    import torch
+    from paper_1603_05279_amd import workloads as wl
+    from paper_1603_05279_amd import xnor
+
+    torch.cuda.set_device(0)
+    runs = max(args.steps, 50)
+
+    def median_us(fn):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(runs)]
+        for a, b in ev:
+            a.record()
+            fn()
+            b.record()
+        torch.cuda.synchronize()
+        return statistics.median(a.elapsed_time(b) for a, b in ev) * 1e3
+
+    # streaming copy: the practical HBM rate the fractions below are also quoted against
+    src = torch.empty(256 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    copy_us = median_us(lambda: dst.copy_(src))
+    copy_gbs = 2 * src.numel() * 4 / (copy_us * 1e-6) / 1e9
+    del src, dst
+    print(f"Streaming copy 256 MiB: {copy_us:.1f} us = {copy_gbs:.0f} GB/s (read + write); published peak 8000 GB/s.")
+    print(f"Every figure: median of {runs} single launches bracketed by HIP events (the bracket itself adds "
+          "about 3 us of dispatch latency to a launch); L2 not flushed between launches.\n")
+    print("| config / layer | G binop | conv fp4 us | conv int8 us | conv popcount us | BinActiv us | block us | "
+          "Tbinop/s (conv fp4) | alg. GB/s | % fp4 peak | % HBM peak | % attainable | pack us | oracle Gbinop/s |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
+    from oracle import xnor_oracle as xo
+    for cfg in ("tiny", "alexnet_conv2", "alexnet_conv345", "resnet18", "fc"):
+        for i, layer in enumerate(wl.config_layers(cfg)):
+            seed = wl.config_seed(cfg, i)
+            if cfg == "fc":
+                d = wl.linear_inputs(layer, seed)
+                n, c, h, w_, k, kh, kw, st, pd = layer.batch, layer.in_features, 1, 1, layer.out_features, 1, 1, 1, 0
+                x = torch.from_numpy(d["x"]).cuda().reshape(n, c, 1, 1)
+                wt = torch.from_numpy(d["w"]).cuda().reshape(k, c, 1, 1)
+                sc = sf = None
+            else:
+                d = wl.conv_inputs(layer, seed)
+                n, c, h, w_, k, kh, kw, st, pd = (layer.n, layer.c, layer.h, layer.w, layer.k_out, layer.kh,
+                                                  layer.kw, layer.stride, layer.pad)
+                x, wt = torch.from_numpy(d["x"]).cuda(), torch.from_numpy(d["w"]).cuda()
+                sc = torch.from_numpy(d["bn_scale"]).cuda() if d["bn_scale"] is not None else None
+                sf = torch.from_numpy(d["bn_shift"]).cuda() if d["bn_shift"] is not None else None
+            desc = xnor.make_desc(n, c, h, w_, k, kh, kw, st, pd)
+            pw = xnor.PackedWeights(wt)
+            bufs = xnor.ConvBuffers(desc)
+            pack_us = median_us(lambda: xnor.xnor_pack_weights(wt, pw.wbits, pw.alpha, pw.wmfma, k, c, kh, kw))
+            ba_us = median_us(lambda: xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, None, desc))
+            conv = {a: median_us(lambda a=a: xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha,
+                                                               bufs.out, None, desc, xnor.ALGOS[a]))
+                    for a in ("mfma_f4", "mfma_i8", "popcount")}
+
+            def block():
+                xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, None, desc)
+                xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha, bufs.out, None, desc,
+                                 xnor.XNOR_ALGO_MFMA_F4)
+            block_us = median_us(block)
+            macs = layer.bit_macs
+            ho, wo = xnor.output_hw(desc)
+            cw = (c + 31) // 32
+            nbytes = (n * h * w_ * (cw * 4 + 4) + ((k + 31) // 32) * ((kh * kw * cw + 1) // 2) * 1024 + k * 4 +
+                      n * k * ho * wo * 4)
+            t = conv["mfma_f4"] * 1e-6
+            tb, gbs = macs / t / 1e12, nbytes / t / 1e9
+            attain = max(2 * macs / 10.1e15, nbytes / 8e12) / t        # against min(peak, AI x BW)
+            t0 = time.perf_counter()
+            if cfg == "fc":
+                xo.binary_linear(d["x"], d["w"])
+            else:
+                xo.binary_conv2d(d["x"], d["w"], (st, st), (pd, pd), d["bn_scale"], d["bn_shift"])
+            orc = macs / (time.perf_counter() - t0) / 1e9
+            print(f"| {cfg} / {layer.name} | {macs / 1e9:.2f} | {conv['mfma_f4']:.1f} | {conv['mfma_i8']:.1f} | "
+                  f"{conv['popcount']:.1f} | {ba_us:.1f} | {block_us:.1f} | {tb:.0f} | {gbs:.0f} | "
+                  f"{100 * 2 * tb / 10100:.1f} | {100 * gbs / 8000:.1f} | {100 * attain:.1f} | {pack_us:.1f} | "
+                  f"{orc:.1f} |", flush=True)
+    print(f"\nOracle: {xo.threads()} host threads.  % attainable = floor time at min(fp4 peak, arithmetic "
+          "intensity x 8 TB/s) / measured time.  The paper's own figures: 58x measured, 62.27x modelled speed-up of "
+          "binary over float convolution on its CPU, memory access excluded (sec. 4.1).")
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -69,6 +161,8 @@ def main():
                     help="alexnet_conv345 only: feed each layer the previous layer's output instead of its own "
                          "synthetic input; 'layerwise' = xnor_binactiv + xnor_conv2d per layer, 'fused' = one "
                          "xnor_binactiv, then xnor_conv2d_binactiv emits the next layer's bits and A directly")
+    ap.add_argument("--report", action="store_true",
+                    help="print a per-layer table over all configurations instead of the one JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy, so a rocprofv3 --pmc run of this command holds "
@@ -86,6 +180,9 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if args.report:
+        report(args)
+        return
     torch.cuda.set_device(0)
     layers = wl.config_layers(args.workload)
     inputs = [wl.conv_inputs(l, wl.config_seed(args.workload, i)) for i, l in enumerate(layers)]
