@@ -64,6 +64,19 @@ def test_invalid_arguments_return_error_codes_without_launching():
     assert L.xnor_binactiv(fake, None, None, fake, fake, fake, ctypes.byref(zero_stride), None) == ERR_SHAPE
     assert L.xnor_linear(fake, fake, None, fake, fake, fake, None, 0, 8, 8, 1, None) == ERR_SHAPE
     assert L.xnor_conv2d(fake, fake, None, fake, None, fake, fake, None, ctypes.byref(good), 3, None) == ERR_NULL
+    # matrix-core kernels address a tile's results with 32-bit offsets: an image whose output exceeds
+    # 2 GiB is refused by them before any launch (XNOR_ALGO_AUTO would take the popcount kernel)
+    huge = xnor.make_desc(1, 32, 256, 256, 32768, 1, 1, 1, 0)
+    assert L.xnor_conv2d(fake, fake, fake, fake, None, fake, fake, None, ctypes.byref(huge), 3, None) == ERR_UNSUP
+    assert L.xnor_conv2d(fake, fake, fake, fake, None, fake, fake, None, ctypes.byref(huge), 2, None) == ERR_UNSUP
+    # fused epilogue: matrix-core loops only, workspace required above 64 filters
+    assert L.xnor_conv2d_binactiv(fake, fake, fake, fake, None, fake, None, None, fake, fake, None, fake,
+                                  ctypes.byref(good), 1, None) == ERR_UNSUP
+    wide = xnor.make_desc(1, 64, 14, 14, 96, 3, 3, 1, 1)
+    assert L.xnor_conv2d_binactiv(fake, fake, fake, fake, None, fake, None, None, fake, fake, None, None,
+                                  ctypes.byref(wide), 0, None) == ERR_NULL
+    assert L.xnor_conv2d_binactiv_workspace_bytes(ctypes.byref(good)) == 0
+    assert L.xnor_conv2d_binactiv_workspace_bytes(ctypes.byref(wide)) == 3 * 14 * 14 * 4
     assert L.xnor_set_tuning(99, 0) == ERR_UNSUP
     assert L.xnor_set_tuning(0, 0) == 0
     with pytest.raises(xnor.XnorError):
