@@ -112,6 +112,26 @@ int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
                   uint32_t *xbits, float *A, float *K, const xnor_conv_desc *d, void *hip_stream);
 
 /*
+ * Max-pooling (and the optional ReLU) between one block's BinConv and the next block's BatchNorm and
+ * BinActiv (block order BatchNorm -> BinActiv -> BinConv -> Pool of sec. 3.2, "Training XNOR-Networks"),
+ * applied to the float tensor on load: the pooled tensor is never written.
+ *     p[n][ch][oy][ox] = max over the pool_h x pool_w window at (oy*stride_h - pad_h, ox*stride_w - pad_w)
+ *                        of x, window positions outside the image skipped (output extent as for a
+ *                        convolution: floor((h_in + 2*pad_h - pool_h)/stride_h) + 1); 2*pad <= pool.
+ *                        The running maximum starts at -inf and a value replaces it only when it
+ *                        compares greater (NaN inputs are skipped).
+ *     relu != 0:         p = max(p, 0)
+ *     then exactly xnor_binactiv on p with K = NULL:  y = fmaf(p, bn_scale, bn_shift), xbits, A.
+ *   x      in   float32 [n][c][h_in][w_in]
+ *   xbits  out  uint32  [n][h_out][w_out][Cw]
+ *   A      out  float32 [n][h_out][w_out]
+ */
+int xnor_pool_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
+                       uint32_t *xbits, float *A, int n, int c, int h_in, int w_in,
+                       int pool_h, int pool_w, int stride_h, int stride_w, int pad_h, int pad_w, int relu,
+                       void *hip_stream);
+
+/*
  * B = sign(W) packed to bits and alpha = ||W||_1/n per filter (sec. 3.1; first loop of the
  * training algorithm).  Run once per layer: at inference only B and alpha are kept.
  *   w      in   float32 [k_out][c][kh][kw]

@@ -131,6 +131,27 @@ def binactiv(x, bn_scale=None, bn_shift=None):
     return y, sign(y), A_map(y)
 
 
+def max_pool(x, pool, stride, pad=(0, 0), relu=False):
+    """Max-pooling of a real tensor x [n][c][h][w] (the Pool layer that follows BinConv in the block order
+    of sec. 3.2), optionally followed by max(., 0) (the optional ReLU of the same section).  Window
+    positions outside the image are skipped; the maximum starts at -inf and only a greater value
+    replaces it, so NaN inputs are skipped.  Output extent floor((h + 2*pad - pool)/stride) + 1."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    n, c, h, w = x.shape
+    (ph, pw), (sh, sw), (qh, qw) = pool, stride, pad
+    ho, wo = (h + 2 * qh - ph) // sh + 1, (w + 2 * qw - pw) // sw + 1
+    out = np.empty((n, c, ho, wo), dtype=np.float32)
+    for oy in range(ho):
+        y0, y1 = max(oy * sh - qh, 0), min(oy * sh - qh + ph, h)
+        for ox in range(wo):
+            x0, x1 = max(ox * sw - qw, 0), min(ox * sw - qw + pw, w)
+            win = x[:, :, y0:y1, x0:x1].reshape(n, c, -1)
+            out[:, :, oy, ox] = np.fmax.reduce(win, axis=2, initial=-np.inf)
+    if relu:
+        out = np.where(out > 0, out, np.float32(0.0)).astype(np.float32)
+    return out
+
+
 def binary_linear(x, W):
     """Fully connected layer as the convolution whose filter covers the whole input
     (footnote of sec. 1): x [batch][in_f], W [out_f][in_f].  Returns dict(dot, K, alpha, out)

@@ -126,6 +126,28 @@ int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
     return K ? launch_boxfilter(A, K, g, st) : XNOR_OK;
 }
 
+int xnor_pool_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
+                       uint32_t *xbits, float *A, int n, int c, int h_in, int w_in,
+                       int pool_h, int pool_w, int stride_h, int stride_w, int pad_h, int pad_w, int relu,
+                       void *hip_stream)
+{
+    if (!x || !xbits || !A) return XNOR_ERR_NULL;
+    if (n <= 0 || c <= 0 || h_in <= 0 || w_in <= 0 || pool_h <= 0 || pool_w <= 0 || stride_h <= 0 ||
+        stride_w <= 0 || pad_h < 0 || pad_w < 0)
+        return XNOR_ERR_SHAPE;
+    if (2 * pad_h > pool_h || 2 * pad_w > pool_w) return XNOR_ERR_SHAPE;     // every window holds an input value
+    const long long hp = (long long)h_in + 2LL * pad_h, wp = (long long)w_in + 2LL * pad_w;
+    if (pool_h > hp || pool_w > wp) return XNOR_ERR_SHAPE;
+    const long long ho = (hp - pool_h) / stride_h + 1, wo = (wp - pool_w) / stride_w + 1;
+    if ((long long)h_in * w_in > 0x7fffffffLL || ho * wo > 0x7fffffffLL ||
+        (long long)n * ho * wo * ((c + 31) / 32) > 0x7fffffffLL || (long long)n * c > 0x7fffffffLL)
+        return XNOR_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(xbits) || !aligned16(A)) return XNOR_ERR_ALIGN;
+    if (xnor_status s = check_bn(bn_scale, bn_shift)) return s;
+    return launch_pool_binactiv(x, bn_scale, bn_shift, xbits, A, n, c, h_in, w_in, pool_h, pool_w, stride_h,
+                                stride_w, pad_h, pad_w, relu ? 1 : 0, (hipStream_t)hip_stream);
+}
+
 int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
                       int k_out, int c, int kh, int kw, void *hip_stream)
 {

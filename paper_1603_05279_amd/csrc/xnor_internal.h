@@ -73,6 +73,10 @@ inline xnor_status hip_status(hipError_t e) { return e == hipSuccess ? XNOR_OK :
 // kernels' host launchers (each returns an xnor_status, enqueues on `stream`, never synchronises)
 xnor_status launch_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
                             uint32_t *xbits, float *A, int n, int c, int hw, hipStream_t stream);
+// the same layer with a max-pool (and optional ReLU) applied to x on load; xbits / A are pooled-size
+xnor_status launch_pool_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
+                                 uint32_t *xbits, float *A, int n, int c, int h, int w, int ph, int pw,
+                                 int sh, int sw, int pad_h, int pad_w, int relu, hipStream_t stream);
 xnor_status launch_boxfilter(const float *A, float *K, const ConvGeom &g, hipStream_t stream);
 xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
                                 int k_out, int c, int taps, hipStream_t stream);

@@ -19,7 +19,7 @@ EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor
            "xnor_set_tuning",
            "xnor_binarize_pack", "xnor_compute_K", "xnor_binactiv", "xnor_pack_weights",
            "xnor_conv2d", "xnor_linear",
-           "xnor_conv2d_binactiv_workspace_bytes", "xnor_conv2d_binactiv"]
+           "xnor_conv2d_binactiv_workspace_bytes", "xnor_conv2d_binactiv", "xnor_pool_binactiv"]
 
 
 class XnorError(RuntimeError):
@@ -71,6 +71,8 @@ def lib():
         L.xnor_conv2d_binactiv_workspace_bytes.restype = ctypes.c_size_t
         L.xnor_conv2d_binactiv.argtypes = [vp] * 12 + [ctypes.POINTER(ConvDesc), ip, vp]
         L.xnor_conv2d_binactiv.restype = ip
+        L.xnor_pool_binactiv.argtypes = [vp] * 5 + [ip] * 11 + [vp]
+        L.xnor_pool_binactiv.restype = ip
         _lib = L
     return _lib
 
@@ -146,6 +148,14 @@ def xnor_binactiv(x, bn_scale, bn_shift, xbits, A, K, desc, stream=None):
         _ptr(x, torch.float32), _ptr(bn_scale, torch.float32), _ptr(bn_shift, torch.float32),
         _ptr(xbits, torch.int32), _ptr(A, torch.float32), _ptr(K, torch.float32),
         ctypes.byref(desc), _stream(stream)))
+
+
+def xnor_pool_binactiv(x, bn_scale, bn_shift, xbits, A, n, c, h_in, w_in, pool, stride, pad=(0, 0), relu=False,
+                       stream=None):
+    _check("xnor_pool_binactiv", lib().xnor_pool_binactiv(
+        _ptr(x, torch.float32), _ptr(bn_scale, torch.float32), _ptr(bn_shift, torch.float32),
+        _ptr(xbits, torch.int32), _ptr(A, torch.float32), n, c, h_in, w_in, pool[0], pool[1], stride[0], stride[1],
+        pad[0], pad[1], int(bool(relu)), _stream(stream)))
 
 
 def xnor_pack_weights(w, wbits, alpha, wmfma, k_out, c, kh, kw, stream=None):

@@ -295,6 +295,27 @@ def test_binactiv_of_a_block_output_has_a_closed_form_from_the_integers():
     np.testing.assert_allclose(Az, np.abs(z.astype(np.float64)).mean(axis=1), rtol=1e-12)
 
 
+def test_max_pool_matches_library_routine_and_hand_example():
+    # hand-worked: 1x1x3x4 plane, 2x2 window, stride 1
+    x = np.array([[[[1, 5, 2, 0], [3, 4, 9, -1], [-7, 8, 6, 2]]]], dtype=np.float32)
+    assert xo.max_pool(x, (2, 2), (1, 1)).reshape(2, 3).tolist() == [[5, 9, 9], [8, 9, 9]]
+    # padding positions are skipped (never win), also when every value is negative
+    neg = -np.ones((1, 1, 2, 2), np.float32)
+    assert (xo.max_pool(neg, (2, 2), (1, 1), (1, 1)) == -1).all()
+    assert xo.max_pool(neg, (2, 2), (1, 1), (1, 1), relu=True).max() == 0
+    # NaN inputs are skipped
+    nan = np.array([[[[np.nan, 2.0], [1.0, np.nan]]]], dtype=np.float32)
+    assert xo.max_pool(nan, (2, 2), (1, 1)).item() == 2.0
+    # special case that is a library routine: torch max_pool2d (pads with -inf, floor mode)
+    rng = np.random.default_rng(31)
+    for (h, w, pool, stride, pad) in [(27, 27, (3, 3), (2, 2), (0, 0)), (13, 13, (3, 3), (2, 2), (0, 0)),
+                                      (9, 11, (3, 2), (2, 1), (1, 1)), (7, 7, (2, 2), (2, 2), (1, 0))]:
+        x = rng.standard_normal((2, 5, h, w)).astype(np.float32)
+        ref = torch.nn.functional.max_pool2d(torch.from_numpy(x), pool, stride, pad).numpy()
+        assert np.array_equal(xo.max_pool(x, pool, stride, pad), ref)
+        assert np.array_equal(xo.max_pool(x, pool, stride, pad, relu=True), np.maximum(ref, 0))
+
+
 # ----------------------------------------------------------- op-count model (sec. 4.1)
 def test_speedup_model_matches_printed_value():
     rows = [l.split() for l in open(os.path.join(GOLDEN, "speedup_model.txt")) if l.strip() and not l.startswith("#")]
