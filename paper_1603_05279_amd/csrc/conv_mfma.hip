@@ -128,7 +128,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
             const uint32_t wl = bb - t * ccw;
             const uint32_t dy = g.div_kw.div(t);
             const uint32_t dx = t - dy * g.kw;
-            xoff_tab[b] = (int)((dy * g.wp + dx) * pl.ps + wl * E::BPB);
+            xoff_tab[b] = (int)(dy * pl.row_pitch + dx * pl.ps + wl * E::BPB);
         }
     }
 
@@ -141,7 +141,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         const uint32_t img = g.div_howo.div(m);
         const uint32_t pix = m - img * howo;
         const uint32_t oy = g.div_wo.div(pix), ox = pix - oy * g.wo;
-        pbase[j] = (((int)(img * g.hp + oy * g.sh) - r_lo) * g.wp + (int)ox * g.sw) * pl.ps +
+        pbase[j] = ((int)(img * g.hp + oy * g.sh) - r_lo) * pl.row_pitch + (int)ox * g.sw * pl.ps +
                    (E::BPS == 1 ? 16 * half : 0);
     }
     // weight records of this wave's filter blocks: record index = fblk * recs_per_fblock + step record
@@ -189,7 +189,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
                 const int xcol = (int)(px - rr * g.wp) - g.pw;
                 const int rowbase = rowinfo[rr];
                 ok[u] = rowbase >= 0 && xcol >= 0 && xcol < g.w;
-                dst[u] = it < items ? (int)(px * pl.ps + wl * E::BPB) : -1;
+                dst[u] = it < items ? (int)(rr * pl.row_pitch + (px - rr * g.wp) * pl.ps + wl * E::BPB) : -1;
                 nch[u] = g.c - (wbase + wl) * 32;
                 bits[u] = 0;
                 if (ok[u]) bits[u] = xbits[((size_t)rowbase + xcol) * g.cw + wbase + wl];
@@ -430,7 +430,15 @@ static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fu
         if (bps == 2 && ccw != g.cw && (ccw % 2)) continue;
         const long long row_bytes = (long long)ccw * bpb;
         const long long ps = row_bytes + ((row_bytes / 16) % 2 == 0 ? 16 : 0);
-        const long long region = (long long)rows * g.wp * ps;
+        // LDS row pitch: at least wp pixels, padded so that stepping from the last output pixel of a row
+        // to the first of the next continues the bank pattern of the steps within a row
+        // (sh * pitch = wo * sw * ps modulo the 256-byte bank period): operand reads of a wave that
+        // spans a row boundary then stay conflict-free
+        long long pitch = (long long)g.wp * ps;
+        for (int add = 0; add < 256; add += 16)
+            if (((long long)g.sh * (pitch + add) - (long long)g.wo * g.sw * ps) % 256 == 0) { pitch += add; break; }
+        const long long region = (long long)rows * pitch;
+        pl->row_pitch = (int)pitch;
         pl->cc_words = ccw;
         pl->ps = (int)ps;
         pl->max_rows = rows;

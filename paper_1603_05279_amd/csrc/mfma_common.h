@@ -14,7 +14,8 @@ struct MfmaPlan {
     int cc_words;     // channel words widened per chunk (divides cw)
     int ps;           // bytes per pixel in LDS (an odd multiple of 16: conflict-free 16-byte reads)
     int max_rows;     // padded input rows a pixel tile can touch
-    int region_bytes; // max_rows * wp * ps
+    int region_bytes; // max_rows * row_pitch
+    int row_pitch;    // LDS bytes per padded input row (>= wp * ps)
     int nsteps;       // K-steps per chunk
     int tap_jump;     // weight records skipped when a chunk moves to the next tap
     int ptiles;       // pixel tiles of the launch (the grid is padded beyond it)
