@@ -188,6 +188,30 @@ int xnor_conv2d_binactiv(const uint32_t *xbits, const uint32_t *wbits, const voi
                          const xnor_conv_desc *d, int algo, void *hip_stream);
 
 /*
+ * Binary-Weight-Network convolution (sec. 3.1, "Binary-Weight-Networks"): real-valued input, weights
+ * estimated by alpha * sign(W):
+ *     out[n][k][oy][ox] = alpha_k * sum over in-bounds taps and channels of  I * sign(W)
+ * (additions and subtractions of the inputs only; zero padding, correlation, no bias, as above).
+ * The sums run on the bfloat16 matrix cores and are float sums of exact terms: xnor_bwn_split writes
+ * every input as three bfloat16 numbers whose sum is the float exactly (finite inputs), the weights
+ * are +-1.  Three calls:
+ *   xnor_bwn_split         x float32 [n][c][h][w]  ->  parts, xnor_bwn_parts_bytes(n, c, h, w) bytes (opaque)
+ *   xnor_bwn_pack_weights  w float32 [k_out][c][kh][kw]  ->  alpha float32 [k_out] (as xnor_pack_weights),
+ *                          wimg, xnor_bwn_wimg_bytes(k_out, c, kh, kw) bytes (opaque); once per layer
+ *   xnor_bwn_conv2d        parts, wimg, alpha  ->  out float32 [n][k_out][h_out][w_out]; d describes the
+ *                          convolution with the real channel count c
+ * Differences between this result and one accumulated in double stay within float rounding of the
+ * running sums (about 1e-7 * sqrt(c*kh*kw) of the magnitude of the terms).
+ */
+size_t xnor_bwn_parts_bytes(int n, int c, int h, int w);
+size_t xnor_bwn_wimg_bytes(int k_out, int c, int kh, int kw);
+int xnor_bwn_split(const float *x, void *parts, int n, int c, int h, int w, void *hip_stream);
+int xnor_bwn_pack_weights(const float *w, float *alpha, void *wimg, int k_out, int c, int kh, int kw,
+                          void *hip_stream);
+int xnor_bwn_conv2d(const void *parts, const void *wimg, const float *alpha, float *out,
+                    const xnor_conv_desc *d, void *hip_stream);
+
+/*
  * Fully connected layer = convolution whose filter covers the whole input (footnote of sec. 1).
  *   xbits [batch][Fw], wbits [out_features][Fw], Fw = ceil(in_features/32)
  *   Krow  [batch]  = mean_j |x[b][j]|  (xnor_compute_K / xnor_binactiv with c = in_features, 1x1)

@@ -40,6 +40,7 @@
 #include <math.h>
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 /* y = x*scale_c + shift_c in float with one rounding (fmaf); scale==NULL copies x.
  * Block order of sec. 3.2 "Training XNOR-Networks": normalise before binarising. */
@@ -157,4 +158,44 @@ void xo_scale(const int32_t *dot, const double *K, const double *alpha, float *o
                 const size_t o = ((size_t)b * k_out + k) * px + p;
                 out[o] = (float)((double)dot[o] * K[(size_t)b * px + p] * alpha[k]);
             }
+}
+
+/* Binary-Weight-Network convolution (sec. 3.1, I * W ~ (I (+) B) alpha): real input, weights
+ * alpha_k * sign(W_k).  out[b][k][oy][ox] = alpha_k * sum_{ch,dy,dx in bounds} I * sign(W): only
+ * additions and subtractions of the inputs, accumulated in double, scaled and rounded once. */
+void xo_bwn(const float *I, const int8_t *sW, const double *alpha, float *out,
+            int n, int c, int h, int w, int k_out, int kh, int kw,
+            int stride_h, int stride_w, int pad_h, int pad_w)
+{
+    const int ho = (h + 2 * pad_h - kh) / stride_h + 1;
+    const int wo = (w + 2 * pad_w - kw) / stride_w + 1;
+    const long jobs = (long)n * k_out;
+#pragma omp parallel for schedule(static)
+    for (long job = 0; job < jobs; ++job) {
+        const int b = (int)(job / k_out), k = (int)(job % k_out);
+        double *acc = (double *)malloc(sizeof(double) * (size_t)ho * wo);
+        for (int i = 0; i < ho * wo; ++i)
+            acc[i] = 0.0;
+        for (int ch = 0; ch < c; ++ch)
+            for (int dy = 0; dy < kh; ++dy)
+                for (int dx = 0; dx < kw; ++dx) {
+                    const int sw = sW[(((size_t)k * c + ch) * kh + dy) * kw + dx];
+                    const float *plane = I + ((size_t)b * c + ch) * h * w;
+                    for (int oy = 0; oy < ho; ++oy) {
+                        const int iy = oy * stride_h - pad_h + dy;
+                        if (iy < 0 || iy >= h)
+                            continue;
+                        for (int ox = 0; ox < wo; ++ox) {
+                            const int ix = ox * stride_w - pad_w + dx;
+                            if (ix < 0 || ix >= w)
+                                continue;
+                            const double v = (double)plane[(size_t)iy * w + ix];
+                            acc[oy * wo + ox] += sw > 0 ? v : -v;      /* add or subtract, no multiply */
+                        }
+                    }
+                }
+        for (int i = 0; i < ho * wo; ++i)
+            out[(size_t)job * ho * wo + i] = (float)(acc[i] * alpha[k]);
+        free(acc);
+    }
 }

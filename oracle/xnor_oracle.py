@@ -152,6 +152,23 @@ def max_pool(x, pool, stride, pad=(0, 0), relu=False):
     return out
 
 
+def bwn_conv2d(x, W, stride=(1, 1), pad=(0, 0)):
+    """Binary-Weight-Network convolution (sec. 3.1): real input x, weights alpha_k * sign(W_k):
+    out = alpha_k * sum I * sign(W) over the in-bounds window (float64 sums, rounded once)."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    n, c, h, w = x.shape
+    k, c2, kh, kw = W.shape
+    assert c == c2
+    ho, wo = out_hw(h, w, kh, kw, stride, pad)
+    sW = sign(W)
+    a = alpha(W)
+    out = np.empty((n, k, ho, wo), dtype=np.float32)
+    _load().xo_bwn(_p(x, ctypes.c_float), _p(sW, ctypes.c_int8), _p(a, ctypes.c_double), _p(out, ctypes.c_float),
+                   n, c, h, w, k, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    return {"out": out, "alpha": a}
+
+
 def binary_linear(x, W):
     """Fully connected layer as the convolution whose filter covers the whole input
     (footnote of sec. 1): x [batch][in_f], W [out_f][in_f].  Returns dict(dot, K, alpha, out)

@@ -228,6 +228,58 @@ int xnor_conv2d_binactiv(const uint32_t *xbits, const uint32_t *wbits, const voi
     return launch_conv_mfma(0, xbits, wmfma, K, A, alpha, out, nullptr, g, st, &fz);
 }
 
+/* ---- Binary-Weight-Network convolution: real activations, +-1 weights (sec. 3.1) ------------------ */
+
+size_t xnor_bwn_parts_bytes(int n, int c, int h, int w)
+{
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return 0;
+    return (size_t)n * h * w * ((c + 15) / 16) * 96u;
+}
+
+size_t xnor_bwn_wimg_bytes(int k_out, int c, int kh, int kw)
+{
+    if (k_out <= 0 || c <= 0 || kh <= 0 || kw <= 0 || (long long)kh * kw > 4096) return 0;
+    return wimg_i8_bytes(k_out, 96 * ((c + 15) / 16), kh * kw);
+}
+
+int xnor_bwn_split(const float *x, void *parts, int n, int c, int h, int w, void *hip_stream)
+{
+    if (!x || !parts) return XNOR_ERR_NULL;
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return XNOR_ERR_SHAPE;
+    if ((long long)h * w > 0x7fffffffLL || (long long)n * h * w * ((c + 15) / 16) * 3 > 0x7fffffffLL)
+        return XNOR_ERR_SHAPE;
+    if (!aligned16(x) || !aligned16(parts)) return XNOR_ERR_ALIGN;
+    return launch_bwn_split(x, parts, n, c, h * w, (hipStream_t)hip_stream);
+}
+
+int xnor_bwn_pack_weights(const float *w, float *alpha, void *wimg, int k_out, int c, int kh, int kw,
+                          void *hip_stream)
+{
+    if (!w || !alpha || !wimg) return XNOR_ERR_NULL;
+    if (k_out <= 0 || c <= 0 || kh <= 0 || kw <= 0) return XNOR_ERR_SHAPE;
+    if ((long long)kh * kw > 4096 || (long long)c * kh * kw > 0x7fffffffLL ||
+        (long long)k_out * kh * kw * ((c + 15) / 16) * 3 > 0x7fffffffLL / 32)
+        return XNOR_ERR_SHAPE;
+    if (!aligned16(w) || !aligned16(alpha) || !aligned16(wimg)) return XNOR_ERR_ALIGN;
+    return launch_bwn_pack(w, alpha, wimg, k_out, c, kh * kw, (hipStream_t)hip_stream);
+}
+
+int xnor_bwn_conv2d(const void *parts, const void *wimg, const float *alpha, float *out,
+                    const xnor_conv_desc *d, void *hip_stream)
+{
+    if (!parts || !wimg || !alpha || !out) return XNOR_ERR_NULL;
+    if (!d) return XNOR_ERR_NULL;
+    // the matrix-core kernel sees 3*ceil(c/16) operand words of 32 bytes per pixel
+    xnor_conv_desc dd = *d;
+    if (d->c <= 0 || d->c > 0x7fffffff / 96) return XNOR_ERR_SHAPE;
+    dd.c = 96 * ((d->c + 15) / 16);
+    ConvGeom g;
+    if (xnor_status s = make_geom(&dd, &g)) return s;
+    if (!aligned16(parts) || !aligned16(wimg) || !aligned16(alpha) || !aligned16(out)) return XNOR_ERR_ALIGN;
+    return launch_conv_mfma(2, static_cast<const uint32_t *>(parts), wimg, nullptr, nullptr, alpha, out, nullptr, g,
+                            (hipStream_t)hip_stream);
+}
+
 int xnor_linear(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
                 const float *Krow, const float *alpha, float *out, int32_t *dot_out,
                 int batch, int in_features, int out_features, int algo, void *hip_stream)

@@ -177,6 +177,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         constexpr int FB = 4;                  // items in flight per thread: loads first, then widening
         for (int it0 = tid; it0 < items; it0 += NT * FB) {
             uint32_t bits[FB];
+            uint4 raw[FB][2];              // FMT 2: the 32-byte word itself
             int dst[FB], nch[FB];
             bool ok[FB];
 #pragma unroll
@@ -192,13 +193,30 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
                 dst[u] = it < items ? (int)(rr * pl.row_pitch + (px - rr * g.wp) * pl.ps + wl * E::BPB) : -1;
                 nch[u] = g.c - (wbase + wl) * 32;
                 bits[u] = 0;
-                if (ok[u]) bits[u] = xbits[((size_t)rowbase + xcol) * g.cw + wbase + wl];
+                if constexpr (FMT == 2) {
+                    raw[u][0] = raw[u][1] = make_uint4(0, 0, 0, 0);
+                    if (ok[u]) {
+                        const uint4 *src = reinterpret_cast<const uint4 *>(xbits) +
+                                           (((size_t)rowbase + xcol) * g.cw + wbase + wl) * 2;
+                        raw[u][0] = src[0];
+                        raw[u][1] = src[1];
+                    }
+                } else {
+                    if (ok[u]) bits[u] = xbits[((size_t)rowbase + xcol) * g.cw + wbase + wl];
+                }
             }
 #pragma unroll
             for (int u = 0; u < FB; ++u)
-                if (dst[u] >= 0) E::widen_word_lut(lds + dst[u], lut, bits[u], ok[u], nch[u]);
+                if (dst[u] >= 0) {
+                    if constexpr (FMT == 2) {
+                        *reinterpret_cast<uint4 *>(lds + dst[u]) = raw[u][0];
+                        *reinterpret_cast<uint4 *>(lds + dst[u] + 16) = raw[u][1];
+                    } else {
+                        E::widen_word_lut(lds + dst[u], lut, bits[u], ok[u], nch[u]);
+                    }
+                }
         }
-        if (wbase == 0 && !K) {
+        if (FMT != 2 && wbase == 0 && !K) {
             // stage the matrix A of the same input rows (0 in the halo) for the K of this tile
             for (int it = tid; it < nrows * g.wp; it += NT) {
                 const uint32_t rr = pl.div_wp.div((uint32_t)it);
@@ -210,7 +228,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         }
         __syncthreads();
         if (wbase == 0) XNOR_TL(2);
-        if (wbase == 0 && !K) for (int kt = tid; kt < PT; kt += NT) {
+        if (FMT != 2 && wbase == 0 && !K) for (int kt = tid; kt < PT; kt += NT) {
             // K of output pixel m0 + tid: the kh x kw taps of A in row-major order over the staged
             // rows (halo entries add +0.0f, the same bits as skipping them), divided by kh*kw
             const uint32_t m = min(m0 + (uint32_t)kt, (uint32_t)g.m_total - 1u);
@@ -245,7 +263,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     // epilogue: out = float(dot) * K * alpha; result register v of a lane is filter row
     // 8*(v/4) + 4*half + v%4 of the 32-filter block, pixel column l32.  alpha of the lane's
     // filter rows is fetched once (clamped index, no branch), stores are predicated.
-    if (!K) __syncthreads();      // the K tile is complete
+    if (FMT != 2 && !K) __syncthreads();      // the K tile is complete
     uint32_t pimg[PW], ppix[PW];
     float Km[PW];
     bool plive[PW];
@@ -257,7 +275,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         const uint32_t mc = plive[j] ? m : (uint32_t)g.m_total - 1u;
         pimg[j] = g.div_howo.div(mc);
         ppix[j] = mc - pimg[j] * howo;
-        Km[j] = K ? K[mc] : ktile[pl_idx];
+        Km[j] = FMT == 2 ? 1.0f : (K ? K[mc] : ktile[pl_idx]);      // real activations carry no K
     }
     // Float (and optional integer) results leave through buffer stores: the resource starts at the
     // tile's first image, a lane's vector offset names its pixel (plus its half-wave's four rows),
@@ -422,7 +440,7 @@ static int plan_lut_offset(const MfmaPlan &pl, int bps, int wp, int PT, int fuse
 
 static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fuse_rows, int par_bytes, MfmaPlan *pl)
 {
-    const int bps = fmt == 0 ? 1 : 2, bpb = fmt == 0 ? 32 : 16;
+    const int bps = fmt == 1 ? 2 : 1, bpb = fmt == 1 ? 16 : 32;
     const int rows = worst_region_rows(g, PT, PT);
     for (int ccw = g.cw; ccw >= 1; --ccw) {
         if (g.cw % ccw) continue;
@@ -494,8 +512,8 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     MfmaPlan pl;
     constexpr int FROWS = FUSE ? WF + FT / 32 : 0, PARB = (FUSE ? 3 : 1) * FT * 4;
     if (!make_plan(g, PT, FMT, g_lds_budget, FROWS, PARB, &pl)) return XNOR_ERR_UNSUPPORTED;
-    const size_t lds = plan_lds_bytes(pl, FMT == 0 ? 1 : 2, g.wp, PT, FROWS, PARB);
-    pl.lut_offset = plan_lut_offset(pl, FMT == 0 ? 1 : 2, g.wp, PT, FROWS, PARB);
+    const size_t lds = plan_lds_bytes(pl, FMT == 1 ? 2 : 1, g.wp, PT, FROWS, PARB);
+    pl.lut_offset = plan_lut_offset(pl, FMT == 1 ? 2 : 1, g.wp, PT, FROWS, PARB);
     // two builds of every tiling: weight records consecutive (one chunk holds all channel words) or not
     // (a chunk of a 1x1 filter is a run of consecutive records too)
     const bool linear = pl.tap_jump == 0 || g.taps == 1;
@@ -519,7 +537,7 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
         grid = dim3((unsigned)wg, 1u);
     }
     if (grid.y > 65535u) return XNOR_ERR_UNSUPPORTED;
-    const size_t img_bytes = FMT == 0 ? wimg_i8_bytes(g.k_out, g.c, g.taps) : wimg_f4_bytes(g.k_out, g.c, g.taps);
+    const size_t img_bytes = FMT == 1 ? wimg_f4_bytes(g.k_out, g.c, g.taps) : wimg_i8_bytes(g.k_out, g.c, g.taps);
     if (img_bytes > 0x7fffffffull) return XNOR_ERR_UNSUPPORTED;
     kern<<<grid, block, lds, stream>>>(xbits, reinterpret_cast<const v4i *>(wimg), (uint32_t)img_bytes, K, A, alpha,
                                        out, dot_out, g, pl, FUSE ? *fz : FuseArgs{});
@@ -563,14 +581,20 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
         }
     }
     // the fused epilogue is built for the tiles marked F (the default choices and the wide-filter ones)
+    // (the bfloat16-parts format is built for the default tilings only, and without the fused epilogue)
 #define XNOR_TILE(ID, FW, PW, WF, WP)                                                                     \
     case ID:                                                                                              \
-        if (fz) return XNOR_ERR_UNSUPPORTED;                                                              \
-        return launch_cfg<FMT, FW, PW, WF, WP, false>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, nullptr)
+        if constexpr (FMT == 2) return XNOR_ERR_UNSUPPORTED;                                              \
+        else {                                                                                            \
+            if (fz) return XNOR_ERR_UNSUPPORTED;                                                          \
+            return launch_cfg<FMT, FW, PW, WF, WP, false>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, nullptr); \
+        }
 #define XNOR_TILE_F(ID, FW, PW, WF, WP)                                                                   \
     case ID:                                                                                              \
-        if (fz) return launch_cfg<FMT, FW, PW, WF, WP, true>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, fz); \
-        return launch_cfg<FMT, FW, PW, WF, WP, false>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, nullptr)
+        if constexpr (FMT != 2) {                                                                         \
+            if (fz) return launch_cfg<FMT, FW, PW, WF, WP, true>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, fz); \
+        }                                                                                                 \
+        return launch_cfg<FMT, FW, PW, WF, WP, false>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, nullptr);
     switch (tile) {
         XNOR_TILE_F(1, 2, 2, 2, 2);   // 128 filters x 128 pixels
         XNOR_TILE_F(2, 2, 2, 1, 4);   //  64 x 256
@@ -595,13 +619,16 @@ xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, 
                              const float *alpha, float *out, int32_t *dot_out,
                              const ConvGeom &g, hipStream_t stream, const FuseArgs *fz)
 {
-    if (g_tile_override == 10 && !fz) {      // persistent kernel where its LDS plan fits, tiled kernel otherwise
+    if (g_tile_override == 10 && !fz && fmt != 2) {      // persistent kernel where its LDS plan fits, tiled kernel otherwise
         const xnor_status s = launch_conv_mfma_pipe(fmt, xbits, wmfma, K, A, alpha, out, dot_out, g, stream);
         if (s != XNOR_ERR_UNSUPPORTED) return s;
     }
+    const uint8_t *img = static_cast<const uint8_t *>(wmfma);
+    // fmt 2: real activations in bfloat16 parts (xbits = 32-byte words, g.c = 32 x words per pixel,
+    // wmfma = the +-1 bfloat16 record image alone); no K, no fused epilogue
+    if (fmt == 2) return fz ? XNOR_ERR_UNSUPPORTED : launch_fmt<2>(xbits, img, nullptr, nullptr, alpha, out, nullptr, g, stream, nullptr);
     // float accumulation of the 4-bit path is exact while every sum stays below 2^24
     if (fmt != 0 && (long long)g.c * g.taps >= (1ll << 24)) return XNOR_ERR_UNSUPPORTED;
-    const uint8_t *img = static_cast<const uint8_t *>(wmfma);
     if (fmt == 0) return launch_fmt<0>(xbits, img, K, A, alpha, out, dot_out, g, stream, fz);
     img += wimg_i8_bytes(g.k_out, g.c, g.taps);
     return launch_fmt<1>(xbits, img, K, A, alpha, out, dot_out, g, stream, fz);

@@ -188,6 +188,27 @@ constexpr int ring_lcm(int a, int b)
     return m;
 }
 
+// Binary-Weight-Network operands (sec. 3.1: real inputs, +-1 weights).  The real activations arrive
+// pre-split into three bfloat16 parts (hi + mid + lo == the float exactly), 16 channels x one part
+// = one 32-byte "word" per pixel; the weights are +-1.0 (0 past the last channel or filter) in
+// bfloat16, the same record for each of the three parts.  Products are exact, accumulation is
+// float: the result is the float sum of exact terms.  Layout-wise this is the int8 encoding (32
+// bytes per pixel and word, the half-wave picks its 16 bytes), with nothing to widen.
+template <> struct Enc<2> {
+    static constexpr int BPS = 1;
+    static constexpr int BPB = 32;
+    typedef v16f acc_t;
+    typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+    static __device__ __forceinline__ acc_t mfma(v4i w, v4i x, acc_t c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, w), __builtin_bit_cast(v8bf, x), c, 0, 0,
+                                                       0);
+    }
+    static __device__ __forceinline__ int to_int(acc_t a, int v) { return (int)a[v]; }
+    static __device__ __forceinline__ float to_float(acc_t a, int v) { return a[v]; }
+    static constexpr int LUT_BYTES = 0;
+    static __device__ __forceinline__ void build_lut(uint8_t *, int, int) {}
+};
+
 // Steps the offset table is padded by beyond the last K-step (copies of the last entry): operand
 // prefetches run ahead of the loop's end by at most one turn plus the activation depth.
 constexpr int KLOOP_TABLE_PAD = 12;

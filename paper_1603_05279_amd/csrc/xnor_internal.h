@@ -111,6 +111,9 @@ xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, 
                              const float *alpha, float *out, int32_t *dot_out,
                              const ConvGeom &g, hipStream_t stream, const FuseArgs *fz = nullptr);
 void set_mfma_tuning(int tile, int lds_budget);
+// Binary-Weight-Network preparation kernels (bwn.hip); the convolution itself is launch_conv_mfma with fmt 2
+xnor_status launch_bwn_split(const float *x, void *parts, int n, int c, int hw, hipStream_t stream);
+xnor_status launch_bwn_pack(const float *w, float *alpha, void *wimg, int k_out, int c, int taps, hipStream_t stream);
 // persistent, role-split form of the same kernel (conv_mfma_pipe.hip)
 xnor_status launch_conv_mfma_pipe(int fmt, const uint32_t *xbits, const void *wmfma, const float *K,
                                   const float *A, const float *alpha, float *out, int32_t *dot_out,

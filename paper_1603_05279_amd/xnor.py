@@ -19,7 +19,9 @@ EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor
            "xnor_set_tuning",
            "xnor_binarize_pack", "xnor_compute_K", "xnor_binactiv", "xnor_pack_weights",
            "xnor_conv2d", "xnor_linear",
-           "xnor_conv2d_binactiv_workspace_bytes", "xnor_conv2d_binactiv", "xnor_pool_binactiv"]
+           "xnor_conv2d_binactiv_workspace_bytes", "xnor_conv2d_binactiv", "xnor_pool_binactiv",
+           "xnor_bwn_parts_bytes", "xnor_bwn_wimg_bytes", "xnor_bwn_split", "xnor_bwn_pack_weights",
+           "xnor_bwn_conv2d"]
 
 
 class XnorError(RuntimeError):
@@ -73,6 +75,16 @@ def lib():
         L.xnor_conv2d_binactiv.restype = ip
         L.xnor_pool_binactiv.argtypes = [vp] * 5 + [ip] * 11 + [vp]
         L.xnor_pool_binactiv.restype = ip
+        L.xnor_bwn_parts_bytes.argtypes = [ip, ip, ip, ip]
+        L.xnor_bwn_parts_bytes.restype = ctypes.c_size_t
+        L.xnor_bwn_wimg_bytes.argtypes = [ip, ip, ip, ip]
+        L.xnor_bwn_wimg_bytes.restype = ctypes.c_size_t
+        L.xnor_bwn_split.argtypes = [vp, vp, ip, ip, ip, ip, vp]
+        L.xnor_bwn_split.restype = ip
+        L.xnor_bwn_pack_weights.argtypes = [vp, vp, vp, ip, ip, ip, ip, vp]
+        L.xnor_bwn_pack_weights.restype = ip
+        L.xnor_bwn_conv2d.argtypes = [vp, vp, vp, vp, ctypes.POINTER(ConvDesc), vp]
+        L.xnor_bwn_conv2d.restype = ip
         _lib = L
     return _lib
 
@@ -156,6 +168,31 @@ def xnor_pool_binactiv(x, bn_scale, bn_shift, xbits, A, n, c, h_in, w_in, pool, 
         _ptr(x, torch.float32), _ptr(bn_scale, torch.float32), _ptr(bn_shift, torch.float32),
         _ptr(xbits, torch.int32), _ptr(A, torch.float32), n, c, h_in, w_in, pool[0], pool[1], stride[0], stride[1],
         pad[0], pad[1], int(bool(relu)), _stream(stream)))
+
+
+def bwn_parts_bytes(n, c, h, w):
+    return int(lib().xnor_bwn_parts_bytes(n, c, h, w))
+
+
+def bwn_wimg_bytes(k_out, c, kh, kw):
+    return int(lib().xnor_bwn_wimg_bytes(k_out, c, kh, kw))
+
+
+def xnor_bwn_split(x, parts, n, c, h, w, stream=None):
+    _check("xnor_bwn_split", lib().xnor_bwn_split(_ptr(x, torch.float32), _ptr(parts, torch.uint8), n, c, h, w,
+                                                  _stream(stream)))
+
+
+def xnor_bwn_pack_weights(w, alpha, wimg, k_out, c, kh, kw, stream=None):
+    _check("xnor_bwn_pack_weights", lib().xnor_bwn_pack_weights(
+        _ptr(w, torch.float32), _ptr(alpha, torch.float32), _ptr(wimg, torch.uint8), k_out, c, kh, kw,
+        _stream(stream)))
+
+
+def xnor_bwn_conv2d(parts, wimg, alpha, out, desc, stream=None):
+    _check("xnor_bwn_conv2d", lib().xnor_bwn_conv2d(
+        _ptr(parts, torch.uint8), _ptr(wimg, torch.uint8), _ptr(alpha, torch.float32), _ptr(out, torch.float32),
+        ctypes.byref(desc), _stream(stream)))
 
 
 def xnor_pack_weights(w, wbits, alpha, wmfma, k_out, c, kh, kw, stream=None):

@@ -316,6 +316,29 @@ def test_max_pool_matches_library_routine_and_hand_example():
         assert np.array_equal(xo.max_pool(x, pool, stride, pad, relu=True), np.maximum(ref, 0))
 
 
+def test_bwn_conv_is_the_float_convolution_with_alpha_sign_weights():
+    # Special case that is a library routine: a float64 convolution with the estimated weights
+    # alpha_k * sign(W_k) (sec. 3.1, W ~ alpha B), strides and padding included
+    rng = np.random.default_rng(41)
+    for (n, c, h, w, k, kh, kw, stride, pad) in [(2, 5, 7, 6, 4, 3, 3, (1, 1), (1, 1)), (1, 3, 9, 9, 6, 2, 3, (2, 1), (0, 1)),
+                                                 (2, 17, 5, 5, 3, 5, 5, (1, 1), (2, 2))]:
+        x = rng.standard_normal((n, c, h, w)).astype(np.float32)
+        W = rng.standard_normal((k, c, kh, kw)).astype(np.float32)
+        r = xo.bwn_conv2d(x, W, stride, pad)
+        West = (r["alpha"][:, None, None, None] * np.where(W >= 0, 1.0, -1.0))
+        ref = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(West), None, stride, pad).numpy()
+        np.testing.assert_allclose(r["out"], ref, rtol=1e-6, atol=1e-7)
+    # hand-worked: one pixel, three channels, weights (+,-,+) of magnitudes 1,2,3 -> alpha = 2
+    x = np.array([0.5, 4.0, -1.5], np.float32).reshape(1, 3, 1, 1)
+    W = np.array([1.0, -2.0, 3.0], np.float32).reshape(1, 3, 1, 1)
+    assert xo.bwn_conv2d(x, W)["out"].item() == 2.0 * (0.5 - 4.0 - 1.5)
+    # W already of the form alpha * B: the estimate is exact, so BWN equals the true convolution
+    B = np.where(rng.standard_normal((4, 6, 3, 3)) >= 0, 1.0, -1.0).astype(np.float32) * 0.25
+    x = rng.standard_normal((1, 6, 8, 8)).astype(np.float32)
+    ref = torch.nn.functional.conv2d(torch.from_numpy(x).double(), torch.from_numpy(B).double(), None, 1, 1).numpy()
+    np.testing.assert_allclose(xo.bwn_conv2d(x, B, (1, 1), (1, 1))["out"], ref, rtol=1e-6, atol=1e-7)
+
+
 # ----------------------------------------------------------- op-count model (sec. 4.1)
 def test_speedup_model_matches_printed_value():
     rows = [l.split() for l in open(os.path.join(GOLDEN, "speedup_model.txt")) if l.strip() and not l.startswith("#")]
