@@ -569,12 +569,19 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
         };
         const int cus = 256;
         auto waste = [&](long long w) { return (double)((w + cus - 1) / cus * cus) / (double)w; };
-        if (g.k_out <= 128) tile = !fz ? 11 : g.k_out <= 64 ? 2 : 1;
+        if (FMT == 2) {
+            // real activations (bfloat16 parts): the K loop is 24 times longer per channel, so the
+            // tiles with the larger register blocks win wherever the filter count fills them
+            if (g.k_out <= 64) tile = 2;
+            else if (g.k_out <= 128) tile = 1;
+            else if (g.k_out <= 256) tile = waste(wgs(256, 96)) <= waste(wgs(256, 128)) ? 4 : 5;
+            else tile = (g.k_out + 255) / 256 * 256 * 10 <= g.k_out * 11 ? 5 : 1;
+        } else if (g.k_out <= 128) tile = !fz ? 11 : g.k_out <= 64 ? 2 : 1;
         else if (g.k_out <= 256) tile = waste(wgs(256, 96)) <= waste(wgs(256, 128)) ? 4 : 5;
         else tile = 1;
         const long long w0 = tile == 11 ? wgs(64, 128) : tile == 2 ? wgs(64, 256) : tile == 4 ? wgs(256, 96)
                              : tile == 5 ? wgs(256, 128) : wgs(128, 128);
-        if (w0 < 200) {
+        if (w0 < (FMT == 2 ? 128 : 200)) {
             if (wgs(64, 128) >= cus) tile = 11;
             else if (wgs(128, 64) >= cus) tile = 13;
             else tile = 14;       // 128 x 32 (measured ahead of 64 x 64 at equal workgroup count)
