@@ -199,3 +199,66 @@ void xo_bwn(const float *I, const int8_t *sW, const double *alpha, float *out,
         free(acc);
     }
 }
+
+/* Binary gradient (sec. 3.2, paragraph "Binary Gradient"): in the backward pass the gradient
+ * that meets the weight filters in a convolution is binarised like the forward input, with the
+ * largest magnitude of the tensor as its scaling factor (not the mean of eq. alpha = |W|_1/n).
+ * The forward layer is out = dot * K * alpha_k with dot = sign(I) (*) sign(W), so the gradient
+ * that reaches the binary convolution is gd = g_out * alpha_k * K (two float multiplies in this
+ * order: the float value decides the sign bit).  Readings: one scaling factor per image,
+ * m_b = max |gd[b]|; sign(gd) by the comparison rule of sec. 3.1; K and alpha may be absent (= 1).
+ * The data-gradient convolution is the transpose of the forward correlation, written out as
+ * the scatter it is: every output position adds sign(gd) * sign(W) to the input positions its
+ * window covered (padded positions receive nothing).  Exact integers; g_in = m_b * dot_t.
+ *   sg [n][k][ho][wo] int8, gmax [n], dot_t [n][c][h][w] int32, gin [n][c][h][w] float. */
+void xo_bingrad(const float *g, const float *K, const float *alpha, const int8_t *sW,
+                int8_t *sg, float *gmax, int32_t *dot_t, float *gin,
+                int n, int c, int h, int w, int k_out, int kh, int kw,
+                int stride_h, int stride_w, int pad_h, int pad_w)
+{
+    const int ho = (h + 2 * pad_h - kh) / stride_h + 1;
+    const int wo = (w + 2 * pad_w - kw) / stride_w + 1;
+    const size_t plane = (size_t)ho * wo;
+    for (int b = 0; b < n; ++b) {
+        float m = 0.0f;
+        for (int k = 0; k < k_out; ++k)
+            for (size_t p = 0; p < plane; ++p) {
+                const size_t i = ((size_t)b * k_out + k) * plane + p;
+                float gd = g[i];
+                if (alpha)
+                    gd = gd * alpha[k];
+                if (K)
+                    gd = gd * K[(size_t)b * plane + p];
+                sg[i] = gd >= 0.0f ? 1 : -1;
+                if (fabsf(gd) > m)
+                    m = fabsf(gd);
+            }
+        gmax[b] = m;
+    }
+    const long jobs = (long)n * c;
+#pragma omp parallel for schedule(static)
+    for (long job = 0; job < jobs; ++job) {
+        const int b = (int)(job / c), ch = (int)(job % c);
+        int32_t *dst = dot_t + (size_t)job * h * w;
+        for (int i = 0; i < h * w; ++i)
+            dst[i] = 0;
+        for (int k = 0; k < k_out; ++k)
+            for (int oy = 0; oy < ho; ++oy)
+                for (int ox = 0; ox < wo; ++ox) {
+                    const int s = sg[((size_t)b * k_out + k) * plane + (size_t)oy * wo + ox];
+                    for (int dy = 0; dy < kh; ++dy) {
+                        const int iy = oy * stride_h - pad_h + dy;
+                        if (iy < 0 || iy >= h)
+                            continue;
+                        for (int dx = 0; dx < kw; ++dx) {
+                            const int ix = ox * stride_w - pad_w + dx;
+                            if (ix < 0 || ix >= w)
+                                continue;
+                            dst[iy * w + ix] += s * sW[(((size_t)k * c + ch) * kh + dy) * kw + dx];
+                        }
+                    }
+                }
+        for (int i = 0; i < h * w; ++i)
+            gin[(size_t)job * h * w + i] = (float)((double)gmax[b] * (double)dst[i]);
+    }
+}

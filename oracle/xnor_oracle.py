@@ -169,6 +169,36 @@ def bwn_conv2d(x, W, stride=(1, 1), pad=(0, 0)):
     return {"out": out, "alpha": a}
 
 
+def binary_grad_input(g_out, W, K=None, alpha_=None, stride=(1, 1), pad=(0, 0), in_hw=None):
+    """Binary-gradient data-gradient convolution (sec. 3.2, "Binary Gradient"): the gradient reaching the
+    binary convolution, gd = g_out * alpha_k * K (float32 products), is replaced by max|gd| * sign(gd)
+    (one maximum per image) and convolved with sign(W) by the transpose of the forward correlation.
+    g_out [n][k][ho][wo], W [k][c][kh][kw], K [n][ho][wo] or None, alpha_ [k] or None; in_hw = (h, w) of the
+    forward input (default: the smallest input that gives ho x wo).
+    Returns dict(sg int8, gmax float32 [n], dot int32 [n][c][h][w], gin float32 [n][c][h][w])."""
+    g_out = np.ascontiguousarray(g_out, dtype=np.float32)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    n, k, ho, wo = g_out.shape
+    k2, c, kh, kw = W.shape
+    assert k == k2
+    if in_hw is None:
+        in_hw = ((ho - 1) * stride[0] + kh - 2 * pad[0], (wo - 1) * stride[1] + kw - 2 * pad[1])
+    h, w = in_hw
+    assert out_hw(h, w, kh, kw, stride, pad) == (ho, wo)
+    Kf = None if K is None else np.ascontiguousarray(K, dtype=np.float32)
+    af = None if alpha_ is None else np.ascontiguousarray(alpha_, dtype=np.float32)
+    sW = sign(W)
+    sg = np.empty(g_out.shape, dtype=np.int8)
+    gmax = np.empty((n,), dtype=np.float32)
+    dot = np.empty((n, c, h, w), dtype=np.int32)
+    gin = np.empty((n, c, h, w), dtype=np.float32)
+    _load().xo_bingrad(_p(g_out, ctypes.c_float), _p(Kf, ctypes.c_float), _p(af, ctypes.c_float),
+                       _p(sW, ctypes.c_int8), _p(sg, ctypes.c_int8), _p(gmax, ctypes.c_float),
+                       _p(dot, ctypes.c_int32), _p(gin, ctypes.c_float),
+                       n, c, h, w, k, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    return {"sg": sg, "gmax": gmax, "dot": dot, "gin": gin}
+
+
 def binary_linear(x, W):
     """Fully connected layer as the convolution whose filter covers the whole input
     (footnote of sec. 1): x [batch][in_f], W [out_f][in_f].  Returns dict(dot, K, alpha, out)

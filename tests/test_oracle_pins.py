@@ -349,3 +349,69 @@ def test_speedup_model_matches_printed_value():
     # depends on channels and filter size, not on the input size
     assert opcount.theoretical_speedup(256, 9, 196) == pytest.approx(opcount.theoretical_speedup(256, 9, 10 ** 6))
     assert opcount.theoretical_speedup(3, 1) < 3.0          # why first/last layers stay real-valued
+
+
+# ----------------------------------------- binary gradient (sec. 3.2, "Binary Gradient")
+BINGRAD_CASES = [(2, 5, 7, 6, 4, 3, 3, (1, 1), (1, 1)), (1, 3, 9, 9, 6, 2, 3, (2, 1), (0, 1)),
+                 (2, 17, 5, 5, 3, 5, 5, (1, 1), (2, 2)), (3, 4, 8, 7, 5, 3, 2, (2, 2), (1, 0))]
+
+
+def test_binary_gradient_is_the_library_transposed_convolution_of_the_signs():
+    # The integer map is the gradient of the forward +-1 correlation with respect to its input, evaluated
+    # at grad_output = sign(gd): a library routine (autograd of a float64 convolution, exact on integers).
+    rng = np.random.default_rng(51)
+    for (n, c, h, w, k, kh, kw, stride, pad) in BINGRAD_CASES:
+        ho, wo = xo.out_hw(h, w, kh, kw, stride, pad)
+        g = rng.standard_normal((n, k, ho, wo)).astype(np.float32)
+        W = rng.standard_normal((k, c, kh, kw)).astype(np.float32)
+        r = xo.binary_grad_input(g, W, None, None, stride, pad, in_hw=(h, w))
+        assert np.array_equal(r["sg"], np.where(g >= 0, 1, -1))
+        x = torch.zeros((n, c, h, w), dtype=torch.float64, requires_grad=True)
+        y = torch.nn.functional.conv2d(x, torch.from_numpy(np.where(W >= 0, 1.0, -1.0)), None, stride, pad)
+        y.backward(torch.from_numpy(r["sg"].astype(np.float64)))
+        assert np.array_equal(r["dot"], x.grad.numpy().astype(np.int32))
+        # scaling factor: the largest magnitude of each image's gradient, not its mean
+        assert np.array_equal(r["gmax"], np.abs(g).reshape(n, -1).max(axis=1))
+        np.testing.assert_allclose(r["gin"], r["gmax"][:, None, None, None].astype(np.float64) * r["dot"], rtol=1e-7)
+
+
+def test_binary_gradient_is_the_adjoint_of_the_forward_dot():
+    # <dot(sI, sW), sg> == <sI, dot_t(sg, sW)> for any +-1 tensors: ties the backward routine to the forward
+    # one (itself pinned above) through an identity of integer arithmetic; catches a flipped or
+    # transposed filter, a wrong padding offset, a dropped tap
+    rng = np.random.default_rng(52)
+    for (n, c, h, w, k, kh, kw, stride, pad) in BINGRAD_CASES:
+        ho, wo = xo.out_hw(h, w, kh, kw, stride, pad)
+        x = rng.standard_normal((n, c, h, w)).astype(np.float32)
+        g = rng.standard_normal((n, k, ho, wo)).astype(np.float32)
+        W = rng.standard_normal((k, c, kh, kw)).astype(np.float32)
+        fwd = xo.dot_map(xo.sign(x), xo.sign(W), stride, pad).astype(np.int64)
+        r = xo.binary_grad_input(g, W, None, None, stride, pad, in_hw=(h, w))
+        lhs = int((fwd * r["sg"]).sum())
+        rhs = int((xo.sign(x).astype(np.int64) * r["dot"]).sum())
+        assert lhs == rhs
+
+
+def test_binary_gradient_scaling_uses_alpha_and_K_in_float():
+    # gd = (g * alpha_k) * K in float32 decides sign and maximum; hand-worked 1x1 case:
+    # two filters, one channel, W = (+3, -2): alpha = (3, 2); K = 0.5; g = (1, -4) at the single pixel
+    g = np.array([1.0, -4.0], np.float32).reshape(1, 2, 1, 1)
+    W = np.array([3.0, -2.0], np.float32).reshape(2, 1, 1, 1)
+    K = np.full((1, 1, 1), 0.5, np.float32)
+    r = xo.binary_grad_input(g, W, K, xo.alpha(W).astype(np.float32))
+    assert r["gmax"].tolist() == [4.0]                 # max(|1*3*0.5|, |-4*2*0.5|)
+    assert r["sg"].ravel().tolist() == [1, -1]
+    assert r["dot"].item() == 1 * 1 + (-1) * (-1)      # sign(g) . sign(W) over the two filters
+    assert r["gin"].item() == 8.0
+    # a product that underflows to -0.0 takes the sign +1 (comparison rule), like the forward input
+    g = np.array([-1e-30], np.float32).reshape(1, 1, 1, 1)
+    r = xo.binary_grad_input(g, np.ones((1, 1, 1, 1), np.float32), np.full((1, 1, 1), 1e-30, np.float32),
+                             np.ones((1,), np.float32))
+    assert r["sg"].item() == 1 and r["gmax"].item() == 0.0
+    # 1x1 filters: the map is a plain matrix product over the filter axis at every pixel
+    rng = np.random.default_rng(53)
+    g = rng.standard_normal((2, 6, 4, 5)).astype(np.float32)
+    W = rng.standard_normal((6, 3, 1, 1)).astype(np.float32)
+    r = xo.binary_grad_input(g, W)
+    ref = np.einsum("nkyx,kc->ncyx", np.where(g >= 0, 1, -1), np.where(W[:, :, 0, 0] >= 0, 1, -1))
+    assert np.array_equal(r["dot"], ref)
