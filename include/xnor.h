@@ -212,6 +212,38 @@ int xnor_bwn_conv2d(const void *parts, const void *wimg, const float *alpha, flo
                     const xnor_conv_desc *d, void *hip_stream);
 
 /*
+ * Binary gradient (sec. 3.2, paragraph "Binary Gradient"): the backward convolution between the weight
+ * filters and the incoming gradient, with that gradient binarised and scaled by its largest magnitude
+ * (not by its mean).  d is always the FORWARD layer's descriptor (input n x c x h_in x w_in, k_out filters);
+ * only stride 1 is built (XNOR_ERR_UNSUPPORTED otherwise).  All pointers are device pointers, 16-byte
+ * aligned, caller-owned; work is enqueued on hip_stream without synchronising.
+ *
+ *   xnor_bingrad_pack_weights  w float32 [k_out][c][kh][kw] (the forward tensor)  ->  the filters of the
+ *       backward convolution, sign(W) rotated by 180 degrees with the channel axes exchanged:
+ *       wtbits uint32 [c][kh*kw][ceil(k_out/32)], wtmfma = xnor_wmfma_bytes(c, k_out, kh, kw) bytes (may be
+ *       NULL: vector-ALU path only), ones float32 [c] (written with 1.0, the per-filter factor of that
+ *       convolution).  Once per layer.
+ *   xnor_bingrad_binarize      g_out float32 [n][k_out][h_out][w_out], K float32 [n][h_out][w_out] or NULL,
+ *       alpha float32 [k_out] or NULL  ->  gbits uint32 [n][h_out][w_out][ceil(k_out/32)]: bit = (gd >= 0) with
+ *       gd = (g_out * alpha_k) * K in float32, the gradient that reaches the binary dot product of the forward
+ *       layer out = dot * K * alpha (absent factors count as 1); gmax float32 [n] = max |gd| over the image
+ *       (0 for an all-zero image, NaN magnitudes ignored).  Two launches (gmax is cleared first).
+ *   xnor_bingrad_conv2d        gbits, wtbits, wtmfma, gmax, ones  ->  g_in float32 [n][c][h_in][w_in] =
+ *       gmax[n] * sum over filters and taps of sign(gd) * sign(W) (positions that were padding in the forward
+ *       pass receive and contribute nothing); dot_out int32 [n][c][h_in][w_in] (may be NULL) = the integer sum.
+ *       scale_plane float32 [n][h_in][w_in] is scratch the caller provides (overwritten).  algo as xnor_conv2d.
+ * The straight-through factor of sign() on the forward input and the gradient through K are not part of
+ * these calls.
+ */
+int xnor_bingrad_pack_weights(const float *w, uint32_t *wtbits, float *ones, void *wtmfma,
+                              int k_out, int c, int kh, int kw, void *hip_stream);
+int xnor_bingrad_binarize(const float *g_out, const float *K, const float *alpha, uint32_t *gbits,
+                          float *gmax, const xnor_conv_desc *d, void *hip_stream);
+int xnor_bingrad_conv2d(const uint32_t *gbits, const uint32_t *wtbits, const void *wtmfma,
+                        const float *gmax, const float *ones, float *scale_plane, float *g_in,
+                        int32_t *dot_out, const xnor_conv_desc *d, int algo, void *hip_stream);
+
+/*
  * Fully connected layer = convolution whose filter covers the whole input (footnote of sec. 1).
  *   xbits [batch][Fw], wbits [out_features][Fw], Fw = ceil(in_features/32)
  *   Krow  [batch]  = mean_j |x[b][j]|  (xnor_compute_K / xnor_binactiv with c = in_features, 1x1)

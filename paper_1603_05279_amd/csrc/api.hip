@@ -280,6 +280,55 @@ int xnor_bwn_conv2d(const void *parts, const void *wimg, const float *alpha, flo
                             (hipStream_t)hip_stream);
 }
 
+int xnor_bingrad_pack_weights(const float *w, uint32_t *wtbits, float *ones, void *wtmfma,
+                              int k_out, int c, int kh, int kw, void *hip_stream)
+{
+    if (!w || !wtbits || !ones) return XNOR_ERR_NULL;
+    if (k_out <= 0 || c <= 0 || kh <= 0 || kw <= 0) return XNOR_ERR_SHAPE;
+    if ((long long)kh * kw > 4096 || (long long)c * kh * kw * ((k_out + 31) / 32) > 0x7fffffffLL ||
+        (long long)k_out * kh * kw > 0x7fffffffLL || (long long)k_out * c * kh * kw > 0x7fffffffLL)
+        return XNOR_ERR_SHAPE;
+    if (!aligned16(w) || !aligned16(wtbits) || !aligned16(ones) || !aligned16(wtmfma)) return XNOR_ERR_ALIGN;
+    // the backward convolution has c filters over k_out channels
+    return launch_pack_weights(w, wtbits, ones, wtmfma, c, k_out, kh * kw, (hipStream_t)hip_stream, true);
+}
+
+int xnor_bingrad_binarize(const float *g_out, const float *K, const float *alpha, uint32_t *gbits,
+                          float *gmax, const xnor_conv_desc *d, void *hip_stream)
+{
+    if (!g_out || !gbits || !gmax) return XNOR_ERR_NULL;
+    ConvGeom g;
+    if (xnor_status s = make_geom(d, &g)) return s;
+    if ((long long)g.m_total * ((g.k_out + 31) / 32) > 0x7fffffffLL) return XNOR_ERR_SHAPE;
+    if (!aligned16(g_out) || !aligned16(K) || !aligned16(alpha) || !aligned16(gbits) || !aligned16(gmax))
+        return XNOR_ERR_ALIGN;
+    return launch_bingrad_binarize(g_out, K, alpha, gbits, gmax, g.n, g.k_out, g.ho * g.wo, (hipStream_t)hip_stream);
+}
+
+int xnor_bingrad_conv2d(const uint32_t *gbits, const uint32_t *wtbits, const void *wtmfma,
+                        const float *gmax, const float *ones, float *scale_plane, float *g_in,
+                        int32_t *dot_out, const xnor_conv_desc *d, int algo, void *hip_stream)
+{
+    if (!gbits || !wtbits || !gmax || !ones || !scale_plane || !g_in) return XNOR_ERR_NULL;
+    ConvGeom fwd;
+    if (xnor_status s = make_geom(d, &fwd)) return s;
+    if (fwd.sh != 1 || fwd.sw != 1) return XNOR_ERR_UNSUPPORTED;
+    // transpose of a stride-1 correlation: a stride-1 correlation of the h_out x w_out gradient (k_out
+    // channels) with c rotated filters and padding kh-1-pad, which gives back h_in x w_in
+    xnor_conv_desc t;
+    t.n = fwd.n; t.c = fwd.k_out; t.h_in = fwd.ho; t.w_in = fwd.wo;
+    t.k_out = fwd.c; t.kh = fwd.kh; t.kw = fwd.kw;
+    t.stride_h = 1; t.stride_w = 1;
+    t.pad_h = fwd.kh - 1 - fwd.ph; t.pad_w = fwd.kw - 1 - fwd.pw;
+    if (!aligned16(gmax) || !aligned16(scale_plane)) return XNOR_ERR_ALIGN;
+    ConvGeom g;
+    if (xnor_status s = make_geom(&t, &g)) return s;
+    if (g.ho != fwd.h || g.wo != fwd.w) return XNOR_ERR_SHAPE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (xnor_status s = launch_bingrad_scale_plane(gmax, scale_plane, fwd.n, fwd.h * fwd.w, st)) return s;
+    return xnor_conv2d(gbits, wtbits, wtmfma, scale_plane, nullptr, ones, g_in, dot_out, &t, algo, hip_stream);
+}
+
 int xnor_linear(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
                 const float *Krow, const float *alpha, float *out, int32_t *dot_out,
                 int batch, int in_features, int out_features, int algo, void *hip_stream)

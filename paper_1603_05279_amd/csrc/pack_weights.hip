@@ -14,6 +14,12 @@ namespace xnor {
 // b = t*cw + wd and taken two per record (record fb*ceil(taps*cw/2) + b/2); lane l owns the 32
 // channels of block 2*(b/2) + (l >> 5) as 32 nibbles, channel j in nibble j (low nibble first);
 // a block past the end is all zero.
+// TRANSPOSED: the filters of the data-gradient convolution of the backward pass (sec. 3.2, "Binary
+// Gradient"), read straight out of the forward tensor W [c][k_out][taps] (c = forward filters, k_out =
+// forward channels in this kernel's naming): filter k, channel ch, tap t is W[ch][k][taps - 1 - t], the
+// forward filter rotated by 180 degrees with the two channel axes exchanged.  alpha is then written as
+// 1 (the scaling factor of that convolution is the gradient's, applied per image).
+template <bool TRANSPOSED>
 __global__ __launch_bounds__(256) void pack_weights_kernel(
     const float *__restrict__ w, uint32_t *__restrict__ wbits, float *__restrict__ alpha,
     int8_t *__restrict__ wmfma, int k_out, int c, int taps, int cw)
@@ -23,7 +29,19 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
     const int tid = threadIdx.x;
     const bool real = k < k_out;
     const size_t n = (size_t)c * taps;
-    const float *wk = w + (size_t)(real ? k : 0) * n;
+    const int kk = real ? k : 0;
+    // element (channel ch, tap t) of this filter
+    struct Filter {
+        const float *base;
+        size_t ch_stride;
+        int taps;
+        __device__ float operator()(int ch, int t) const
+        {
+            return TRANSPOSED ? base[(size_t)ch * ch_stride + (taps - 1 - t)] : base[(size_t)ch * ch_stride + t];
+        }
+    };
+    const Filter wk{TRANSPOSED ? w + (size_t)kk * taps : w + (size_t)kk * n,
+                    TRANSPOSED ? (size_t)k_out * taps : (size_t)taps, taps};
 
     if (real) {
         for (int item = tid; item < taps * cw; item += 256) {
@@ -31,18 +49,22 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
             const int nch = min(32, c - wd * 32);
             uint32_t word = 0;
             for (int j = 0; j < nch; ++j)
-                word |= (wk[(size_t)(wd * 32 + j) * taps + t] >= 0.0f ? 1u : 0u) << j;
+                word |= (wk(wd * 32 + j, t) >= 0.0f ? 1u : 0u) << j;
             wbits[((size_t)k * taps + t) * cw + wd] = word;
         }
-        float s = 0.0f;
-        for (size_t i = tid; i < n; i += 256) s += __builtin_fabsf(wk[i]);
-        red[tid] = s;
-        __syncthreads();
-        for (int step = 128; step > 0; step >>= 1) {
-            if (tid < step) red[tid] += red[tid + step];
+        if (TRANSPOSED) {
+            if (tid == 0) alpha[k] = 1.0f;
+        } else {
+            float s = 0.0f;
+            for (size_t i = tid; i < n; i += 256) s += __builtin_fabsf(wk.base[i]);
+            red[tid] = s;
             __syncthreads();
+            for (int step = 128; step > 0; step >>= 1) {
+                if (tid < step) red[tid] += red[tid + step];
+                __syncthreads();
+            }
+            if (tid == 0) alpha[k] = red[0] / (float)n;
         }
-        if (tid == 0) alpha[k] = red[0] / (float)n;
     }
     if (wmfma) {
         const int fb = k >> 5, row = k & 31;
@@ -55,7 +77,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 int8_t s = 0;
-                if (real && ch0 + j < c) s = (wk[(size_t)(ch0 + j) * taps + t] >= 0.0f) ? 1 : -1;
+                if (real && ch0 + j < c) s = (wk(ch0 + j, t) >= 0.0f) ? 1 : -1;
                 u.b[j] = s;
             }
             const size_t rec = ((size_t)fb * taps + t) * cw + wd;
@@ -74,7 +96,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
                 for (int j = 0; j < 32; ++j) {
                     const int ch = wd * 32 + j;
                     uint32_t code = 0;
-                    if (ch < c) code = (wk[(size_t)ch * taps + t] >= 0.0f) ? 0x2u : 0xAu;
+                    if (ch < c) code = (wk(ch, t) >= 0.0f) ? 0x2u : 0xAu;
                     u.b[j >> 1] |= (uint8_t)(code << (4 * (j & 1)));
                 }
             }
@@ -89,7 +111,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
             if (real) {
                 const int nch = min(32, c - wd * 32);
                 for (int j = 0; j < nch; ++j)
-                    word |= (wk[(size_t)(wd * 32 + j) * taps + t] >= 0.0f ? 1u : 0u) << j;
+                    word |= (wk(wd * 32 + j, t) >= 0.0f ? 1u : 0u) << j;
             }
             wp[(((size_t)fb * taps + t) * cw + wd) * 32 + row] = word;
         }
@@ -101,12 +123,15 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
 }
 
 xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
-                                int k_out, int c, int taps, hipStream_t stream)
+                                int k_out, int c, int taps, hipStream_t stream, bool transposed)
 {
     const int cw = (c + 31) / 32;
     const int kpad = (k_out + 31) / 32 * 32;
     dim3 grid((unsigned)(wmfma ? kpad : k_out)), block(256);
-    pack_weights_kernel<<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw);
+    if (transposed)
+        pack_weights_kernel<true><<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw);
+    else
+        pack_weights_kernel<false><<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw);
     return hip_status(hipGetLastError());
 }
 

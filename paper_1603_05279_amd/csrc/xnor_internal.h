@@ -79,7 +79,12 @@ xnor_status launch_pool_binactiv(const float *x, const float *bn_scale, const fl
                                  int sh, int sw, int pad_h, int pad_w, int relu, hipStream_t stream);
 xnor_status launch_boxfilter(const float *A, float *K, const ConvGeom &g, hipStream_t stream);
 xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
-                                int k_out, int c, int taps, hipStream_t stream);
+                                int k_out, int c, int taps, hipStream_t stream, bool transposed = false);
+// Binary gradient (bingrad.hip): sign words of gd = g * alpha_k * K over the filters + per-image max |gd|;
+// a plane [n][hw] filled with each image's maximum
+xnor_status launch_bingrad_binarize(const float *g, const float *K, const float *alpha, uint32_t *gbits,
+                                    float *gmax, int n, int k_out, int hw, hipStream_t stream);
+xnor_status launch_bingrad_scale_plane(const float *gmax, float *plane, int n, int hw, hipStream_t stream);
 // K may be NULL in the convolution launchers: the kernels then compute it from A on the fly.
 // wmfma may be NULL (then the canonical wbits order is used, at a lower rate)
 xnor_status launch_conv_popcount(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma, const float *K, const float *A,

@@ -21,7 +21,8 @@ EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor
            "xnor_conv2d", "xnor_linear",
            "xnor_conv2d_binactiv_workspace_bytes", "xnor_conv2d_binactiv", "xnor_pool_binactiv",
            "xnor_bwn_parts_bytes", "xnor_bwn_wimg_bytes", "xnor_bwn_split", "xnor_bwn_pack_weights",
-           "xnor_bwn_conv2d"]
+           "xnor_bwn_conv2d",
+           "xnor_bingrad_pack_weights", "xnor_bingrad_binarize", "xnor_bingrad_conv2d"]
 
 
 class XnorError(RuntimeError):
@@ -85,6 +86,12 @@ def lib():
         L.xnor_bwn_pack_weights.restype = ip
         L.xnor_bwn_conv2d.argtypes = [vp, vp, vp, vp, ctypes.POINTER(ConvDesc), vp]
         L.xnor_bwn_conv2d.restype = ip
+        L.xnor_bingrad_pack_weights.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp]
+        L.xnor_bingrad_pack_weights.restype = ip
+        L.xnor_bingrad_binarize.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(ConvDesc), vp]
+        L.xnor_bingrad_binarize.restype = ip
+        L.xnor_bingrad_conv2d.argtypes = [vp] * 8 + [ctypes.POINTER(ConvDesc), ip, vp]
+        L.xnor_bingrad_conv2d.restype = ip
         _lib = L
     return _lib
 
@@ -193,6 +200,26 @@ def xnor_bwn_conv2d(parts, wimg, alpha, out, desc, stream=None):
     _check("xnor_bwn_conv2d", lib().xnor_bwn_conv2d(
         _ptr(parts, torch.uint8), _ptr(wimg, torch.uint8), _ptr(alpha, torch.float32), _ptr(out, torch.float32),
         ctypes.byref(desc), _stream(stream)))
+
+
+def xnor_bingrad_pack_weights(w, wtbits, ones, wtmfma, k_out, c, kh, kw, stream=None):
+    _check("xnor_bingrad_pack_weights", lib().xnor_bingrad_pack_weights(
+        _ptr(w, torch.float32), _ptr(wtbits, torch.int32), _ptr(ones, torch.float32),
+        _ptr(wtmfma, torch.uint8), k_out, c, kh, kw, _stream(stream)))
+
+
+def xnor_bingrad_binarize(g_out, K, alpha, gbits, gmax, desc, stream=None):
+    _check("xnor_bingrad_binarize", lib().xnor_bingrad_binarize(
+        _ptr(g_out, torch.float32), _ptr(K, torch.float32), _ptr(alpha, torch.float32), _ptr(gbits, torch.int32),
+        _ptr(gmax, torch.float32), ctypes.byref(desc), _stream(stream)))
+
+
+def xnor_bingrad_conv2d(gbits, wtbits, wtmfma, gmax, ones, scale_plane, g_in, dot_out, desc, algo=XNOR_ALGO_AUTO,
+                        stream=None):
+    _check("xnor_bingrad_conv2d", lib().xnor_bingrad_conv2d(
+        _ptr(gbits, torch.int32), _ptr(wtbits, torch.int32), _ptr(wtmfma, torch.uint8), _ptr(gmax, torch.float32),
+        _ptr(ones, torch.float32), _ptr(scale_plane, torch.float32), _ptr(g_in, torch.float32),
+        _ptr(dot_out, torch.int32), ctypes.byref(desc), int(algo), _stream(stream)))
 
 
 def xnor_pack_weights(w, wbits, alpha, wmfma, k_out, c, kh, kw, stream=None):
