@@ -143,6 +143,46 @@ def report(args):
                   f"{conv['popcount']:.1f} | {ba_us:.1f} | {block_us:.1f} | {tb:.0f} | {gbs:.0f} | "
                   f"{100 * 2 * tb / 10100:.1f} | {100 * gbs / 8000:.1f} | {100 * attain:.1f} | {pack_us:.1f} | "
                   f"{orc:.1f} |", flush=True)
+    # the widened rows: Binary-Weight-Network convolution and binary-gradient backward convolution
+    print("\n| config / layer | BWN split us | BWN conv us | bf16 TFLOP/s (3 parts) | % bf16 peak | fp32-equiv TFLOP/s | "
+          "grad binarize us | grad conv us | Tbinop/s (grad conv) |")
+    print("|---|---|---|---|---|---|---|---|---|")
+    for cfg in ("alexnet_conv2", "alexnet_conv345", "resnet18"):
+        for i, layer in enumerate(wl.config_layers(cfg)):
+            n, c, h, w_, k, kh, kw, st, pd = (layer.n, layer.c, layer.h, layer.w, layer.k_out, layer.kh, layer.kw,
+                                              layer.stride, layer.pad)
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(wl.config_seed(cfg, i))
+            x = torch.randn((n, c, h, w_), device="cuda", generator=gen)
+            wt = torch.randn((k, c, kh, kw), device="cuda", generator=gen)
+            desc = xnor.make_desc(n, c, h, w_, k, kh, kw, st, pd)
+            ho, wo = xnor.output_hw(desc)
+            u8 = lambda nbytes: torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
+            parts, wimg = u8(xnor.bwn_parts_bytes(n, c, h, w_)), u8(xnor.bwn_wimg_bytes(k, c, kh, kw))
+            alpha = torch.empty((k,), device="cuda")
+            out = torch.empty((n, k, ho, wo), device="cuda")
+            xnor.xnor_bwn_pack_weights(wt, alpha, wimg, k, c, kh, kw)
+            split_us = median_us(lambda: xnor.xnor_bwn_split(x, parts, n, c, h, w_))
+            bwn_us = median_us(lambda: xnor.xnor_bwn_conv2d(parts, wimg, alpha, out, desc))
+            flops = 2.0 * layer.bit_macs
+            row = (f"| {cfg} / {layer.name} | {split_us:.1f} | {bwn_us:.1f} | {3 * flops / bwn_us / 1e6:.0f} | "
+                   f"{100 * 3 * flops / bwn_us / 1e6 / 2500:.1f} | {flops / bwn_us / 1e6:.0f} |")
+            if st == 1:
+                Kp = torch.rand((n, ho, wo), device="cuda", generator=gen) + 0.5
+                kw32 = xnor.words_per_pixel(k)
+                wtbits = torch.empty((c, kh * kw, kw32), dtype=torch.int32, device="cuda")
+                wtmfma = u8(xnor.wmfma_bytes(c, k, kh, kw))
+                ones, gmax = torch.empty((c,), device="cuda"), torch.empty((n,), device="cuda")
+                gbits = torch.empty((n, ho, wo, kw32), dtype=torch.int32, device="cuda")
+                plane, gin = torch.empty((n, h, w_), device="cuda"), torch.empty((n, c, h, w_), device="cuda")
+                xnor.xnor_bingrad_pack_weights(wt, wtbits, ones, wtmfma, k, c, kh, kw)
+                gb_us = median_us(lambda: xnor.xnor_bingrad_binarize(out, Kp, alpha, gbits, gmax, desc))
+                gc_us = median_us(lambda: xnor.xnor_bingrad_conv2d(gbits, wtbits, wtmfma, gmax, ones, plane, gin, None,
+                                                                   desc, xnor.XNOR_ALGO_AUTO))
+                row += f" {gb_us:.1f} | {gc_us:.1f} | {layer.bit_macs / gc_us / 1e6:.0f} |"
+            else:
+                row += " - | - | - |"
+            print(row, flush=True)
     print(f"\nOracle: {xo.threads()} host threads.  % attainable = floor time at min(fp4 peak, arithmetic "
           "intensity x 8 TB/s) / measured time.  The paper's own figures: 58x measured, 62.27x modelled speed-up of "
           "binary over float convolution on its CPU, memory access excluded (sec. 4.1).")

@@ -15,6 +15,7 @@ namespace xnor {
 // is reduced over the wave by lane exchanges, over the waves in LDS, and merged into gmax[image] with an
 // integer atomic maximum on the float's bit pattern (|gd| >= 0, so the patterns order like the values;
 // the result does not depend on the order of arrival; NaN magnitudes are ignored).
+template <bool HAS_ALPHA, bool HAS_K>
 __global__ __launch_bounds__(256) void bingrad_binarize_kernel(
     const float *__restrict__ g, const float *__restrict__ K, const float *__restrict__ alpha,
     uint32_t *__restrict__ gbits, float *__restrict__ gmax, int c, int hw, int cw, int tiles_per_image)
@@ -24,13 +25,17 @@ __global__ __launch_bounds__(256) void bingrad_binarize_kernel(
     uint8_t *wbytes = smem + 16;                                        // [64 px][cw words][4 bytes]
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
-    const int img = blockIdx.x / tiles_per_image;
-    const int tile = blockIdx.x - img * tiles_per_image;
+    // workgroups go to the 8 XCDs round-robin; within every complete window of 64 tiles each XCD takes a
+    // run of 8 consecutive ones, so the cache lines that straddle tile boundaries hit in its own L2
+    const unsigned b = blockIdx.x, win = (b >> 6) << 6;
+    const int blk = (int)(win + 64u <= gridDim.x ? win + ((b & 7u) << 3) + ((b >> 3) & 7u) : b);
+    const int img = blk / tiles_per_image;
+    const int tile = blk - img * tiles_per_image;
     const int p0 = tile * 64, p = p0 + lane;
     const bool live = p < hw;
     const int pc = live ? p : hw - 1;
     const float *gi = g + (size_t)img * c * hw + pc;
-    const float kp = K ? K[(size_t)img * hw + pc] : 1.0f;
+    const float kp = HAS_K ? K[(size_t)img * hw + pc] : 1.0f;
     const int groups = (c + 7) >> 3;
     float m = 0.0f;
 #pragma unroll 4
@@ -44,8 +49,8 @@ __global__ __launch_bounds__(256) void bingrad_binarize_kernel(
         for (int j = 0; j < 8; ++j) {
             const int ch = min(ch0 + j, c - 1);
             float gd = v[j];
-            if (alpha) gd = gd * alpha[ch];
-            if (K) gd = gd * kp;
+            if (HAS_ALPHA) gd = gd * alpha[ch];
+            if (HAS_K) gd = gd * kp;
             const bool ok = ch0 + j < c && live;
             byte |= ((ok && gd >= 0.0f) ? 1u : 0u) << j;
             const float a = __builtin_fabsf(gd);
@@ -102,8 +107,11 @@ xnor_status launch_bingrad_binarize(const float *g, const float *K, const float 
     if (lds > 64 * 1024 || (long long)n * tiles > 0x7fffffffLL) return XNOR_ERR_UNSUPPORTED;
     // the maxima start at zero: cleared by a kernel, so that the sequence can be captured in a graph
     fill_zero_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream>>>(gmax, n);
-    bingrad_binarize_kernel<<<dim3((unsigned)(n * tiles)), dim3(256), lds, stream>>>(g, K, alpha, gbits, gmax,
-                                                                                       k_out, hw, cw, tiles);
+    const dim3 grid((unsigned)(n * tiles)), block(256);
+#define XNOR_BG(HA, HK) bingrad_binarize_kernel<HA, HK><<<grid, block, lds, stream>>>(g, K, alpha, gbits, gmax, k_out, hw, cw, tiles)
+    if (alpha) { if (K) XNOR_BG(true, true); else XNOR_BG(true, false); }
+    else       { if (K) XNOR_BG(false, true); else XNOR_BG(false, false); }
+#undef XNOR_BG
     return hip_status(hipGetLastError());
 }
 
