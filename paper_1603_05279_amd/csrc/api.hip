@@ -239,7 +239,7 @@ size_t xnor_bwn_parts_bytes(int n, int c, int h, int w)
 size_t xnor_bwn_wimg_bytes(int k_out, int c, int kh, int kw)
 {
     if (k_out <= 0 || c <= 0 || kh <= 0 || kw <= 0 || (long long)kh * kw > 4096) return 0;
-    return wimg_i8_bytes(k_out, 96 * ((c + 15) / 16), kh * kw);
+    return wimg_bf16_bytes(k_out, (c + 15) / 16, kh * kw);
 }
 
 int xnor_bwn_split(const float *x, void *parts, int n, int c, int h, int w, void *hip_stream)

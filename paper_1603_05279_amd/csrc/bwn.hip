@@ -54,9 +54,9 @@ xnor_status launch_bwn_split(const float *x, void *parts, int n, int c, int hw, 
 }
 
 // Weight side: alpha_k = ||W_k||_1 / n (sec. 3.1) and the +-1 bfloat16 record image
-// [filter block of 32][tap][word = 3*group + part] of 1 KiB records in matrix-operand lane order
-// (lane l: filter l & 31, channels 16*group + 8*(l >> 5) .. +7), the same record for the three
-// parts, plus one trailing all-zero record.  One workgroup per filter.
+// [filter block of 32][tap][16-channel group] of 1 KiB records in matrix-operand lane order
+// (lane l: filter l & 31, channels 16*group + 8*(l >> 5) .. +7); a record multiplies all three
+// parts of its group.  One trailing all-zero record.  One workgroup per filter.
 __global__ __launch_bounds__(256) void bwn_pack_kernel(const float *__restrict__ w, float *__restrict__ alpha,
                                                        uint16_t *__restrict__ wimg, int k_out, int c, int taps, int cg)
 {
@@ -73,17 +73,16 @@ __global__ __launch_bounds__(256) void bwn_pack_kernel(const float *__restrict__
         __syncthreads();
     }
     if (tid == 0) alpha[f] = red[0] / (float)nw;
-    // records: index ((fblk*taps + t)*cg + grp)*3 + part, 512 bfloat16 each; lane slot (f & 31) + 32*half holds 8 values
+    // records: index (fblk*taps + t)*cg + grp, 512 bfloat16 each; lane slot (f & 31) + 32*half holds 8 values
     const int fblk = f >> 5, row = f & 31;
     for (int i = tid; i < taps * cg * 16; i += 256) {
         const int t = i / (cg * 16), rem = i - t * cg * 16;
         const int grp = rem >> 4, j = rem & 15;           // channel 16*grp + j
         const int ch = grp * 16 + j;
         const uint16_t v = ch < c ? (wf[(size_t)ch * taps + t] >= 0.0f ? 0x3F80 : 0xBF80) : 0;
-        const size_t rec = ((size_t)(fblk * taps + t) * cg + grp) * 3;
+        const size_t rec = (size_t)(fblk * taps + t) * cg + grp;
         const int slot = (row + 32 * (j >> 3)) * 8 + (j & 7);
-#pragma unroll
-        for (int part = 0; part < 3; ++part) wimg[(rec + part) * 512 + slot] = v;
+        wimg[rec * 512 + slot] = v;
     }
 }
 
@@ -96,7 +95,7 @@ xnor_status launch_bwn_pack(const float *w, float *alpha, void *wimg, int k_out,
 {
     const int cg = (c + 15) / 16;
     // rows of the last filter block past k_out and the trailing record must read as zero
-    const size_t bytes = wimg_i8_bytes(k_out, 96 * cg, taps);      // 3*cg words of "32 channels" per pixel
+    const size_t bytes = wimg_bf16_bytes(k_out, cg, taps);
     bwn_clear_kernel<<<dim3(1024), dim3(256), 0, stream>>>(static_cast<uint32_t *>(wimg), bytes / 4);
     if (xnor_status s = hip_status(hipGetLastError())) return s;
     bwn_pack_kernel<<<dim3((unsigned)k_out), dim3(256), 0, stream>>>(w, alpha, static_cast<uint16_t *>(wimg), k_out, c,

@@ -34,7 +34,7 @@ __device__ long long *g_timeline = nullptr;
 
 // Accumulator tiles of up to 8 result blocks leave room for two waves per SIMD (256 registers each).
 template <int FMT, int FW, int PW, int WF, int WP, bool FUSE, bool LINEAR>
-__global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfma_kernel(
+__global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 1)) void conv_mfma_kernel(
     const uint32_t *__restrict__ xbits, const v4i *__restrict__ wimg, uint32_t wimg_bytes,
     const float *__restrict__ K, const float *__restrict__ A, const float *__restrict__ alpha,
     float *__restrict__ out, int32_t *__restrict__ dot_out, ConvGeom g, MfmaPlan pl, FuseArgs fz)
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
     // Weight prefetch depth.  Five steps pay off on long K loops; the 64-filter tiles serve layers
     // with short K loops and many workgroups, and the fused epilogue needs registers of its own:
     // there three steps keep more waves resident.
-    constexpr int DW = (FUSE || FT <= 64) ? 3 : 5;
+    constexpr int DW = (FUSE || FT <= 64 || FMT == 2) ? 3 : 5;      // (bfloat16 parts: a step is three times as long)
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     int *rowinfo = reinterpret_cast<int *>(lds + pl.region_bytes);
     int *xoff_tab = rowinfo + pl.max_rows;     // [(nsteps + KLOOP_TABLE_PAD) * BPS]
@@ -142,10 +142,10 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         const uint32_t pix = m - img * howo;
         const uint32_t oy = g.div_wo.div(pix), ox = pix - oy * g.wo;
         pbase[j] = ((int)(img * g.hp + oy * g.sh) - r_lo) * pl.row_pitch + (int)ox * g.sw * pl.ps +
-                   (E::BPS == 1 ? 16 * half : 0);
+                   (E::HALF_SPLIT ? 16 * half : 0);
     }
     // weight records of this wave's filter blocks: record index = fblk * recs_per_fblock + step record
-    const int recs_per_fb = E::BPS == 1 ? g.taps * g.cw : (g.taps * g.cw + 1) / 2;
+    const int recs_per_fb = (g.taps * g.cw + E::BPS - 1) / E::BPS;
     // Weight records are fetched with buffer loads: scalar record offset + the lane's 16-byte slot,
     // so the K loop spends no vector registers or ALU work on weight addresses.
     const __amdgpu_buffer_rsrc_t wrsrc =
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= 8 ? 2 : 1)) void conv_mfm
         const int fb = min(f0 / 32 + wf * FW + i, g.fblocks - 1);
         wrec0[i] = __builtin_amdgcn_readfirstlane(fb * recs_per_fb);
     }
-    const int tab_lane = (E::BPS == 2 ? half : 0);
+    const int tab_lane = (E::HALF_SPLIT ? 0 : half);
 
     acc_t acc[FW][PW];
 #pragma unroll
@@ -426,26 +426,30 @@ static const int LDS_LIMIT = 160 * 1024;
 
 // fuse_rows: rows of PT words for the fused epilogue's |z| sums and sign words (0 without it)
 // par_bytes: alpha (fused epilogue: also scale and shift) of the workgroup's filters
-static size_t plan_lds_bytes(const MfmaPlan &pl, int bps, int wp, int PT, int fuse_rows, int par_bytes)
+// channel words per K-step and bytes of the widening table of an operand format (Enc<fmt>::BPS, LUT_BYTES)
+static constexpr int fmt_bps(int fmt) { return fmt == 1 ? 2 : fmt == 2 ? 3 : 1; }
+static constexpr int fmt_lut_bytes(int fmt) { return fmt == 0 ? 512 * 8 : fmt == 1 ? 512 * 4 : 0; }
+static size_t plan_lds_bytes(const MfmaPlan &pl, int fmt, int wp, int PT, int fuse_rows, int par_bytes)
 {
     const size_t rest = (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 +
-                        (size_t)((pl.nsteps + KLOOP_TABLE_PAD) * bps) * 4 + (size_t)pl.max_rows * wp * 4 +
+                        (size_t)((pl.nsteps + KLOOP_TABLE_PAD) * fmt_bps(fmt)) * 4 + (size_t)pl.max_rows * wp * 4 +
                         (size_t)PT * 4 * (1 + fuse_rows) + 16;
-    return (rest + 15) / 16 * 16 + (bps == 1 ? 512 * 8 : 512 * 4) + par_bytes;       // + the widening table
+    return (rest + 15) / 16 * 16 + fmt_lut_bytes(fmt) + par_bytes;       // + the widening table
 }
-static int plan_lut_offset(const MfmaPlan &pl, int bps, int wp, int PT, int fuse_rows, int par_bytes)
+static int plan_lut_offset(const MfmaPlan &pl, int fmt, int wp, int PT, int fuse_rows, int par_bytes)
 {
-    return (int)(plan_lds_bytes(pl, bps, wp, PT, fuse_rows, par_bytes) - (bps == 1 ? 512 * 8 : 512 * 4) - par_bytes);
+    return (int)(plan_lds_bytes(pl, fmt, wp, PT, fuse_rows, par_bytes) - fmt_lut_bytes(fmt) - par_bytes);
 }
 
 static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fuse_rows, int par_bytes, MfmaPlan *pl)
 {
-    const int bps = fmt == 1 ? 2 : 1, bpb = fmt == 1 ? 16 : 32;
+    const int bps = fmt_bps(fmt), bpb = fmt == 1 ? 16 : 32;
     const int rows = worst_region_rows(g, PT, PT);
     for (int ccw = g.cw; ccw >= 1; --ccw) {
         if (g.cw % ccw) continue;
-        // 4-bit operands take two channel words per step: chunks must keep word pairs together
-        if (bps == 2 && ccw != g.cw && (ccw % 2)) continue;
+        // 4-bit operands take two channel words per step, bfloat16 parts three: chunks must keep the
+        // words of a step together
+        if (ccw != g.cw && (ccw % bps)) continue;
         const long long row_bytes = (long long)ccw * bpb;
         const long long ps = row_bytes + ((row_bytes / 16) % 2 == 0 ? 16 : 0);
         // LDS row pitch: at least wp pixels, padded so that stepping from the last output pixel of a row
@@ -464,8 +468,8 @@ static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fu
         pl->tap_jump = (ccw == g.cw) ? 0 : (g.cw - ccw) / bps;
         if (region >= (1ll << 30)) continue;
         pl->region_bytes = (int)region;
-        const long long total = (long long)plan_lds_bytes(*pl, bps, g.wp, PT, fuse_rows, par_bytes);
-        const bool last = (ccw == 1) || (bps == 2 && ccw == 2);
+        const long long total = (long long)plan_lds_bytes(*pl, fmt, g.wp, PT, fuse_rows, par_bytes);
+        const bool last = ccw <= bps;
         // one chunk with all channel words keeps the weight records consecutive (the K loop without
         // bookkeeping) and saves the refills: worth up to half the CU's LDS (two workgroups per CU)
         const long long budget = ccw == g.cw ? (lds_budget > 80 * 1024 ? lds_budget : 80 * 1024) : lds_budget;
@@ -512,8 +516,8 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     MfmaPlan pl;
     constexpr int FROWS = FUSE ? WF + FT / 32 : 0, PARB = (FUSE ? 3 : 1) * FT * 4;
     if (!make_plan(g, PT, FMT, g_lds_budget, FROWS, PARB, &pl)) return XNOR_ERR_UNSUPPORTED;
-    const size_t lds = plan_lds_bytes(pl, FMT == 1 ? 2 : 1, g.wp, PT, FROWS, PARB);
-    pl.lut_offset = plan_lut_offset(pl, FMT == 1 ? 2 : 1, g.wp, PT, FROWS, PARB);
+    const size_t lds = plan_lds_bytes(pl, FMT, g.wp, PT, FROWS, PARB);
+    pl.lut_offset = plan_lut_offset(pl, FMT, g.wp, PT, FROWS, PARB);
     // two builds of every tiling: weight records consecutive (one chunk holds all channel words) or not
     // (a chunk of a 1x1 filter is a run of consecutive records too)
     const bool linear = pl.tap_jump == 0 || g.taps == 1;
@@ -537,7 +541,9 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
         grid = dim3((unsigned)wg, 1u);
     }
     if (grid.y > 65535u) return XNOR_ERR_UNSUPPORTED;
-    const size_t img_bytes = FMT == 1 ? wimg_f4_bytes(g.k_out, g.c, g.taps) : wimg_i8_bytes(g.k_out, g.c, g.taps);
+    const size_t img_bytes = FMT == 1 ? wimg_f4_bytes(g.k_out, g.c, g.taps)
+                             : FMT == 2 ? wimg_bf16_bytes(g.k_out, g.cw / 3, g.taps)
+                                        : wimg_i8_bytes(g.k_out, g.c, g.taps);
     if (img_bytes > 0x7fffffffull) return XNOR_ERR_UNSUPPORTED;
     kern<<<grid, block, lds, stream>>>(xbits, reinterpret_cast<const v4i *>(wimg), (uint32_t)img_bytes, K, A, alpha,
                                        out, dot_out, g, pl, FUSE ? *fz : FuseArgs{});
@@ -572,15 +578,21 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
         if (FMT == 2) {
             // real activations (bfloat16 parts): the K loop is 24 times longer per channel, so the
             // tiles with the larger register blocks win wherever the filter count fills them
+            // (measured): up to 64 filters 64 x 256, up to 128 filters 128 x 128; beyond that the tile
+            // among 256 x 96 (when one tile holds every filter), 128 x 128 and 128 x 64 that leaves the
+            // fewest CUs idle in the last round, the larger one on a tie
             if (g.k_out <= 64) tile = 2;
             else if (g.k_out <= 128) tile = 1;
-            else if (g.k_out <= 256) tile = waste(wgs(256, 96)) <= waste(wgs(256, 128)) ? 4 : 5;
-            else tile = (g.k_out + 255) / 256 * 256 * 10 <= g.k_out * 11 ? 5 : 1;
+            else {
+                const double w4 = g.k_out <= 256 ? waste(wgs(256, 96)) : 1e30;
+                const double w1 = waste(wgs(128, 128)), w13 = waste(wgs(128, 64));
+                tile = w4 <= 1.03 * w1 && w4 <= 1.03 * w13 ? 4 : w1 <= 1.03 * w13 ? 1 : 13;
+            }
         } else if (g.k_out <= 128) tile = !fz ? 11 : g.k_out <= 64 ? 2 : 1;
         else if (g.k_out <= 256) tile = waste(wgs(256, 96)) <= waste(wgs(256, 128)) ? 4 : 5;
         else tile = 1;
         const long long w0 = tile == 11 ? wgs(64, 128) : tile == 2 ? wgs(64, 256) : tile == 4 ? wgs(256, 96)
-                             : tile == 5 ? wgs(256, 128) : wgs(128, 128);
+                             : tile == 5 ? wgs(256, 128) : tile == 13 ? wgs(128, 64) : wgs(128, 128);
         if (w0 < (FMT == 2 ? 128 : 200)) {
             if (wgs(64, 128) >= cus) tile = 11;
             else if (wgs(128, 64) >= cus) tile = 13;

@@ -51,7 +51,9 @@ inline int worst_region_rows(const ConvGeom &g, int run, int step)
 template <int FMT> struct Enc;
 
 template <> struct Enc<0> {                    // int8
-    static constexpr int BPS = 1;              // channel words per K-step
+    static constexpr int BPS = 1;              // channel words per K-step (= per weight record)
+    static constexpr int NX = 1;               // matrix instructions per K-step and result block
+    static constexpr bool HALF_SPLIT = true;   // a lane's half-wave picks 16 of a word's 32 bytes
     static constexpr int BPB = 32;             // LDS bytes per pixel per channel word
     typedef v16i acc_t;
     static __device__ __forceinline__ acc_t mfma(v4i w, v4i x, acc_t c) {
@@ -120,6 +122,8 @@ template <> struct Enc<0> {                    // int8
 
 template <> struct Enc<1> {                    // 4-bit float E2M1
     static constexpr int BPS = 2;
+    static constexpr int NX = 1;
+    static constexpr bool HALF_SPLIT = false;  // a lane's half-wave picks one word of the step's pair
     static constexpr int BPB = 16;
     typedef v16f acc_t;
     static __device__ __forceinline__ acc_t mfma(v4i w, v4i x, acc_t c) {
@@ -191,11 +195,14 @@ constexpr int ring_lcm(int a, int b)
 // Binary-Weight-Network operands (sec. 3.1: real inputs, +-1 weights).  The real activations arrive
 // pre-split into three bfloat16 parts (hi + mid + lo == the float exactly), 16 channels x one part
 // = one 32-byte "word" per pixel; the weights are +-1.0 (0 past the last channel or filter) in
-// bfloat16, the same record for each of the three parts.  Products are exact, accumulation is
-// float: the result is the float sum of exact terms.  Layout-wise this is the int8 encoding (32
-// bytes per pixel and word, the half-wave picks its 16 bytes), with nothing to widen.
+// bfloat16, one record per 16-channel group that multiplies all three parts (the record is fetched
+// once per K-step and feeds three matrix instructions per result block).  Products are exact,
+// accumulation is float: the result is the float sum of exact terms.  Layout-wise a word is like the
+// int8 encoding's (32 bytes per pixel and word, the half-wave picks its 16 bytes), with nothing to widen.
 template <> struct Enc<2> {
-    static constexpr int BPS = 1;
+    static constexpr int BPS = 3;       // a K-step = one 16-channel group = the three parts' words, one weight record
+    static constexpr int NX = 3;        // matrix instructions per step and result block (one per part)
+    static constexpr bool HALF_SPLIT = true;
     static constexpr int BPB = 32;
     typedef v16f acc_t;
     typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
@@ -298,18 +305,24 @@ __device__ __forceinline__ void mfma_kloop(typename E::acc_t (&acc)[FW][PW], con
     auto load_w = [&](v4i (&dst)[FW]) { ws.load(dst); };
     const int *tab = xoff_tab + tab_lane;
     auto load_t = [&](int s) -> int { return tab[s * E::BPS]; };
-    auto load_x = [&](v4i (&dst)[PW], int toff) {
-#pragma unroll
-        for (int j = 0; j < PW; ++j) dst[j] = *reinterpret_cast<const v4i *>(lds_x + pbase[j] + toff);
-    };
-    auto fma_all = [&](const v4i (&w)[FW], const v4i (&x)[PW]) {
+    constexpr int NX = E::NX;                  // words of a step that share its weight record
+    auto load_x = [&](v4i (&dst)[PW][NX], int toff) {
 #pragma unroll
         for (int j = 0; j < PW; ++j)
 #pragma unroll
-            for (int i = 0; i < FW; ++i) acc[i][j] = E::mfma(w[i], x[j], acc[i][j]);
+            for (int q = 0; q < NX; ++q)
+                dst[j][q] = *reinterpret_cast<const v4i *>(lds_x + pbase[j] + toff + q * E::BPB);
+    };
+    auto fma_all = [&](const v4i (&w)[FW], const v4i (&x)[PW][NX]) {
+#pragma unroll
+        for (int q = 0; q < NX; ++q)
+#pragma unroll
+            for (int j = 0; j < PW; ++j)
+#pragma unroll
+                for (int i = 0; i < FW; ++i) acc[i][j] = E::mfma(w[i], x[j][q], acc[i][j]);
     };
 
-    v4i w[RW][FW], x[RX][PW];
+    v4i w[RW][FW], x[RX][PW][NX];
     int tq[2];
 #pragma unroll
     for (int u = 0; u < DW; ++u) load_w(w[u]);
@@ -321,9 +334,9 @@ __device__ __forceinline__ void mfma_kloop(typename E::acc_t (&acc)[FW][PW], con
         tq[(u + 1) & 1] = load_t(s + u + DX + 1);
         load_x(x[(u + DX) % RX], tq[u & 1]);            // step s+u+DX, offset read one sub-step ago
         fma_all(w[u % RW], x[u % RX]);
-        // one LDS read behind each of the first PW+1 MFMAs, then the FW weight loads
+        // one LDS read behind each of the first PW*NX+1 MFMAs, then the FW weight loads
 #pragma unroll
-        for (int q = 0; q < PW + 1; ++q) {
+        for (int q = 0; q < PW * NX + 1; ++q) {
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         }
@@ -332,7 +345,7 @@ __device__ __forceinline__ void mfma_kloop(typename E::acc_t (&acc)[FW][PW], con
             __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
             __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, FW * PW - PW - 1 - FW, 0);
+        __builtin_amdgcn_sched_group_barrier(0x008, FW * PW * NX - PW * NX - 1 - FW, 0);
         __builtin_amdgcn_sched_barrier(0);
     };
     int s = 0;

@@ -134,5 +134,11 @@ __host__ __device__ inline size_t wimg_f4_bytes(int k_out, int c, int taps)
 {
     return ((size_t)((k_out + 31) / 32) * (((size_t)taps * (size_t)((c + 31) / 32) + 1) / 2) + 1) * 1024u;
 }
+// Binary-Weight-Network image: one +-1 bfloat16 record per filter block, tap and 16-channel group
+// (groups = ceil(c/16)), plus the trailing all-zero record
+__host__ __device__ inline size_t wimg_bf16_bytes(int k_out, int groups, int taps)
+{
+    return ((size_t)((k_out + 31) / 32) * (size_t)taps * (size_t)groups + 1) * 1024u;
+}
 
 }  // namespace xnor
