@@ -17,39 +17,60 @@ __device__ __forceinline__ float bf16_value(uint32_t h) { return __builtin_bit_c
 
 // x [n][c][hw] float  ->  parts [n][hw][Cg][3][16] bfloat16, Cg = ceil(c/16): for every pixel and group
 // of 16 channels three 32-byte words (hi, mid, lo) with hi + mid + lo == x exactly; channels >= c are 0.
-// One workgroup = 64 pixels x one channel group; lanes along pixels (coalesced reads), each lane
-// writes its 96 contiguous bytes.
-__global__ __launch_bounds__(64) void bwn_split_kernel(const float *__restrict__ x, uint32_t *__restrict__ parts,
-                                                       int c, int hw, int cg)
+// One workgroup = 64 pixels x 4 channel groups, one group per wave; lanes along pixels (every channel
+// row is read as coalesced 256-byte segments, 16 loads in flight per lane).  A lane's 96 bytes go to LDS
+// (row stride 4*96 + 16 bytes: 16-byte writes of neighbouring lanes fall on different banks), from where
+// the workgroup writes each pixel's 4*96 bytes as one contiguous run, 16 bytes per lane.
+constexpr int SPLIT_G = 4, SPLIT_ROW = SPLIT_G * 96 + 16;
+__global__ __launch_bounds__(256) void bwn_split_kernel(const float *__restrict__ x, uint8_t *__restrict__ parts,
+                                                        int c, int hw, int cg)
 {
-    const int p = blockIdx.x * 64 + threadIdx.x;
-    const int grp = blockIdx.y, img = blockIdx.z;
-    if (p >= hw) return;
-    const float *xi = x + ((size_t)img * c + (size_t)grp * 16) * hw + p;
-    uint32_t hi[16], mid[16], lo[16];
+    __shared__ __attribute__((aligned(16))) uint8_t stage[64 * SPLIT_ROW];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int p0 = blockIdx.x * 64, g0 = blockIdx.y * SPLIT_G, img = blockIdx.z;
+    const int grp = g0 + wave;
+    const int pc = min(p0 + lane, hw - 1);
+    if (grp < cg) {
+        const float *xi = x + ((size_t)img * c + (size_t)grp * 16) * hw + pc;
+        float v[16];
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        const bool ok = grp * 16 + j < c;
-        const float v = ok ? xi[(size_t)j * hw] : 0.0f;
-        hi[j] = bf16_rne(v);
-        const float r1 = v - bf16_value(hi[j]);          // exact
-        mid[j] = bf16_rne(r1);
-        const float r2 = r1 - bf16_value(mid[j]);        // exact, at most 8 significant bits left
-        lo[j] = bf16_rne(r2);
+        for (int j = 0; j < 16; ++j) v[j] = xi[(size_t)min(j, c - 1 - grp * 16) * hw];     // clamped, masked below
+        uint32_t hi[16], mid[16], lo[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float t = grp * 16 + j < c ? v[j] : 0.0f;
+            hi[j] = bf16_rne(t);
+            const float r1 = t - bf16_value(hi[j]);          // exact
+            mid[j] = bf16_rne(r1);
+            const float r2 = r1 - bf16_value(mid[j]);        // exact, at most 8 significant bits left
+            lo[j] = bf16_rne(r2);
+        }
+        uint4 *dst = reinterpret_cast<uint4 *>(stage + lane * SPLIT_ROW + wave * 96);
+        auto pack4 = [](const uint32_t *h) { return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)); };
+        dst[0] = pack4(hi);  dst[1] = pack4(hi + 8);
+        dst[2] = pack4(mid); dst[3] = pack4(mid + 8);
+        dst[4] = pack4(lo);  dst[5] = pack4(lo + 8);
     }
-    uint4 *dst = reinterpret_cast<uint4 *>(parts + (((size_t)img * hw + p) * cg + grp) * 24);   // 24 dwords = 96 bytes
-    auto pack4 = [](const uint32_t *h) { return make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16)); };
-    dst[0] = pack4(hi);  dst[1] = pack4(hi + 8);
-    dst[2] = pack4(mid); dst[3] = pack4(mid + 8);
-    dst[4] = pack4(lo);  dst[5] = pack4(lo + 8);
+    __syncthreads();
+    const int ng = min(SPLIT_G, cg - g0);            // groups of this workgroup
+    const int upp = ng * 6;                          // 16-byte units per pixel
+    const int npx = min(64, hw - p0);
+    uint8_t *out = parts + (((size_t)img * hw + p0) * cg + g0) * 96;
+    for (int i = tid; i < npx * upp; i += 256) {
+        const int px = i / upp, u = i - px * upp;
+        *reinterpret_cast<uint4 *>(out + (size_t)px * cg * 96 + u * 16) =
+            *reinterpret_cast<const uint4 *>(stage + px * SPLIT_ROW + u * 16);
+    }
 }
 
 xnor_status launch_bwn_split(const float *x, void *parts, int n, int c, int hw, hipStream_t stream)
 {
     const int cg = (c + 15) / 16;
-    if (cg > 65535 || n > 65535) return XNOR_ERR_UNSUPPORTED;
-    dim3 grid((unsigned)((hw + 63) / 64), (unsigned)cg, (unsigned)n);
-    bwn_split_kernel<<<grid, dim3(64), 0, stream>>>(x, static_cast<uint32_t *>(parts), c, hw, cg);
+    const int gblocks = (cg + SPLIT_G - 1) / SPLIT_G;
+    if (gblocks > 65535 || n > 65535) return XNOR_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)((hw + 63) / 64), (unsigned)gblocks, (unsigned)n);
+    bwn_split_kernel<<<grid, dim3(256), 0, stream>>>(x, static_cast<uint8_t *>(parts), c, hw, cg);
     return hip_status(hipGetLastError());
 }
 
