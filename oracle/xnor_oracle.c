@@ -262,3 +262,59 @@ void xo_bingrad(const float *g, const float *K, const float *alpha, const int8_t
             gin[(size_t)job * h * w + i] = (float)((double)gmax[b] * (double)dst[i]);
     }
 }
+
+/* k-bit quantisation (sec. 3.2, paragraph "k-bit Quantization"): q_k(x) = 2*([(2^k - 1)(x+1)/2]/(2^k - 1) - 1/2)
+ * for x in [-1, 1], in place of sign().  With L = 2^k - 1 the level index is u = [L*(x+1)/2] in 0..L and
+ * q_k = (2u - L)/L: the odd integer a = 2u - L in [-L, L] over L.  Readings: inputs outside [-1, 1] are
+ * clamped (NaN -> -1); [.] rounds halves up (u = floor(v + 1/2)), so that q_1 = sign with sign(0) = +1;
+ * the level index is decided in float arithmetic in this order of operations, each rounded to float:
+ * v = ((x + 1) * 0.5) * L + 0.5, u = floor(v), clamped to 0..L.  k in 1..8. */
+void xo_qk_levels(const float *x, int32_t *a, size_t count, int k)
+{
+    const int L = (1 << k) - 1;
+    for (size_t i = 0; i < count; ++i) {
+        float t = x[i];
+        t = t >= -1.0f ? t : -1.0f;                 /* NaN -> -1 */
+        t = t <= 1.0f ? t : 1.0f;
+        const float h = (t + 1.0f) * 0.5f;
+        const float v = h * (float)L + 0.5f;
+        int u = (int)floorf(v);
+        u = u < 0 ? 0 : (u > L ? L : u);
+        a[i] = 2 * u - L;
+    }
+}
+
+/* Convolution of k-bit quantised inputs with k-bit quantised weights: the plain correlation of
+ * q_ka(x) and q_kw(w), zero padding, evaluated exactly: num = sum a_x * a_w over the in-bounds window
+ * (odd-integer numerators, 64-bit accumulation), out = num / (La * Lw).
+ *   ax [n][c][h][w], aw [k_out][c][kh][kw] int32 numerators; num [n][k_out][ho][wo] int64. */
+void xo_kbit_dot(const int32_t *ax, const int32_t *aw, int64_t *num,
+                 int n, int c, int h, int w, int k_out, int kh, int kw,
+                 int stride_h, int stride_w, int pad_h, int pad_w)
+{
+    const int ho = (h + 2 * pad_h - kh) / stride_h + 1;
+    const int wo = (w + 2 * pad_w - kw) / stride_w + 1;
+    const long jobs = (long)n * k_out;
+#pragma omp parallel for schedule(static)
+    for (long job = 0; job < jobs; ++job) {
+        const int b = (int)(job / k_out), k = (int)(job % k_out);
+        for (int oy = 0; oy < ho; ++oy)
+            for (int ox = 0; ox < wo; ++ox) {
+                int64_t s = 0;
+                for (int ch = 0; ch < c; ++ch)
+                    for (int dy = 0; dy < kh; ++dy) {
+                        const int iy = oy * stride_h - pad_h + dy;
+                        if (iy < 0 || iy >= h)
+                            continue;
+                        for (int dx = 0; dx < kw; ++dx) {
+                            const int ix = ox * stride_w - pad_w + dx;
+                            if (ix < 0 || ix >= w)
+                                continue;
+                            s += (int64_t)ax[(((size_t)b * c + ch) * h + iy) * w + ix] *
+                                 (int64_t)aw[(((size_t)k * c + ch) * kh + dy) * kw + dx];
+                        }
+                    }
+                num[((size_t)job * ho + oy) * wo + ox] = s;
+            }
+    }
+}

@@ -199,6 +199,32 @@ def binary_grad_input(g_out, W, K=None, alpha_=None, stride=(1, 1), pad=(0, 0), 
     return {"sg": sg, "gmax": gmax, "dot": dot, "gin": gin}
 
 
+def qk_levels(x, k):
+    """Numerators a = 2u - L (odd integers in [-L, L], L = 2^k - 1) of q_k(x) = a / L (sec. 3.2, "k-bit
+    Quantization"); inputs clamped to [-1, 1], halves rounded up, level decided in float32."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    a = np.empty(x.shape, dtype=np.int32)
+    _load().xo_qk_levels(_p(x, ctypes.c_float), _p(a, ctypes.c_int32), ctypes.c_size_t(x.size), int(k))
+    return a
+
+
+def kbit_conv2d(x, W, ka, kw_bits, stride=(1, 1), pad=(0, 0)):
+    """Correlation of q_ka(x) with q_kw(W) (both in [-1, 1]; sec. 3.2, "k-bit Quantization"), zero padding.
+    Returns dict(num int64 = sum of numerator products, out float32 = num / (La * Lw))."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    W = np.ascontiguousarray(W, dtype=np.float32)
+    n, c, h, w = x.shape
+    k, c2, kh, kw = W.shape
+    assert c == c2
+    ho, wo = out_hw(h, w, kh, kw, stride, pad)
+    ax, aw = qk_levels(x, ka), qk_levels(W, kw_bits)
+    num = np.empty((n, k, ho, wo), dtype=np.int64)
+    _load().xo_kbit_dot(_p(ax, ctypes.c_int32), _p(aw, ctypes.c_int32), _p(num, ctypes.c_int64),
+                        n, c, h, w, k, kh, kw, stride[0], stride[1], pad[0], pad[1])
+    La, Lw = (1 << ka) - 1, (1 << kw_bits) - 1
+    return {"num": num, "out": (num.astype(np.float64) / (La * Lw)).astype(np.float32)}
+
+
 def binary_linear(x, W):
     """Fully connected layer as the convolution whose filter covers the whole input
     (footnote of sec. 1): x [batch][in_f], W [out_f][in_f].  Returns dict(dot, K, alpha, out)

@@ -415,3 +415,54 @@ def test_binary_gradient_scaling_uses_alpha_and_K_in_float():
     r = xo.binary_grad_input(g, W)
     ref = np.einsum("nkyx,kc->ncyx", np.where(g >= 0, 1, -1), np.where(W[:, :, 0, 0] >= 0, 1, -1))
     assert np.array_equal(r["dot"], ref)
+
+
+# ----------------------------------------- k-bit quantisation (sec. 3.2, "k-bit Quantization")
+def test_qk_matches_the_formula_in_exact_rational_arithmetic():
+    # q_k(x) = 2 * (round((2^k - 1)(x + 1)/2) / (2^k - 1) - 1/2), evaluated with Fractions on inputs that are
+    # exact binary fractions away from rounding ties (so float rounding of the level decision cannot matter)
+    for k in range(1, 9):
+        L = (1 << k) - 1
+        xs = [Fraction(j, 64) for j in range(-64, 65)]
+        xs = [x for x in xs if ((L * (x + 1) / 2) % 1) != Fraction(1, 2)]
+        a = xo.qk_levels(np.array([float(x) for x in xs], np.float32), k)
+        for x, ai in zip(xs, a):
+            v = L * (x + 1) / 2
+            u = (v + Fraction(1, 2)).__floor__()          # round to nearest (no ties among these inputs)
+            q = 2 * (Fraction(u, L) - Fraction(1, 2))
+            assert Fraction(int(ai), L) == q, (k, x)
+
+
+def test_q1_is_sign_and_levels_are_uniform_and_clamped():
+    rng = np.random.default_rng(61)
+    x = rng.uniform(-1, 1, 1000).astype(np.float32)
+    x[:4] = [0.0, -0.0, 1.0, -1.0]
+    assert np.array_equal(xo.qk_levels(x, 1), xo.sign(x).astype(np.int32))       # k = 1: the sign function, sign(0) = +1
+    for k in (2, 3, 8):
+        L = (1 << k) - 1
+        a = xo.qk_levels(x, k)
+        assert a.min() >= -L and a.max() <= L and (a % 2 != 0).all()                # 2^k levels (2u - L)/L, u = 0..L
+        assert np.abs(a / L - x).max() <= 1.0 / L + 1e-6                            # nearest level: error <= half a step
+    assert xo.qk_levels(np.array([5.0, -7.0, np.inf, -np.inf, np.nan], np.float32), 3).tolist() == [7, -7, 7, -7, -7]
+    # ties round up: k = 2, x = -2/3 + 1/3 = -1/3 is a level; x = 0 lies halfway between levels -1/3 and +1/3
+    assert xo.qk_levels(np.array([0.0], np.float32), 2).tolist() == [1]
+    # monotone
+    xs = np.linspace(-1.2, 1.2, 4001).astype(np.float32)
+    assert (np.diff(xo.qk_levels(xs, 4)) >= 0).all()
+
+
+def test_kbit_conv_is_the_float_convolution_of_the_quantised_tensors():
+    # library float64 convolution of the dequantised values (exact rationals with small denominators)
+    rng = np.random.default_rng(62)
+    for (n, c, h, w, k, kh, kw, stride, pad, ka, kb) in [(2, 5, 7, 6, 4, 3, 3, (1, 1), (1, 1), 2, 1), (1, 3, 9, 9, 6, 2, 3, (2, 1), (0, 1), 3, 2),
+                                                          (2, 17, 5, 5, 3, 5, 5, (1, 1), (2, 2), 1, 1), (1, 4, 6, 6, 2, 3, 3, (1, 1), (0, 0), 4, 4)]:
+        x = rng.uniform(-1, 1, (n, c, h, w)).astype(np.float32)
+        W = rng.uniform(-1, 1, (k, c, kh, kw)).astype(np.float32)
+        r = xo.kbit_conv2d(x, W, ka, kb, stride, pad)
+        La, Lw = (1 << ka) - 1, (1 << kb) - 1
+        qx = xo.qk_levels(x, ka).astype(np.float64) / La
+        qw = xo.qk_levels(W, kb).astype(np.float64) / Lw
+        ref = torch.nn.functional.conv2d(torch.from_numpy(qx), torch.from_numpy(qw), None, stride, pad).numpy()
+        np.testing.assert_allclose(r["num"] / (La * Lw), ref, rtol=0, atol=1e-9)
+        if ka == 1 and kb == 1:          # one bit each: the binary dot map of the forward path
+            assert np.array_equal(r["num"], xo.dot_map(xo.sign(x), xo.sign(W), stride, pad))
