@@ -14,34 +14,52 @@ namespace xnor {
 // b = t*cw + wd and taken two per record (record fb*ceil(taps*cw/2) + b/2); lane l owns the 32
 // channels of block 2*(b/2) + (l >> 5) as 32 nibbles, channel j in nibble j (low nibble first);
 // a block past the end is all zero.
-// TRANSPOSED: the filters of the data-gradient convolution of the backward pass (sec. 3.2, "Binary
+// MODE 1 (transposed): the filters of the data-gradient convolution of the backward pass (sec. 3.2, "Binary
 // Gradient"), read straight out of the forward tensor W [c][k_out][taps] (c = forward filters, k_out =
 // forward channels in this kernel's naming): filter k, channel ch, tap t is W[ch][k][taps - 1 - t], the
-// forward filter rotated by 180 degrees with the two channel axes exchanged.  alpha is then written as
-// 1 (the scaling factor of that convolution is the gradient's, applied per image).
-template <bool TRANSPOSED>
+// forward filter rotated by 180 degrees with the two channel axes exchanged.
+// MODE 2 (bit planes of k-bit quantised weights, sec. 3.2 "k-bit Quantization"): the kernel's k_out counts
+// planes x filters; "filter" p * (k_out / aux) + f is plane p of filter f: +1 where bit p of the level index
+// of q_aux(w) is set, -1 where it is clear (q_k = sum_p 2^p s_p / (2^k - 1) with s_p = +-1).
+// In both modes alpha is written as 1 (the scaling of those convolutions is applied elsewhere).
+__device__ __forceinline__ int qk_level_index(float x, int L)
+{
+    // level index u = floor(((x + 1) * 0.5) * L + 0.5) of q_k, x clamped to [-1, 1] (NaN -> -1); every
+    // operation rounded to float in this order (the build disables contraction)
+    float t = x >= -1.0f ? x : -1.0f;
+    t = t <= 1.0f ? t : 1.0f;
+    const float v = ((t + 1.0f) * 0.5f) * (float)L + 0.5f;
+    return min(max((int)__builtin_floorf(v), 0), L);
+}
+
+template <int MODE>
 __global__ __launch_bounds__(256) void pack_weights_kernel(
     const float *__restrict__ w, uint32_t *__restrict__ wbits, float *__restrict__ alpha,
-    int8_t *__restrict__ wmfma, int k_out, int c, int taps, int cw)
+    int8_t *__restrict__ wmfma, int k_out, int c, int taps, int cw, int aux)
 {
+    constexpr bool TRANSPOSED = MODE == 1;
     __shared__ float red[256];
     const int k = blockIdx.x;              // grid covers the filters padded to a multiple of 32
     const int tid = threadIdx.x;
     const bool real = k < k_out;
     const size_t n = (size_t)c * taps;
     const int kk = real ? k : 0;
+    const int nfilt = MODE == 2 ? k_out / aux : k_out;      // filters of the tensor w
+    const int plane = MODE == 2 ? kk / nfilt : 0;
+    const int kf = MODE == 2 ? kk - plane * nfilt : kk;
     // element (channel ch, tap t) of this filter
     struct Filter {
         const float *base;
         size_t ch_stride;
-        int taps;
+        int taps, plane, L;
         __device__ float operator()(int ch, int t) const
         {
+            if (MODE == 2) return ((qk_level_index(base[(size_t)ch * ch_stride + t], L) >> plane) & 1) ? 1.0f : -1.0f;
             return TRANSPOSED ? base[(size_t)ch * ch_stride + (taps - 1 - t)] : base[(size_t)ch * ch_stride + t];
         }
     };
-    const Filter wk{TRANSPOSED ? w + (size_t)kk * taps : w + (size_t)kk * n,
-                    TRANSPOSED ? (size_t)k_out * taps : (size_t)taps, taps};
+    const Filter wk{TRANSPOSED ? w + (size_t)kf * taps : w + (size_t)kf * n,
+                    TRANSPOSED ? (size_t)k_out * taps : (size_t)taps, taps, plane, (1 << aux) - 1};
 
     if (real) {
         for (int item = tid; item < taps * cw; item += 256) {
@@ -52,7 +70,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
                 word |= (wk(wd * 32 + j, t) >= 0.0f ? 1u : 0u) << j;
             wbits[((size_t)k * taps + t) * cw + wd] = word;
         }
-        if (TRANSPOSED) {
+        if (MODE != 0) {
             if (tid == 0) alpha[k] = 1.0f;
         } else {
             float s = 0.0f;
@@ -123,15 +141,17 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
 }
 
 xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
-                                int k_out, int c, int taps, hipStream_t stream, bool transposed)
+                                int k_out, int c, int taps, hipStream_t stream, int mode, int aux)
 {
     const int cw = (c + 31) / 32;
     const int kpad = (k_out + 31) / 32 * 32;
     dim3 grid((unsigned)(wmfma ? kpad : k_out)), block(256);
-    if (transposed)
-        pack_weights_kernel<true><<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw);
+    if (mode == 1)
+        pack_weights_kernel<1><<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, 1);
+    else if (mode == 2)
+        pack_weights_kernel<2><<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, aux);
     else
-        pack_weights_kernel<false><<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw);
+        pack_weights_kernel<0><<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, 1);
     return hip_status(hipGetLastError());
 }
 
