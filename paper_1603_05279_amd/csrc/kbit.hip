@@ -92,33 +92,44 @@ xnor_status launch_kbit_pack_input(const float *x, uint32_t *planes, int k, int 
 
 // dots [ka*n][kw*k_out][howo]: the +-1 dot products of the plane pairs as floats (exact integers below 2^24).
 // num = sum_{p,q} 2^(p+q) dots[p*n + img][q*k_out + f], out = num / (La * Lw) with one rounding.
+constexpr int COMBINE_PLANES = 4;
 __global__ __launch_bounds__(256) void kbit_combine_kernel(const float *__restrict__ dots, float *__restrict__ out,
                                                            int32_t *__restrict__ num_out, int n, int k_out, int howo,
-                                                           int ka, int kw, double scale)
+                                                           int ka, int kw, double scale, int fgroups)
 {
-    const size_t total = (size_t)n * k_out * howo;
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (size_t)gridDim.x * 256) {
-        const size_t plane = i / howo;                 // img * k_out + f
-        const int pix = (int)(i - plane * howo);
-        const int img = (int)(plane / k_out), f = (int)(plane - (size_t)img * k_out);
-        long long num = 0;
+    // one workgroup per image and group of 4 filters: no index divisions per element, and the loads of
+    // the 4 output planes are independent (small planes would otherwise leave a wave one load deep)
+    const int img = blockIdx.x / fgroups, f0 = (blockIdx.x - img * fgroups) * COMBINE_PLANES;
+    const size_t kk = (size_t)kw * k_out;
+    for (int pix = threadIdx.x; pix < howo; pix += 256) {
+        int num[COMBINE_PLANES];                        // fits: the host checked La * Lw * c * taps < 2^31
+#pragma unroll
+        for (int u = 0; u < COMBINE_PLANES; ++u) num[u] = 0;
         for (int p = 0; p < ka; ++p)
             for (int q = 0; q < kw; ++q) {
-                const float d = dots[(((size_t)p * n + img) * ((size_t)kw * k_out) + (size_t)q * k_out + f) * howo + pix];
-                num += (long long)d << (p + q);
+                const float *src = dots + (((size_t)p * n + img) * kk + (size_t)q * k_out) * howo + pix;
+#pragma unroll
+                for (int u = 0; u < COMBINE_PLANES; ++u)
+                    num[u] += (int)src[(size_t)min(f0 + u, k_out - 1) * howo] << (p + q);
             }
-        if (num_out) num_out[i] = (int32_t)num;
-        out[i] = (float)((double)num / scale);
+#pragma unroll
+        for (int u = 0; u < COMBINE_PLANES; ++u)
+            if (f0 + u < k_out) {
+                const size_t o = ((size_t)img * k_out + f0 + u) * howo + pix;
+                if (num_out) num_out[o] = num[u];
+                out[o] = (float)((double)num[u] / scale);
+            }
     }
 }
 
 xnor_status launch_kbit_combine(const float *dots, float *out, int32_t *num_out, int n, int k_out, int howo,
                                 int ka, int kw, hipStream_t stream)
 {
-    const size_t total = (size_t)n * k_out * howo;
-    const unsigned blocks = (unsigned)std::min<size_t>((total + 255) / 256, 65536);
+    const int fgroups = (k_out + COMBINE_PLANES - 1) / COMBINE_PLANES;
+    if ((long long)n * fgroups > 0x7fffffffLL) return XNOR_ERR_UNSUPPORTED;
     const double scale = (double)((1 << ka) - 1) * (double)((1 << kw) - 1);
-    kbit_combine_kernel<<<dim3(blocks), dim3(256), 0, stream>>>(dots, out, num_out, n, k_out, howo, ka, kw, scale);
+    kbit_combine_kernel<<<dim3((unsigned)(n * fgroups)), dim3(256), 0, stream>>>(dots, out, num_out, n, k_out, howo, ka,
+                                                                                kw, scale, fgroups);
     return hip_status(hipGetLastError());
 }
 
