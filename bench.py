@@ -145,8 +145,9 @@ def report(args):
                   f"{orc:.1f} |", flush=True)
     # the widened rows: Binary-Weight-Network convolution and binary-gradient backward convolution
     print("\n| config / layer | BWN split us | BWN conv us | bf16 TFLOP/s (3 parts) | % bf16 peak | fp32-equiv TFLOP/s | "
-          "grad binarize us | grad conv us | Tbinop/s (grad conv) |")
-    print("|---|---|---|---|---|---|---|---|---|")
+          "grad binarize us | grad conv us | Tbinop/s (grad conv) | 2-bit pack us | 2x2-bit conv us | "
+          "pool 3x3/2 + BinActiv of the output us |")
+    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
     for cfg in ("alexnet_conv2", "alexnet_conv345", "resnet18"):
         for i, layer in enumerate(wl.config_layers(cfg)):
             n, c, h, w_, k, kh, kw, st, pd = (layer.n, layer.c, layer.h, layer.w, layer.k_out, layer.kh, layer.kw,
@@ -182,6 +183,27 @@ def report(args):
                 row += f" {gb_us:.1f} | {gc_us:.1f} | {layer.bit_macs / gc_us / 1e6:.0f} |"
             else:
                 row += " - | - | - |"
+            # 2-bit inputs x 2-bit weights (inputs scaled into [-1, 1])
+            cw32 = xnor.words_per_pixel(c)
+            xs = torch.tanh(x)
+            xpl = torch.empty((2, n, h, w_, cw32), dtype=torch.int32, device="cuda")
+            wb2 = torch.empty((2 * k, kh * kw, cw32), dtype=torch.int32, device="cuda")
+            wm2, ones2 = u8(xnor.wmfma_bytes(2 * k, c, kh, kw)), torch.empty((2 * k,), device="cuda")
+            ws2 = u8(xnor.kbit_workspace_bytes(desc, 2, 2))
+            xnor.xnor_kbit_pack_weights(torch.tanh(wt), wb2, ones2, wm2, 2, k, c, kh, kw)
+            kp_us = median_us(lambda: xnor.xnor_kbit_pack_input(xs, xpl, 2, n, c, h, w_))
+            kc_us = median_us(lambda: xnor.xnor_kbit_conv2d(xpl, wb2, wm2, ones2, ws2, out, None, desc, 2, 2))
+            row += f" {kp_us:.1f} | {kc_us:.1f} |"
+            del xpl, wb2, wm2, ws2
+            # max-pool 3x3 stride 2 of this layer's output fused into the next block's BinActiv
+            if ho >= 3 and wo >= 3:
+                hp_, wp_ = (ho - 3) // 2 + 1, (wo - 3) // 2 + 1
+                pb = torch.empty((n, hp_, wp_, xnor.words_per_pixel(k)), dtype=torch.int32, device="cuda")
+                pa = torch.empty((n, hp_, wp_), device="cuda")
+                pl_us = median_us(lambda: xnor.xnor_pool_binactiv(out, None, None, pb, pa, n, k, ho, wo, (3, 3), (2, 2)))
+                row += f" {pl_us:.1f} |"
+            else:
+                row += " - |"
             print(row, flush=True)
     print(f"\nOracle: {xo.threads()} host threads.  % attainable = floor time at min(fp4 peak, arithmetic "
           "intensity x 8 TB/s) / measured time.  The paper's own figures: 58x measured, 62.27x modelled speed-up of "
