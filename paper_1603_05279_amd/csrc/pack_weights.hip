@@ -35,7 +35,7 @@ __device__ __forceinline__ int qk_level_index(float x, int L)
 template <int MODE>
 __global__ __launch_bounds__(256) void pack_weights_kernel(
     const float *__restrict__ w, uint32_t *__restrict__ wbits, float *__restrict__ alpha,
-    int8_t *__restrict__ wmfma, int k_out, int c, int taps, int cw, int aux)
+    int8_t *__restrict__ wmfma, int k_out, int c, int taps, int cw, int aux, int stage)
 {
     constexpr bool TRANSPOSED = MODE == 1;
     __shared__ float red[256];
@@ -47,8 +47,8 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
     const int nfilt = MODE == 2 ? k_out / aux : k_out;      // filters of the tensor w
     const int plane = MODE == 2 ? kk / nfilt : 0;
     const int kf = MODE == 2 ? kk - plane * nfilt : kk;
-    // element (channel ch, tap t) of this filter
-    struct Filter {
+    // element (channel ch, tap t) of this filter, read from the tensor in the mode's order
+    struct Source {
         const float *base;
         size_t ch_stride;
         int taps, plane, L;
@@ -58,8 +58,26 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
             return TRANSPOSED ? base[(size_t)ch * ch_stride + (taps - 1 - t)] : base[(size_t)ch * ch_stride + t];
         }
     };
-    const Filter wk{TRANSPOSED ? w + (size_t)kf * taps : w + (size_t)kf * n,
-                    TRANSPOSED ? (size_t)k_out * taps : (size_t)taps, taps, plane, (1 << aux) - 1};
+    const Source src{TRANSPOSED ? w + (size_t)kf * taps : w + (size_t)kf * n,
+                     TRANSPOSED ? (size_t)k_out * taps : (size_t)taps, taps, plane, (1 << aux) - 1};
+    // The four images below each walk the whole filter with a 32-channel stride per thread.  When the
+    // filter fits the staging buffer it is first copied to LDS in [channel][tap] order (one coalesced pass
+    // in mode 0) and every later access reads LDS; larger filters are read from memory each time.
+    extern __shared__ float staged[];
+    if (stage) {
+        for (int i = tid; i < (int)n; i += 256) {
+            const int ch = i / taps;
+            staged[i] = src(ch, i - ch * taps);
+        }
+        __syncthreads();
+    }
+    struct Filter {
+        const Source &src;
+        const float *lds;
+        int taps;
+        __device__ float operator()(int ch, int t) const { return lds ? lds[ch * taps + t] : src(ch, t); }
+    };
+    const Filter wk{src, stage ? staged : nullptr, taps};
 
     if (real) {
         for (int item = tid; item < taps * cw; item += 256) {
@@ -74,7 +92,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
             if (tid == 0) alpha[k] = 1.0f;
         } else {
             float s = 0.0f;
-            for (size_t i = tid; i < n; i += 256) s += __builtin_fabsf(wk.base[i]);
+            for (size_t i = tid; i < n; i += 256) s += __builtin_fabsf(stage ? staged[i] : src.base[i]);
             red[tid] = s;
             __syncthreads();
             for (int step = 128; step > 0; step >>= 1) {
@@ -146,12 +164,15 @@ xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, v
     const int cw = (c + 31) / 32;
     const int kpad = (k_out + 31) / 32 * 32;
     dim3 grid((unsigned)(wmfma ? kpad : k_out)), block(256);
+    const size_t fbytes = (size_t)c * taps * sizeof(float);
+    const int stage = fbytes <= 60 * 1024 ? 1 : 0;
+    const size_t lds = stage ? fbytes : 0;
     if (mode == 1)
-        pack_weights_kernel<1><<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, 1);
+        pack_weights_kernel<1><<<grid, block, lds, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, 1, stage);
     else if (mode == 2)
-        pack_weights_kernel<2><<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, aux);
+        pack_weights_kernel<2><<<grid, block, lds, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, aux, stage);
     else
-        pack_weights_kernel<0><<<grid, block, 0, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, 1);
+        pack_weights_kernel<0><<<grid, block, lds, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, 1, stage);
     return hip_status(hipGetLastError());
 }
 
