@@ -33,7 +33,11 @@
  * per-window beta = |X|_1/n against K, exhaustive +-1 dot vs bitcount identity,
  * all-ones input closed form, constant-magnitude special case against a library
  * float convolution, sign flip antisymmetry, parity/bound invariants, the FC =
- * whole-input-filter equivalence.  Every function below is pinned by at least one.
+ * whole-input-filter equivalence; for the later functions: xo_bwn against a library
+ * float convolution with weights alpha*sign(W); xo_bingrad against autograd of a
+ * library convolution and the adjoint identity with xo_dot; xo_qk_levels against the
+ * formula in rational arithmetic and q_1 = sign; xo_kbit_dot against a library
+ * convolution of the dequantised tensors.  Every function below is pinned by at least one.
  *
  * Build: gcc -O3 -fopenmp -ffp-contract=off -shared -fPIC
  */
