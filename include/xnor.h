@@ -188,6 +188,21 @@ int xnor_conv2d_binactiv(const uint32_t *xbits, const uint32_t *wbits, const voi
                          const xnor_conv_desc *d, int algo, void *hip_stream);
 
 /*
+ * Binary convolution with the block's pooling layer applied in the epilogue (block order BinConv -> Pool,
+ * with the optional ReLU after BinConv; sec. 3.2):
+ *   out_pool[n][k][py][px] = max over the pool_h x pool_w window at (py*pstride_h, px*pstride_w) of
+ *                            y = float(dot) * K * alpha   (y = max(y, 0) first when relu != 0),
+ * h_pool = floor((h_out - pool_h)/pstride_h) + 1, w_pool likewise (no pooling padding; the window must fit the
+ * convolution output).  The unpooled tensor is never written.  The maximum skips NaN and is never NaN.
+ * Arguments as xnor_conv2d (K or A, alpha, wmfma required: matrix-core path with 4-bit operands only);
+ * out_pool float32 [n][k_out][h_pool][w_pool].  XNOR_ERR_UNSUPPORTED when the convolution rows under one
+ * pooled row (pool_h rows of w_out pixels) exceed the largest pixel tile (192 pixels), or c*kh*kw >= 2^24.
+ */
+int xnor_conv2d_pool(const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
+                     const float *alpha, float *out_pool, const xnor_conv_desc *d,
+                     int pool_h, int pool_w, int pstride_h, int pstride_w, int relu, void *hip_stream);
+
+/*
  * Binary-Weight-Network convolution (sec. 3.1, "Binary-Weight-Networks"): real-valued input, weights
  * estimated by alpha * sign(W):
  *     out[n][k][oy][ox] = alpha_k * sum over in-bounds taps and channels of  I * sign(W)

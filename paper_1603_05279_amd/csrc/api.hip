@@ -190,6 +190,22 @@ int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
     }
 }
 
+int xnor_conv2d_pool(const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
+                     const float *alpha, float *out_pool, const xnor_conv_desc *d,
+                     int pool_h, int pool_w, int pstride_h, int pstride_w, int relu, void *hip_stream)
+{
+    if (!xbits || !wmfma || (!K && !A) || !alpha || !out_pool) return XNOR_ERR_NULL;
+    ConvGeom g;
+    if (xnor_status s = make_geom(d, &g)) return s;
+    if (pool_h <= 0 || pool_w <= 0 || pstride_h <= 0 || pstride_w <= 0 || pool_h > g.ho || pool_w > g.wo)
+        return XNOR_ERR_SHAPE;
+    if (!aligned16(xbits) || !aligned16(wmfma) || !aligned16(K) || !aligned16(A) || !aligned16(alpha) ||
+        !aligned16(out_pool))
+        return XNOR_ERR_ALIGN;
+    return launch_conv_mfma_pool(xbits, wmfma, K, A, alpha, out_pool, g, pool_h, pool_w, pstride_h, pstride_w,
+                                 relu ? 1 : 0, (hipStream_t)hip_stream);
+}
+
 size_t xnor_conv2d_binactiv_workspace_bytes(const xnor_conv_desc *d)
 {
     ConvGeom g;

@@ -17,6 +17,7 @@
 // and pixels the N operand, so each lane of the result holds one pixel column: stores along a
 // filter plane are contiguous across lanes.
 #include "mfma_common.h"
+#include <algorithm>
 
 namespace xnor {
 
@@ -33,7 +34,7 @@ __device__ long long *g_timeline = nullptr;
 #endif
 
 // Accumulator tiles of up to 8 result blocks leave room for two waves per SIMD (256 registers each).
-template <int FMT, int FW, int PW, int WF, int WP, bool FUSE, bool LINEAR>
+template <int FMT, int FW, int PW, int WF, int WP, bool FUSE, bool LINEAR, bool POOL = false>
 __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 1)) void conv_mfma_kernel(
     const uint32_t *__restrict__ xbits, const v4i *__restrict__ wimg, uint32_t wimg_bytes,
     const float *__restrict__ K, const float *__restrict__ A, const float *__restrict__ alpha,
@@ -85,14 +86,29 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     const int wave = tid >> 6, lane = tid & 63;
     const int l32 = lane & 31, half = lane >> 5;
     const int wf = wave % WF, wp = wave / WF;
-    const uint32_t m0 = ptile * (uint32_t)PT;
     const int f0 = (int)ftile * FT;
     const uint32_t howo = (uint32_t)(g.ho * g.wo);
+    // the tile's run of flattened output pixels [m0, m_end): PT consecutive ones, or (pooled epilogue) the
+    // convolution rows under a group of pooled rows of one image
+    uint32_t m0, m_end;
+    uint32_t pool_img = 0;
+    int pool_py0 = 0, pool_rows = 0;               // first pooled row and pooled rows of this tile
+    if constexpr (POOL) {
+        pool_img = pl.pool.div_groups.div(ptile);
+        const int gi = (int)(ptile - pool_img * (uint32_t)pl.pool.groups);
+        pool_py0 = gi * pl.pool.pr;
+        pool_rows = min(pl.pool.pr, pl.pool.hpo - pool_py0);
+        m0 = pool_img * howo + (uint32_t)(pool_py0 * pl.pool.sh * g.wo);
+        m_end = m0 + (uint32_t)(((pool_rows - 1) * pl.pool.sh + pl.pool.ph) * g.wo);
+    } else {
+        m0 = ptile * (uint32_t)PT;
+        m_end = min(m0 + (uint32_t)PT, (uint32_t)g.m_total);
+    }
     const int ccw = pl.cc_words;
     const int nsteps = pl.nsteps;
 
     // padded input rows this tile touches: R = image*hp + padded row
-    const uint32_t m_last = min(m0 + (uint32_t)PT, (uint32_t)g.m_total) - 1u;
+    const uint32_t m_last = m_end - 1u;
     const uint32_t img_a = g.div_howo.div(m0), img_b = g.div_howo.div(m_last);
     const uint32_t oy_a = g.div_wo.div(m0 - img_a * howo), oy_b = g.div_wo.div(m_last - img_b * howo);
     const int r_lo = (int)(img_a * g.hp + oy_a * g.sh);
@@ -137,7 +153,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     int pbase[PW];
 #pragma unroll
     for (int j = 0; j < PW; ++j) {
-        const uint32_t m = min(m0 + (uint32_t)((wp * PW + j) * 32 + l32), (uint32_t)g.m_total - 1u);
+        const uint32_t m = min(m0 + (uint32_t)((wp * PW + j) * 32 + l32), m_end - 1u);
         const uint32_t img = g.div_howo.div(m);
         const uint32_t pix = m - img * howo;
         const uint32_t oy = g.div_wo.div(pix), ox = pix - oy * g.wo;
@@ -231,7 +247,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         if (FMT != 2 && wbase == 0 && !K) for (int kt = tid; kt < PT; kt += NT) {
             // K of output pixel m0 + tid: the kh x kw taps of A in row-major order over the staged
             // rows (halo entries add +0.0f, the same bits as skipping them), divided by kh*kw
-            const uint32_t m = min(m0 + (uint32_t)kt, (uint32_t)g.m_total - 1u);
+            const uint32_t m = min(m0 + (uint32_t)kt, m_end - 1u);
             const uint32_t img = g.div_howo.div(m);
             const uint32_t pix = m - img * howo;
             const uint32_t oy = g.div_wo.div(pix), ox = pix - oy * g.wo;
@@ -271,8 +287,8 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     for (int j = 0; j < PW; ++j) {
         const int pl_idx = (wp * PW + j) * 32 + l32;
         const uint32_t m = m0 + (uint32_t)pl_idx;
-        plive[j] = m < (uint32_t)g.m_total;
-        const uint32_t mc = plive[j] ? m : (uint32_t)g.m_total - 1u;
+        plive[j] = m < m_end;
+        const uint32_t mc = plive[j] ? m : m_end - 1u;
         pimg[j] = g.div_howo.div(mc);
         ppix[j] = mc - pimg[j] * howo;
         Km[j] = FMT == 2 ? 1.0f : (K ? K[mc] : ktile[pl_idx]);      // real activations carry no K
@@ -308,7 +324,61 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
             }
         }
     };
-    if constexpr (!FUSE) {
+    if constexpr (POOL) {
+    // Pooled epilogue: y = float(dot) * K * alpha (optionally max(y, 0)) of one filter block goes to a
+    // per-wave LDS tile [32 filters][PT + 1 pixels] laid over the (finished) activation region; lanes
+    // then take the maximum over the pooling windows and store the pooled rows of this tile.  LDS serves
+    // one wave's instructions in order, so a wave's own writes are visible to its reads without a
+    // workgroup barrier.  The maximum starts at -inf and skips NaN (maxNum).
+    constexpr int YP = PT + 1;
+    float al[FW][16];
+#pragma unroll
+    for (int i = 0; i < FW; ++i)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 a4 = *reinterpret_cast<const float4 *>(par_lds + (wf * FW + i) * 32 + 8 * q + 4 * half);
+            al[i][4 * q] = a4.x; al[i][4 * q + 1] = a4.y; al[i][4 * q + 2] = a4.z; al[i][4 * q + 3] = a4.w;
+        }
+    __syncthreads();                              // every wave is done reading activations (and alpha is in registers)
+    float *ystage = reinterpret_cast<float *>(lds) + (size_t)wave * 32 * YP;
+    const PoolPlan &pp = pl.pool;
+    const int npool = pool_rows * pp.wpo;         // pooled pixels of this tile
+    // lanes -> (filter offset, pooled pixel): as many filters side by side as fit into the wave
+    const int nf = npool >= 64 ? 1 : 64 / npool;
+    const int fo = npool >= 64 ? 0 : lane / npool;
+    const int pq = lane - fo * npool;
+    const int pstep = npool >= 64 ? 64 : npool;
+    const bool lane_on = fo < nf;
+    float *pooled = reinterpret_cast<float *>(out);
+    const size_t plane = (size_t)pp.hpo * pp.wpo;
+#pragma unroll
+    for (int i = 0; i < FW; ++i) {
+#pragma unroll
+        for (int j = 0; j < PW; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                float y = E::to_float(acc[i][j], v) * Km[j] * al[i][v];
+                if (pp.relu) y = y > 0.0f ? y : 0.0f;
+                ystage[(8 * (v >> 2) + 4 * half + (v & 3)) * YP + (wp * PW + j) * 32 + l32] = y;
+            }
+        __builtin_amdgcn_wave_barrier();
+        const int row0 = f0 + (wf * FW + i) * 32;
+        if (lane_on)
+            for (int f = fo; f < 32; f += nf) {
+                if (row0 + f >= g.k_out) break;
+                for (int q = pq; q < npool; q += pstep) {
+                    const uint32_t py = pp.div_wpo.div((uint32_t)q);
+                    const int px = q - (int)py * pp.wpo;
+                    const float *src = ystage + f * YP + (int)py * pp.sh * g.wo + px * pp.sw;
+                    float mx = -__builtin_inff();
+                    for (int dy = 0; dy < pp.ph; ++dy)
+                        for (int dx = 0; dx < pp.pw; ++dx) mx = __builtin_fmaxf(mx, src[dy * g.wo + dx]);
+                    pooled[((size_t)pool_img * g.k_out + row0 + f) * plane + (size_t)pool_py0 * pp.wpo + q] = mx;
+                }
+            }
+        __builtin_amdgcn_wave_barrier();
+    }
+    } else if constexpr (!FUSE) {
 #pragma unroll
     for (int i = 0; i < FW; ++i) {
         float al[16];
@@ -441,10 +511,11 @@ static int plan_lut_offset(const MfmaPlan &pl, int fmt, int wp, int PT, int fuse
     return (int)(plan_lds_bytes(pl, fmt, wp, PT, fuse_rows, par_bytes) - fmt_lut_bytes(fmt) - par_bytes);
 }
 
-static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fuse_rows, int par_bytes, MfmaPlan *pl)
+static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fuse_rows, int par_bytes, MfmaPlan *pl,
+                      int rows_override = 0)
 {
     const int bps = fmt_bps(fmt), bpb = fmt == 1 ? 16 : 32;
-    const int rows = worst_region_rows(g, PT, PT);
+    const int rows = rows_override ? rows_override : worst_region_rows(g, PT, PT);
     for (int ccw = g.cw; ccw >= 1; --ccw) {
         if (g.cw % ccw) continue;
         // 4-bit operands take two channel words per step, bfloat16 parts three: chunks must keep the
@@ -554,6 +625,83 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
         return hip_status(hipGetLastError());
     }
     return XNOR_OK;
+}
+
+// Pooled-epilogue launch of one tiling (4-bit operands): a pixel tile is a group of pooled rows of one image.
+template <int FW, int PW, int WF, int WP>
+static xnor_status launch_cfg_pool(const uint32_t *xbits, const void *wimg, const float *K, const float *A,
+                                   const float *alpha, float *out_pool, const ConvGeom &g, const PoolPlan &pool,
+                                   hipStream_t stream)
+{
+    constexpr int FT = 32 * FW * WF, PT = 32 * PW * WP, WAVES = WF * WP;
+    MfmaPlan pl;
+    const int conv_rows = (pool.pr - 1) * pool.sh + pool.ph;          // convolution rows under a tile
+    if (conv_rows * g.wo > PT) return XNOR_ERR_UNSUPPORTED;
+    if (!make_plan(g, PT, 1, g_lds_budget, 0, FT * 4, &pl, (conv_rows - 1) * g.sh + g.kh)) return XNOR_ERR_UNSUPPORTED;
+    size_t lds = plan_lds_bytes(pl, 1, g.wp, PT, 0, FT * 4);
+    pl.lut_offset = plan_lut_offset(pl, 1, g.wp, PT, 0, FT * 4);
+    lds = std::max(lds, (size_t)WAVES * 32 * (PT + 1) * sizeof(float));       // the epilogue's per-wave y tiles
+    if (lds > (size_t)LDS_LIMIT) return XNOR_ERR_UNSUPPORTED;
+    const bool linear = pl.tap_jump == 0 || g.taps == 1;
+    auto kern = linear ? conv_mfma_kernel<1, FW, PW, WF, WP, false, true, true>
+                       : conv_mfma_kernel<1, FW, PW, WF, WP, false, false, true>;
+    static bool attr_done[2] = {false, false};
+    if (!attr_done[linear]) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT) != hipSuccess)
+            return XNOR_ERR_HIP;
+        attr_done[linear] = true;
+    }
+    const long long ptiles = (long long)g.n * pool.groups;
+    if (ptiles > 0x7fffffffLL) return XNOR_ERR_UNSUPPORTED;
+    pl.ptiles = (int)ptiles;
+    pl.ftiles = (g.k_out + FT - 1) / FT;
+    pl.wmajor = 0;
+    pl.pool = pool;
+    if (pl.ftiles > 65535) return XNOR_ERR_UNSUPPORTED;
+    const size_t img_bytes = wimg_f4_bytes(g.k_out, g.c, g.taps);
+    if (img_bytes > 0x7fffffffull) return XNOR_ERR_UNSUPPORTED;
+    // the XCD-aware tile order works on whole windows of 64 pixel tiles; the grid is not padded beyond ptiles
+    kern<<<dim3((unsigned)pl.ptiles, (unsigned)pl.ftiles), dim3(64 * WAVES), lds, stream>>>(
+        xbits, reinterpret_cast<const v4i *>(wimg), (uint32_t)img_bytes, K, A, alpha, out_pool, nullptr, g, pl, FuseArgs{});
+    return hip_status(hipGetLastError());
+}
+
+xnor_status launch_conv_mfma_pool(const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
+                                  const float *alpha, float *out_pool, const ConvGeom &g, int ph, int pw, int sh,
+                                  int sw, int relu, hipStream_t stream)
+{
+    if ((long long)g.c * g.taps >= (1ll << 24)) return XNOR_ERR_UNSUPPORTED;       // exact float accumulation
+    PoolPlan pool;
+    pool.ph = ph; pool.pw = pw; pool.sh = sh; pool.sw = sw; pool.relu = relu;
+    pool.hpo = (g.ho - ph) / sh + 1;
+    pool.wpo = (g.wo - pw) / sw + 1;
+    pool.div_wpo = FastDiv::make((uint32_t)pool.wpo);
+    // Tile: 256 filters x 96, 160 or 192 pixels.  Each holds as many pooled rows as its pixels allow; the
+    // choice minimises (rounds of workgroups over the 256 CUs) x (pixels per tile), the smaller tile on a tie.
+    const int pts[3] = {96, 160, 192};
+    int best = -1, best_pr = 0;
+    long long best_cost = 0;
+    const int ftiles = (g.k_out + 255) / 256;
+    for (int t = 0; t < 3; ++t) {
+        const int rows_fit = pts[t] / g.wo;                     // convolution rows a tile can hold
+        if (rows_fit < ph) continue;
+        const int pr = std::min((rows_fit - ph) / sh + 1, pool.hpo);
+        const long long groups = (pool.hpo + pr - 1) / pr;
+        const long long wgs = (long long)g.n * groups * ftiles;
+        const long long cost = (wgs + 255) / 256 * pts[t];
+        if (best < 0 || cost < best_cost) { best = t; best_cost = cost; best_pr = pr; }
+    }
+    if (best < 0) return XNOR_ERR_UNSUPPORTED;                  // a pooling window's rows do not fit any tile
+    pool.pr = best_pr;
+    pool.groups = (pool.hpo + best_pr - 1) / best_pr;
+    pool.div_groups = FastDiv::make((uint32_t)pool.groups);
+    const uint8_t *img = static_cast<const uint8_t *>(wmfma) + wimg_i8_bytes(g.k_out, g.c, g.taps);
+    switch (best) {
+    case 0: return launch_cfg_pool<2, 3, 4, 1>(xbits, img, K, A, alpha, out_pool, g, pool, stream);
+    case 1: return launch_cfg_pool<2, 5, 4, 1>(xbits, img, K, A, alpha, out_pool, g, pool, stream);
+    default: return launch_cfg_pool<2, 6, 4, 1>(xbits, img, K, A, alpha, out_pool, g, pool, stream);
+    }
 }
 
 template <int FMT>

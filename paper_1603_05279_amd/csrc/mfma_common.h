@@ -10,6 +10,19 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef unsigned v4u __attribute__((ext_vector_type(4)));
 
+// Max-pooling applied in the convolution's epilogue (block order BinConv -> Pool, sec. 3.2).  A pixel tile is
+// then a group of `pr` pooled rows of one image: the (pr-1)*sh + ph convolution rows under them, all
+// columns, as one run of consecutive flattened output pixels (neighbouring groups overlap by ph - sh rows,
+// which are computed twice).
+struct PoolPlan {
+    int ph, pw, sh, sw;   // window, stride (no padding)
+    int hpo, wpo;         // pooled extent
+    int pr;               // pooled rows per tile
+    int groups;           // tiles per image = ceil(hpo / pr)
+    int relu;             // max(., 0) before pooling (the optional ReLU after BinConv)
+    FastDiv div_groups, div_wpo;
+};
+
 struct MfmaPlan {
     int cc_words;     // channel words widened per chunk (divides cw)
     int ps;           // bytes per pixel in LDS (an odd multiple of 16: conflict-free 16-byte reads)
@@ -23,6 +36,7 @@ struct MfmaPlan {
     int ftiles;       // filter tiles of the launch
     int wmajor;       // 1: 1-D grid that keeps the pixel tiles of a filter tile on one XCD
     FastDiv div_wp, div_hp, div_ccw, div_cw;
+    PoolPlan pool;    // used by the pooled-epilogue instantiations only
 };
 
 // Most padded input rows touched by any run of `run` consecutive (flattened) output pixels that

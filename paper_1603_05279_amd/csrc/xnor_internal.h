@@ -123,6 +123,11 @@ struct FuseArgs {
 xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
                              const float *alpha, float *out, int32_t *dot_out,
                              const ConvGeom &g, hipStream_t stream, const FuseArgs *fz = nullptr);
+// the same convolution (4-bit operands) with max-pooling (window ph x pw, stride sh x sw, no padding, optional
+// ReLU first) applied in the epilogue: out_pool [n][k_out][hpo][wpo], the unpooled tensor is never written
+xnor_status launch_conv_mfma_pool(const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
+                                  const float *alpha, float *out_pool, const ConvGeom &g, int ph, int pw, int sh,
+                                  int sw, int relu, hipStream_t stream);
 void set_mfma_tuning(int tile, int lds_budget);
 // Binary-Weight-Network preparation kernels (bwn.hip); the convolution itself is launch_conv_mfma with fmt 2
 xnor_status launch_bwn_split(const float *x, void *parts, int n, int c, int hw, hipStream_t stream);

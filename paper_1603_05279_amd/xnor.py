@@ -23,6 +23,7 @@ EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor
            "xnor_bwn_parts_bytes", "xnor_bwn_wimg_bytes", "xnor_bwn_split", "xnor_bwn_pack_weights",
            "xnor_bwn_conv2d",
            "xnor_bingrad_pack_weights", "xnor_bingrad_binarize", "xnor_bingrad_conv2d",
+           "xnor_conv2d_pool",
            "xnor_kbit_workspace_bytes", "xnor_kbit_pack_input", "xnor_kbit_pack_weights", "xnor_kbit_conv2d"]
 
 
@@ -93,6 +94,8 @@ def lib():
         L.xnor_bingrad_binarize.restype = ip
         L.xnor_bingrad_conv2d.argtypes = [vp] * 8 + [ctypes.POINTER(ConvDesc), ip, vp]
         L.xnor_bingrad_conv2d.restype = ip
+        L.xnor_conv2d_pool.argtypes = [vp] * 6 + [ctypes.POINTER(ConvDesc)] + [ip] * 5 + [vp]
+        L.xnor_conv2d_pool.restype = ip
         L.xnor_kbit_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc), ip, ip]
         L.xnor_kbit_workspace_bytes.restype = ctypes.c_size_t
         L.xnor_kbit_pack_input.argtypes = [vp, vp, ip, ip, ip, ip, ip, vp]
@@ -265,6 +268,13 @@ def xnor_conv2d(xbits, wbits, wmfma, K, A, alpha, out, dot_out, desc, algo=XNOR_
         _ptr(xbits, torch.int32), _ptr(wbits, torch.int32), _ptr(wmfma, torch.uint8),
         _ptr(K, torch.float32), _ptr(A, torch.float32), _ptr(alpha, torch.float32), _ptr(out, torch.float32),
         _ptr(dot_out, torch.int32), ctypes.byref(desc), int(algo), _stream(stream)))
+
+
+def xnor_conv2d_pool(xbits, wmfma, K, A, alpha, out_pool, desc, pool, pstride, relu=False, stream=None):
+    _check("xnor_conv2d_pool", lib().xnor_conv2d_pool(
+        _ptr(xbits, torch.int32), _ptr(wmfma, torch.uint8), _ptr(K, torch.float32), _ptr(A, torch.float32),
+        _ptr(alpha, torch.float32), _ptr(out_pool, torch.float32), ctypes.byref(desc), pool[0], pool[1], pstride[0],
+        pstride[1], int(bool(relu)), _stream(stream)))
 
 
 def xnor_linear(xbits, wbits, wmfma, Krow, alpha, out, dot_out, batch, in_features, out_features,
