@@ -18,6 +18,7 @@
 // filter plane are contiguous across lanes.
 #include "mfma_common.h"
 #include <algorithm>
+#include <type_traits>
 
 namespace xnor {
 
@@ -340,43 +341,85 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
             al[i][4 * q] = a4.x; al[i][4 * q + 1] = a4.y; al[i][4 * q + 2] = a4.z; al[i][4 * q + 3] = a4.w;
         }
     __syncthreads();                              // every wave is done reading activations (and alpha is in registers)
-    float *ystage = reinterpret_cast<float *>(lds) + (size_t)wave * 32 * YP;
+    // 16 filter rows at a time (register groups v = 0..7, then 8..15): [16][PT + 1] floats per wave
+    float *ystage = reinterpret_cast<float *>(lds) + (size_t)wave * 16 * YP;
     const PoolPlan &pp = pl.pool;
     const int npool = pool_rows * pp.wpo;         // pooled pixels of this tile
-    // lanes -> (filter offset, pooled pixel): as many filters side by side as fit into the wave
-    const int nf = npool >= 64 ? 1 : 64 / npool;
+    // lanes -> (filter offset, pooled pixel): as many filters side by side as fit into the wave; a lane
+    // keeps its pooled pixel and walks the filters in steps of nf, eight filters' window loads in flight
+    const int nf = npool >= 64 ? 1 : min(64 / npool, 16);
     const int fo = npool >= 64 ? 0 : lane / npool;
     const int pq = lane - fo * npool;
     const int pstep = npool >= 64 ? 64 : npool;
     const bool lane_on = fo < nf;
     float *pooled = reinterpret_cast<float *>(out);
     const size_t plane = (size_t)pp.hpo * pp.wpo;
+    // maxima of 8 filters (rows fb + u*nf + fo of the staged 16) over one pooled pixel's window
+    auto window_max = [&](auto PHc, auto PWc, const float *win, const int (&roff)[8], float (&mx)[8]) {
+        constexpr int CH = decltype(PHc)::value, CW = decltype(PWc)::value;       // 0: run-time window
+        if constexpr (CH > 0) {
+            float t[CH * CW][8];
+#pragma unroll
+            for (int dy = 0; dy < CH; ++dy)
+#pragma unroll
+                for (int dx = 0; dx < CW; ++dx)
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) t[dy * CW + dx][u] = win[roff[u] + dy * g.wo + dx];
+#pragma unroll
+            for (int w9 = 0; w9 < CH * CW; ++w9)
+#pragma unroll
+                for (int u = 0; u < 8; ++u) mx[u] = __builtin_fmaxf(mx[u], t[w9][u]);
+        } else {
+            for (int dy = 0; dy < pp.ph; ++dy)
+                for (int dx = 0; dx < pp.pw; ++dx) {
+                    float t[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) t[u] = win[roff[u] + dy * g.wo + dx];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) mx[u] = __builtin_fmaxf(mx[u], t[u]);
+                }
+        }
+    };
+    const int wkind = (pp.ph == 3 && pp.pw == 3) ? 3 : (pp.ph == 2 && pp.pw == 2) ? 2 : 0;
 #pragma unroll
     for (int i = 0; i < FW; ++i) {
 #pragma unroll
-        for (int j = 0; j < PW; ++j)
+        for (int hq = 0; hq < 2; ++hq) {          // filter rows 16*hq .. 16*hq + 15 of the block
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                float y = E::to_float(acc[i][j], v) * Km[j] * al[i][v];
-                if (pp.relu) y = y > 0.0f ? y : 0.0f;
-                ystage[(8 * (v >> 2) + 4 * half + (v & 3)) * YP + (wp * PW + j) * 32 + l32] = y;
-            }
-        __builtin_amdgcn_wave_barrier();
-        const int row0 = f0 + (wf * FW + i) * 32;
-        if (lane_on)
-            for (int f = fo; f < 32; f += nf) {
-                if (row0 + f >= g.k_out) break;
-                for (int q = pq; q < npool; q += pstep) {
-                    const uint32_t py = pp.div_wpo.div((uint32_t)q);
-                    const int px = q - (int)py * pp.wpo;
-                    const float *src = ystage + f * YP + (int)py * pp.sh * g.wo + px * pp.sw;
-                    float mx = -__builtin_inff();
-                    for (int dy = 0; dy < pp.ph; ++dy)
-                        for (int dx = 0; dx < pp.pw; ++dx) mx = __builtin_fmaxf(mx, src[dy * g.wo + dx]);
-                    pooled[((size_t)pool_img * g.k_out + row0 + f) * plane + (size_t)pool_py0 * pp.wpo + q] = mx;
+            for (int j = 0; j < PW; ++j)
+#pragma unroll
+                for (int v8 = 0; v8 < 8; ++v8) {
+                    const int v = 8 * hq + v8;
+                    float y = E::to_float(acc[i][j], v) * Km[j] * al[i][v];
+                    if (pp.relu) y = y > 0.0f ? y : 0.0f;
+                    ystage[(8 * (v8 >> 2) + 4 * half + (v8 & 3)) * YP + (wp * PW + j) * 32 + l32] = y;
+                }
+            __builtin_amdgcn_wave_barrier();
+            const int row0 = f0 + (wf * FW + i) * 32 + 16 * hq;
+            const int nrow = min(16, g.k_out - row0);       // staged filters that exist (wave-uniform, may be <= 0)
+            for (int q = pq; q < npool; q += pstep) {
+                const uint32_t py = pp.div_wpo.div((uint32_t)q);
+                const int px = q - (int)py * pp.wpo;
+                const float *win = ystage + (int)py * pp.sh * g.wo + px * pp.sw;
+                float *dst = pooled + ((size_t)pool_img * g.k_out + row0 + fo) * plane + (size_t)pool_py0 * pp.wpo + q;
+                for (int fb = 0; fb < nrow; fb += 8 * nf) {       // wave-uniform trip count
+                    int roff[8];
+                    float mx[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) {
+                        roff[u] = min(fb + u * nf + fo, 15) * YP;      // clamped: always inside the wave's tile
+                        mx[u] = -__builtin_inff();
+                    }
+                    if (wkind == 3) window_max(std::integral_constant<int, 3>{}, std::integral_constant<int, 3>{}, win, roff, mx);
+                    else if (wkind == 2) window_max(std::integral_constant<int, 2>{}, std::integral_constant<int, 2>{}, win, roff, mx);
+                    else window_max(std::integral_constant<int, 0>{}, std::integral_constant<int, 0>{}, win, roff, mx);
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (lane_on && fb + u * nf + fo < nrow) dst[(size_t)(fb + u * nf) * plane] = mx[u];
                 }
             }
-        __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_wave_barrier();
+        }
     }
     } else if constexpr (!FUSE) {
 #pragma unroll
@@ -640,7 +683,7 @@ static xnor_status launch_cfg_pool(const uint32_t *xbits, const void *wimg, cons
     if (!make_plan(g, PT, 1, g_lds_budget, 0, FT * 4, &pl, (conv_rows - 1) * g.sh + g.kh)) return XNOR_ERR_UNSUPPORTED;
     size_t lds = plan_lds_bytes(pl, 1, g.wp, PT, 0, FT * 4);
     pl.lut_offset = plan_lut_offset(pl, 1, g.wp, PT, 0, FT * 4);
-    lds = std::max(lds, (size_t)WAVES * 32 * (PT + 1) * sizeof(float));       // the epilogue's per-wave y tiles
+    lds = std::max(lds, (size_t)WAVES * 16 * (PT + 1) * sizeof(float));       // the epilogue's per-wave y tiles
     if (lds > (size_t)LDS_LIMIT) return XNOR_ERR_UNSUPPORTED;
     const bool linear = pl.tap_jump == 0 || g.taps == 1;
     auto kern = linear ? conv_mfma_kernel<1, FW, PW, WF, WP, false, true, true>
@@ -678,7 +721,8 @@ xnor_status launch_conv_mfma_pool(const uint32_t *xbits, const void *wmfma, cons
     pool.wpo = (g.wo - pw) / sw + 1;
     pool.div_wpo = FastDiv::make((uint32_t)pool.wpo);
     // Tile: 256 filters x 96, 160 or 192 pixels.  Each holds as many pooled rows as its pixels allow; the
-    // choice minimises (rounds of workgroups over the 256 CUs) x (pixels per tile), the smaller tile on a tie.
+    // choice minimises (rounds of workgroups over the CUs' workgroup slots) x (pixels per tile), the smaller
+    // tile on a tie.
     const int pts[3] = {96, 160, 192};
     int best = -1, best_pr = 0;
     long long best_cost = 0;
@@ -689,7 +733,8 @@ xnor_status launch_conv_mfma_pool(const uint32_t *xbits, const void *wmfma, cons
         const int pr = std::min((rows_fit - ph) / sh + 1, pool.hpo);
         const long long groups = (pool.hpo + pr - 1) / pr;
         const long long wgs = (long long)g.n * groups * ftiles;
-        const long long cost = (wgs + 255) / 256 * pts[t];
+        const long long slots = t == 0 ? 512 : 256;            // two workgroups of the 96-pixel tile share a CU
+        const long long cost = (wgs + slots - 1) / slots * pts[t];
         if (best < 0 || cost < best_cost) { best = t; best_cost = cost; best_pr = pr; }
     }
     if (best < 0) return XNOR_ERR_UNSUPPORTED;                  // a pooling window's rows do not fit any tile
