@@ -273,6 +273,11 @@ static xnor_status launch_binactiv_one(dim3 grid, size_t lds, hipStream_t stream
     return hip_status(hipGetLastError());
 }
 
+template <bool POOL, int PH, int PW, int NW>
+static xnor_status launch_binactiv_nw(const float *x, const float *bn_scale, const float *bn_shift,
+                                      uint32_t *xbits, float *A, int n, int c, int hw, const PoolGeom &pg,
+                                      hipStream_t stream);
+
 template <bool POOL, int PH = 0, int PW = 0>
 static xnor_status launch_binactiv_impl(const float *x, const float *bn_scale, const float *bn_shift,
                                         uint32_t *xbits, float *A, int n, int c, int hw, const PoolGeom &pg,
@@ -282,7 +287,21 @@ static xnor_status launch_binactiv_impl(const float *x, const float *bn_scale, c
     const int tiles = (hw + 63) / 64;
     const long long blocks = (long long)n * tiles;
     if (blocks > 0x7ffffff0LL) return XNOR_ERR_SHAPE;
-    constexpr int NW = POOL ? 16 : 4;
+    // 16 waves per workgroup for the pooled form and wherever 4-wave workgroups would leave the CUs with fewer
+    // than 8 waves each (small planes: a 7 x 7 image is one 64-pixel tile): more loads in flight per CU
+    if (!POOL && blocks * 4 < 256 * 8 && c >= 128)
+        return launch_binactiv_nw<POOL, PH, PW, 16>(x, bn_scale, bn_shift, xbits, A, n, c, hw, pg, stream);
+    return launch_binactiv_nw<POOL, PH, PW, POOL ? 16 : 4>(x, bn_scale, bn_shift, xbits, A, n, c, hw, pg, stream);
+}
+
+template <bool POOL, int PH, int PW, int NW>
+static xnor_status launch_binactiv_nw(const float *x, const float *bn_scale, const float *bn_shift,
+                                      uint32_t *xbits, float *A, int n, int c, int hw, const PoolGeom &pg,
+                                      hipStream_t stream)
+{
+    const int cw = (c + 31) / 32;
+    const int tiles = (hw + 63) / 64;
+    const long long blocks = (long long)n * tiles;
     size_t lds = NW * 64 * sizeof(float) + (size_t)64 * cw * 4;
     if (lds > 64 * 1024) return XNOR_ERR_UNSUPPORTED;       // more than ~500k channels per pixel
     lds += (size_t)NW * 2 * pg.stage * sizeof(float);
