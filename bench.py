@@ -205,7 +205,21 @@ def report(args):
             else:
                 row += " - |"
             print(row, flush=True)
-    print(f"\nOracle: {xo.threads()} host threads.  % attainable = floor time at min(fp4 peak, arithmetic "
+    # the oracle on one thread, tiny configuration (the other oracle figures use every host thread)
+    import ctypes
+    gomp = ctypes.CDLL("libgomp.so.1")
+    nthreads = xo.threads()
+    tiny = wl.config_layers("tiny")[0]
+    dt_in = wl.conv_inputs(tiny, wl.config_seed("tiny"))
+    gomp.omp_set_num_threads(1)
+    t0 = time.perf_counter()
+    for _ in range(20):
+        xo.binary_conv2d(dt_in["x"], dt_in["w"], (tiny.stride, tiny.stride), (tiny.pad, tiny.pad))
+    one = 20 * tiny.bit_macs / (time.perf_counter() - t0) / 1e9
+    gomp.omp_set_num_threads(nthreads)
+    print(f"\nOracle on one thread, tiny configuration: {one:.2f} Gbinop/s.  One binop = one +-1 multiply-accumulate; "
+          "counting XNOR and bitcount as two operations doubles every Tbinop/s figure above.")
+    print(f"Oracle: {xo.threads()} host threads.  % attainable = floor time at min(fp4 peak, arithmetic "
           "intensity x 8 TB/s) / measured time.  The paper's own figures: 58x measured, 62.27x modelled speed-up of "
           "binary over float convolution on its CPU, memory access excluded (sec. 4.1).")
 
