@@ -19,7 +19,7 @@ if ROOT not in sys.path:
 
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # command (scaled by a 256 MiB copy: reads x2.00, writes x1.00), see profiles/; None where not measured.
-MEASURED_TRAFFIC = {("alexnet_conv2", "mfma_f4"): 1826.9 * 1024 * 2.0 + 49189.6 * 1024}
+MEASURED_TRAFFIC = {("alexnet_conv2", "mfma_f4"): 1830.6 * 1024 * 2.0 + 49229.0 * 1024}
 
 PEAKS = {  # MI355X published dense peaks
     "mfma_f4": {"bound": "mfma", "peak": 10100.0, "unit": "TFLOP/s"},     # fp4 10.1 PFLOP/s, 2 flops per MAC
