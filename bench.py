@@ -248,7 +248,7 @@ def main():
         sys.exit("bench.py: --chain needs --workload alexnet_conv345 (the only workload whose layers feed each other)")
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over the batch with no "
-                 "exchange step; see DESIGN.md). Run with --gpus 1.")
+                 "exchange step, each GPU running these same kernels on its share of the images). Run with --gpus 1.")
 
     import torch
     from paper_1603_05279_amd import workloads as wl
