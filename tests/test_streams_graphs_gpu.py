@@ -85,3 +85,68 @@ def test_full_size_sampled_properties():
     torch.cuda.synchronize()
     assert np.array_equal(bufs.dot.cpu().numpy().astype(np.int64), -dot)
     assert torch.equal(bufs.out, -out_pos)
+
+
+def test_graph_replays_of_the_widened_entry_points():
+    """Binary-gradient (clears its per-image maxima with a kernel, merges them with atomics), k-bit, Binary-Weight-
+    Network and pooled-epilogue sequences captured in one graph: every replay reproduces the eager results bit for
+    bit, with stale buffer contents and eager launches between the replays."""
+    rng = np.random.default_rng(12)
+    n, c, h, w, k = 4, 48, 13, 13, 72
+    desc = xnor.make_desc(n, c, h, w, k, 3, 3, 1, 1)
+    dev = "cuda"
+    x = to_dev(rng.standard_normal((n, c, h, w)).astype(np.float32))
+    wt = to_dev((rng.standard_normal((k, c, 3, 3)) * 0.05).astype(np.float32))
+    g_out = to_dev(rng.standard_normal((n, k, h, w)).astype(np.float32))
+    pw = xnor.PackedWeights(wt)
+    bufs = xnor.ConvBuffers(desc)
+    xnor.xnor_binactiv(x, None, None, bufs.xbits, bufs.A, bufs.K, desc)
+    kw32, cw32 = xnor.words_per_pixel(k), xnor.words_per_pixel(c)
+    u8 = lambda nbytes: torch.empty((nbytes,), dtype=torch.uint8, device=dev)
+    f32 = lambda *s: torch.full(s, float("nan"), dtype=torch.float32, device=dev)
+    i32 = lambda *s: torch.zeros(s, dtype=torch.int32, device=dev)
+    # prepared once, outside the graph (per layer)
+    wtbits, wtmfma, ones = i32(c, 9, kw32), u8(xnor.wmfma_bytes(c, k, 3, 3)), f32(c)
+    xnor.xnor_bingrad_pack_weights(wt, wtbits, ones, wtmfma, k, c, 3, 3)
+    wimg, alpha_b = u8(xnor.bwn_wimg_bytes(k, c, 3, 3)), f32(k)
+    xnor.xnor_bwn_pack_weights(wt, alpha_b, wimg, k, c, 3, 3)
+    wb2, wm2, ones2 = i32(2 * k, 9, cw32), u8(xnor.wmfma_bytes(2 * k, c, 3, 3)), f32(2 * k)
+    xnor.xnor_kbit_pack_weights(torch.tanh(wt * 10), wb2, ones2, wm2, 2, k, c, 3, 3)
+    xs = torch.tanh(x)
+    out = {"gbits": i32(n, h, w, kw32), "gmax": f32(n), "plane": f32(n, h, w), "gin": f32(n, c, h, w),
+           "parts": u8(xnor.bwn_parts_bytes(n, c, h, w)), "bwn": f32(n, k, h, w),
+           "xpl": i32(2, n, h, w, cw32), "ws": u8(xnor.kbit_workspace_bytes(desc, 2, 2)), "kb": f32(n, k, h, w),
+           "pool": f32(n, k, 6, 6)}
+
+    def sequence():
+        xnor.xnor_bingrad_binarize(g_out, bufs.K, pw.alpha, out["gbits"], out["gmax"], desc)
+        xnor.xnor_bingrad_conv2d(out["gbits"], wtbits, wtmfma, out["gmax"], ones, out["plane"], out["gin"], None, desc)
+        xnor.xnor_bwn_split(x, out["parts"], n, c, h, w)
+        xnor.xnor_bwn_conv2d(out["parts"], wimg, alpha_b, out["bwn"], desc)
+        xnor.xnor_kbit_pack_input(xs, out["xpl"], 2, n, c, h, w)
+        xnor.xnor_kbit_conv2d(out["xpl"], wb2, wm2, ones2, out["ws"], out["kb"], None, desc, 2, 2)
+        xnor.xnor_conv2d_pool(bufs.xbits, pw.wmfma, bufs.K, None, pw.alpha, out["pool"], desc, (3, 3), (2, 2))
+
+    checked = ("gbits", "gmax", "gin", "bwn", "kb", "pool")
+    sequence()
+    torch.cuda.synchronize()
+    eager = {name: out[name].clone() for name in checked}
+    assert not any(torch.isnan(eager[name]).any() for name in ("gmax", "gin", "bwn", "kb", "pool"))
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(graph, stream=side):
+        sequence()
+    torch.cuda.synchronize()
+    for replay in range(4):
+        for name in ("gmax", "plane", "gin", "bwn", "kb", "pool"):
+            out[name].fill_(777.0)                    # stale contents, e.g. a maximum larger than any |gd|
+        out["gbits"].fill_(-1)
+        out["ws"].fill_(255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name in checked:
+            assert torch.equal(out[name], eager[name]), (name, replay)
+        sequence()                                    # eager work between replays
+        torch.cuda.synchronize()
