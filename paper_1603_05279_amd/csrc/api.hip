@@ -179,8 +179,10 @@ int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
         if (!wmfma) return XNOR_ERR_NULL;
         return launch_conv_mfma(algo == XNOR_ALGO_MFMA_F4 ? 1 : 0, xbits, wmfma, K, A, alpha, out, dot_out, g, st);
     case XNOR_ALGO_AUTO: {
-        if (wmfma) {
-            const xnor_status s = launch_conv_mfma(1, xbits, wmfma, K, A, alpha, out, dot_out, g, st);
+        if (wmfma) {        // 4-bit operands, then int8 (sums of 2^24 and more terms), then the vector ALU
+            xnor_status s = launch_conv_mfma(1, xbits, wmfma, K, A, alpha, out, dot_out, g, st);
+            if (s != XNOR_ERR_UNSUPPORTED) return s;
+            s = launch_conv_mfma(0, xbits, wmfma, K, A, alpha, out, dot_out, g, st);
             if (s != XNOR_ERR_UNSUPPORTED) return s;
         }
         return launch_conv_popcount(xbits, wbits, wmfma, K, A, alpha, out, dot_out, g, st);

@@ -113,3 +113,29 @@ def test_linear_matches_oracle(algo):
     assert np.array_equal(dot.cpu().numpy(), r["dot"])
     np.testing.assert_allclose(bufs.K.cpu().numpy().reshape(b), r["K"], rtol=RTOL, atol=ATOL)
     np.testing.assert_allclose(out.cpu().numpy(), r["out"], rtol=RTOL, atol=ATOL)
+
+
+def test_auto_stays_exact_beyond_the_float_accumulator():
+    """2^24 terms per dot product: the 4-bit path (float accumulator) is refused, the library's own choice must
+    fall back to an exact integer path and still match the oracle bit for bit."""
+    import torch
+    from paper_1603_05279_amd import xnor
+    c = 1 << 24
+    rng = np.random.default_rng(24)
+    x = rng.standard_normal((1, c, 1, 1)).astype(np.float32)
+    w = x.reshape(1, c, 1, 1).copy()
+    w[0, : c // 4] *= -1.0                                   # a quarter of the signs disagree: dot = c/2
+    desc = xnor.make_desc(1, c, 1, 1, 1, 1, 1)
+    xd, wd = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    pw = xnor.PackedWeights(wd)
+    bufs = xnor.ConvBuffers(desc, with_dot=True)
+    xnor.xnor_binactiv(xd, None, None, bufs.xbits, bufs.A, bufs.K, desc)
+    with pytest.raises(xnor.XnorError) as e:
+        xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, None, pw.alpha, bufs.out, bufs.dot, desc,
+                         xnor.XNOR_ALGO_MFMA_F4)
+    assert e.value.status == -3
+    xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, None, pw.alpha, bufs.out, bufs.dot, desc, xnor.XNOR_ALGO_AUTO)
+    torch.cuda.synchronize()
+    assert bufs.dot.item() == c // 2
+    ref = float(c // 2) * float(np.abs(x).astype(np.float64).mean()) ** 2
+    np.testing.assert_allclose(bufs.out.item(), ref, rtol=1e-5)
