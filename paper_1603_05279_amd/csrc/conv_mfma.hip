@@ -756,13 +756,14 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
 {
     int tile = g_tile_override;
     if (tile == 0 || tile == 10) {
-        // Measured rules (fp4, all benchmark layers).  Up to 128 filters: 64 x 128 (fused epilogue: 64 x 256
-        // or 128 x 128, so that one workgroup holds every filter).  129..256 filters: a tile that holds
-        // every filter (weights stream through L1 once per pixel tile, the fused epilogue needs no
+        // Measured rules (fp4, all benchmark layers).  Up to 64 filters: 64 x 256 when that still gives every
+        // CU two workgroups, else 64 x 128; up to 128 filters: 128 x 64, else 64 x 128 (fused epilogue:
+        // 64 x 256 or 128 x 128, so that one workgroup holds every filter).  129..256 filters: a tile that
+        // holds every filter (weights stream through L1 once per pixel tile, the fused epilogue needs no
         // partial sums), 256 x 96 or 256 x 128, whichever leaves fewer CUs idle in its last round of
-        // workgroups.  More filters: 128 x 128.  Problems with few output tiles (fully connected
-        // layers: few "pixels", long K) take the largest smaller tile that still gives every CU a
-        // workgroup.
+        // workgroups.  More filters: 256 x 128 when the filter count is a multiple of 256, else 128 x 128.
+        // Problems with few output tiles (fully connected layers: few "pixels", long K) take the largest
+        // smaller tile that still gives every CU a workgroup.
         auto wgs = [&](int ft, int pt) {
             return (long long)((g.m_total + pt - 1) / pt) * ((g.k_out + ft - 1) / ft);
         };
@@ -781,12 +782,13 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
                 const double w1 = waste(wgs(128, 128)), w13 = waste(wgs(128, 64));
                 tile = w4 <= 1.03 * w1 && w4 <= 1.03 * w13 ? 4 : w1 <= 1.03 * w13 ? 1 : 13;
             }
-        } else if (g.k_out <= 128) tile = !fz ? 11 : g.k_out <= 64 ? 2 : 1;
+        } else if (g.k_out <= 64) tile = (fz || wgs(64, 256) >= 2 * cus) ? 2 : 11;
+        else if (g.k_out <= 128) tile = fz ? 1 : wgs(128, 64) >= 2 * cus ? 13 : 11;
         else if (g.k_out <= 256) tile = waste(wgs(256, 96)) <= waste(wgs(256, 128)) ? 4 : 5;
-        else tile = 1;
+        else tile = (g.k_out % 256 == 0 && !fz) ? 5 : 1;
         const long long w0 = tile == 11 ? wgs(64, 128) : tile == 2 ? wgs(64, 256) : tile == 4 ? wgs(256, 96)
                              : tile == 5 ? wgs(256, 128) : tile == 13 ? wgs(128, 64) : wgs(128, 128);
-        if (w0 < (FMT == 2 ? 128 : 200)) {
+        if (w0 < (FMT == 2 ? 128 : 160)) {
             if (wgs(64, 128) >= cus) tile = 11;
             else if (wgs(128, 64) >= cus) tile = 13;
             else tile = 14;       // 128 x 32 (measured ahead of 64 x 64 at equal workgroup count)
