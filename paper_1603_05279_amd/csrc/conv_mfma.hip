@@ -785,7 +785,7 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
         } else if (g.k_out <= 64) tile = (fz || wgs(64, 256) >= 2 * cus) ? 2 : 11;
         else if (g.k_out <= 128) tile = fz ? 1 : wgs(128, 64) >= 2 * cus ? 13 : 11;
         else if (g.k_out <= 256) tile = waste(wgs(256, 96)) <= waste(wgs(256, 128)) ? 4 : 5;
-        else tile = (g.k_out % 256 == 0 && !fz) ? 5 : 1;
+        else tile = g.k_out % 256 == 0 ? 5 : fz ? 13 : 1;      // (fused epilogue: 128 x 64 ahead of 128 x 128)
         const long long w0 = tile == 11 ? wgs(64, 128) : tile == 2 ? wgs(64, 256) : tile == 4 ? wgs(256, 96)
                              : tile == 5 ? wgs(256, 128) : tile == 13 ? wgs(128, 64) : wgs(128, 128);
         if (w0 < (FMT == 2 ? 128 : 160)) {
