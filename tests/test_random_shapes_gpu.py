@@ -1,6 +1,8 @@
 """Seeded random problem shapes through every inner loop and the fused epilogue, element by element
 against the CPU oracle: ragged pixel and filter tails, channel counts around the word size, filters
 larger than the unpadded image, strides, asymmetric padding amounts."""
+import os
+
 import numpy as np
 import pytest
 
@@ -28,7 +30,8 @@ def random_shapes(seed, count):
     return shapes
 
 
-SHAPES = random_shapes(20240611, 40)
+# XNOR_TEST_SHAPES / XNOR_TEST_SEED widen the sweep for a soak run (defaults keep the suite short)
+SHAPES = random_shapes(int(os.environ.get("XNOR_TEST_SEED", 20240611)), int(os.environ.get("XNOR_TEST_SHAPES", 40)))
 
 
 @pytest.mark.parametrize("algo", ["popcount", "mfma_i8", "mfma_f4"])
