@@ -229,8 +229,8 @@ int xnor_bwn_conv2d(const void *parts, const void *wimg, const float *alpha, flo
 /*
  * Binary gradient (sec. 3.2, paragraph "Binary Gradient"): the backward convolution between the weight
  * filters and the incoming gradient, with that gradient binarised and scaled by its largest magnitude
- * (not by its mean).  d is always the FORWARD layer's descriptor (input n x c x h_in x w_in, k_out filters);
- * only stride 1 is built (XNOR_ERR_UNSUPPORTED otherwise).  All pointers are device pointers, 16-byte
+ * (not by its mean).  d is always the FORWARD layer's descriptor (input n x c x h_in x w_in, k_out filters),
+ * any stride.  All pointers are device pointers, 16-byte
  * aligned, caller-owned; work is enqueued on hip_stream without synchronising.
  *
  *   xnor_bingrad_pack_weights  w float32 [k_out][c][kh][kw] (the forward tensor)  ->  the filters of the
@@ -246,7 +246,9 @@ int xnor_bwn_conv2d(const void *parts, const void *wimg, const float *alpha, flo
  *   xnor_bingrad_conv2d        gbits, wtbits, wtmfma, gmax, ones  ->  g_in float32 [n][c][h_in][w_in] =
  *       gmax[n] * sum over filters and taps of sign(gd) * sign(W) (positions that were padding in the forward
  *       pass receive and contribute nothing); dot_out int32 [n][c][h_in][w_in] (may be NULL) = the integer sum.
- *       scale_plane float32 [n][h_in][w_in] is scratch the caller provides (overwritten).  algo as xnor_conv2d.
+ *       scale_plane float32 [n][h_in][w_in] is scratch the caller provides (overwritten).  algo as xnor_conv2d;
+ *       for a forward stride above 1 the gradient is staged with zeros between its pixels, which the matrix-core
+ *       paths do (wtmfma required; XNOR_ALGO_POPCOUNT gives XNOR_ERR_UNSUPPORTED).
  * The straight-through factor of sign() on the forward input and the gradient through K are not part of
  * these calls.
  */

@@ -34,6 +34,9 @@ xnor_status make_geom(const xnor_conv_desc *d, ConvGeom *g)
     g->div_wo = FastDiv::make((uint32_t)wo);
     g->div_howo = FastDiv::make((uint32_t)(ho * wo));
     g->div_kw = FastDiv::make((uint32_t)d->kw);
+    g->dil_h = g->dil_w = 1;
+    g->real_h = g->h; g->real_w = g->w;
+    g->div_dil_h = g->div_dil_w = FastDiv::make(1u);
     return XNOR_OK;
 }
 
@@ -160,19 +163,18 @@ int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma
     return launch_pack_weights(w, wbits, alpha, wmfma, k_out, c, kh * kw, (hipStream_t)hip_stream);
 }
 
-int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
-                const float *K, const float *A, const float *alpha, float *out, int32_t *dot_out,
-                const xnor_conv_desc *d, int algo, void *hip_stream)
+namespace {
+// Inner-loop choice for a validated geometry.  A dilated input (transposed convolution of a strided layer) is
+// staged by the matrix-core kernels only, and needs K given (A of the virtual image does not exist).
+xnor_status conv_dispatch(const ConvGeom &g, const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+                          const float *K, const float *A, const float *alpha, float *out, int32_t *dot_out,
+                          int algo, hipStream_t st)
 {
-    if (!xbits || !wbits || (!K && !A) || !alpha || !out) return XNOR_ERR_NULL;
-    ConvGeom g;
-    if (xnor_status s = make_geom(d, &g)) return s;
-    if (!aligned16(xbits) || !aligned16(wbits) || !aligned16(wmfma) || !aligned16(K) || !aligned16(A) ||
-        !aligned16(alpha) || !aligned16(out) || !aligned16(dot_out))
-        return XNOR_ERR_ALIGN;
-    hipStream_t st = (hipStream_t)hip_stream;
+    const bool dilated = g.dil_h > 1 || g.dil_w > 1;
+    if (dilated && !K) return XNOR_ERR_UNSUPPORTED;
     switch (algo) {
     case XNOR_ALGO_POPCOUNT:
+        if (dilated) return XNOR_ERR_UNSUPPORTED;
         return launch_conv_popcount(xbits, wbits, wmfma, K, A, alpha, out, dot_out, g, st);
     case XNOR_ALGO_MFMA_I8:
     case XNOR_ALGO_MFMA_F4:
@@ -185,11 +187,26 @@ int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
             s = launch_conv_mfma(0, xbits, wmfma, K, A, alpha, out, dot_out, g, st);
             if (s != XNOR_ERR_UNSUPPORTED) return s;
         }
+        if (dilated) return XNOR_ERR_UNSUPPORTED;
         return launch_conv_popcount(xbits, wbits, wmfma, K, A, alpha, out, dot_out, g, st);
     }
     default:
         return XNOR_ERR_UNSUPPORTED;
     }
+}
+}  // namespace
+
+int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+                const float *K, const float *A, const float *alpha, float *out, int32_t *dot_out,
+                const xnor_conv_desc *d, int algo, void *hip_stream)
+{
+    if (!xbits || !wbits || (!K && !A) || !alpha || !out) return XNOR_ERR_NULL;
+    ConvGeom g;
+    if (xnor_status s = make_geom(d, &g)) return s;
+    if (!aligned16(xbits) || !aligned16(wbits) || !aligned16(wmfma) || !aligned16(K) || !aligned16(A) ||
+        !aligned16(alpha) || !aligned16(out) || !aligned16(dot_out))
+        return XNOR_ERR_ALIGN;
+    return conv_dispatch(g, xbits, wbits, wmfma, K, A, alpha, out, dot_out, algo, (hipStream_t)hip_stream);
 }
 
 int xnor_conv2d_pool(const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
@@ -330,21 +347,29 @@ int xnor_bingrad_conv2d(const uint32_t *gbits, const uint32_t *wtbits, const voi
     if (!gbits || !wtbits || !gmax || !ones || !scale_plane || !g_in) return XNOR_ERR_NULL;
     ConvGeom fwd;
     if (xnor_status s = make_geom(d, &fwd)) return s;
-    if (fwd.sh != 1 || fwd.sw != 1) return XNOR_ERR_UNSUPPORTED;
-    // transpose of a stride-1 correlation: a stride-1 correlation of the h_out x w_out gradient (k_out
-    // channels) with c rotated filters and padding kh-1-pad, which gives back h_in x w_in
+    // Transpose of the forward correlation: a stride-1 correlation of the gradient, dilated by the forward
+    // stride (zeros between its pixels) and extended by the input rows and columns the last forward window
+    // left uncovered, with the c rotated filters and padding kh-1-pad; it gives back h_in x w_in.
     xnor_conv_desc t;
-    t.n = fwd.n; t.c = fwd.k_out; t.h_in = fwd.ho; t.w_in = fwd.wo;
+    t.n = fwd.n; t.c = fwd.k_out;
+    t.h_in = fwd.h + 2 * fwd.ph - fwd.kh + 1;            // = (h_out-1)*stride_h + 1 + uncovered rows
+    t.w_in = fwd.w + 2 * fwd.pw - fwd.kw + 1;
     t.k_out = fwd.c; t.kh = fwd.kh; t.kw = fwd.kw;
     t.stride_h = 1; t.stride_w = 1;
     t.pad_h = fwd.kh - 1 - fwd.ph; t.pad_w = fwd.kw - 1 - fwd.pw;
-    if (!aligned16(gmax) || !aligned16(scale_plane)) return XNOR_ERR_ALIGN;
+    if (!aligned16(gbits) || !aligned16(wtbits) || !aligned16(wtmfma) || !aligned16(gmax) || !aligned16(ones) ||
+        !aligned16(scale_plane) || !aligned16(g_in) || !aligned16(dot_out))
+        return XNOR_ERR_ALIGN;
     ConvGeom g;
     if (xnor_status s = make_geom(&t, &g)) return s;
     if (g.ho != fwd.h || g.wo != fwd.w) return XNOR_ERR_SHAPE;
+    g.dil_h = fwd.sh; g.dil_w = fwd.sw;
+    g.real_h = fwd.ho; g.real_w = fwd.wo;
+    g.div_dil_h = FastDiv::make((uint32_t)fwd.sh);
+    g.div_dil_w = FastDiv::make((uint32_t)fwd.sw);
     hipStream_t st = (hipStream_t)hip_stream;
     if (xnor_status s = launch_bingrad_scale_plane(gmax, scale_plane, fwd.n, fwd.h * fwd.w, st)) return s;
-    return xnor_conv2d(gbits, wtbits, wtmfma, scale_plane, nullptr, ones, g_in, dot_out, &t, algo, hip_stream);
+    return conv_dispatch(g, gbits, wtbits, wtmfma, scale_plane, nullptr, ones, g_in, dot_out, algo, st);
 }
 
 namespace {

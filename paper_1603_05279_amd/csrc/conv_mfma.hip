@@ -132,7 +132,10 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         const uint32_t R = (uint32_t)(r_lo + rr);
         const uint32_t img = pl.div_hp.div(R);
         const int y = (int)(R - img * g.hp) - g.ph;
-        rowinfo[rr] = (y >= 0 && y < g.h) ? (int)((img * g.h + y) * g.w) : -1;    // first pixel of the row
+        // first pixel of the (real) input row, -1 for padding rows and the zero rows of a dilated input
+        const uint32_t ry = g.div_dil_h.div((uint32_t)max(y, 0));
+        const bool rv = y >= 0 && y < g.h && (int)ry * g.dil_h == y && (int)ry < g.real_h;
+        rowinfo[rr] = rv ? (int)((img * g.real_h + ry) * g.real_w) : -1;
     }
     XNOR_TL(5);
     // LDS offset of every channel block of a chunk relative to a pixel's window origin:
@@ -204,9 +207,10 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
                 const uint32_t px = pl.div_ccw.div(itc);
                 const int wl = (int)(itc - px * ccw);
                 const uint32_t rr = pl.div_wp.div(px);
-                const int xcol = (int)(px - rr * g.wp) - g.pw;
+                const int xv = (int)(px - rr * g.wp) - g.pw;                 // column of the (virtual) input
+                const int xcol = (int)g.div_dil_w.div((uint32_t)max(xv, 0));  // column of the real tensor
                 const int rowbase = rowinfo[rr];
-                ok[u] = rowbase >= 0 && xcol >= 0 && xcol < g.w;
+                ok[u] = rowbase >= 0 && xv >= 0 && xv < g.w && xcol * g.dil_w == xv && xcol < g.real_w;
                 dst[u] = it < items ? (int)(rr * pl.row_pitch + (px - rr * g.wp) * pl.ps + wl * E::BPB) : -1;
                 nch[u] = g.c - (wbase + wl) * 32;
                 bits[u] = 0;
@@ -833,7 +837,7 @@ xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, 
                              const float *alpha, float *out, int32_t *dot_out,
                              const ConvGeom &g, hipStream_t stream, const FuseArgs *fz)
 {
-    if (g_tile_override == 10 && !fz && fmt != 2) {      // persistent kernel where its LDS plan fits, tiled kernel otherwise
+    if (g_tile_override == 10 && !fz && fmt != 2 && g.dil_h == 1 && g.dil_w == 1) {      // persistent kernel where its LDS plan fits, tiled kernel otherwise
         const xnor_status s = launch_conv_mfma_pipe(fmt, xbits, wmfma, K, A, alpha, out, dot_out, g, stream);
         if (s != XNOR_ERR_UNSUPPORTED) return s;
     }

@@ -31,6 +31,11 @@ struct ConvGeom {
     int m_total;       // n*ho*wo output pixels
     int fblocks;       // ceil(k_out/32) filter blocks in the matrix-core weight image
     FastDiv div_wo, div_howo, div_kw;
+    // Input dilation (transposed convolutions of strided layers): the h x w input above is a virtual image
+    // whose pixel (y, x) is pixel (y / dil_h, x / dil_w) of the real real_h x real_w tensor when both
+    // divisions are exact and in range, and zero otherwise.  1 / h / w for ordinary convolutions.
+    int dil_h, dil_w, real_h, real_w;
+    FastDiv div_dil_h, div_dil_w;
 };
 
 // K of output pixel m (flattened image, row, column): the in-bounds taps of A summed in row-major

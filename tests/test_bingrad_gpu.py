@@ -12,7 +12,7 @@ from tests.helpers import to_dev
 
 pytestmark = pytest.mark.gpu
 
-# forward layer: n, c, h, w, k_out, kh, kw, pad  (stride 1)
+# forward layer: n, c, h, w, k_out, kh, kw, pad  (stride 1; strided layers below)
 CASES = [
     (1, 1, 1, 1, 1, 1, 1, (0, 0)),
     (2, 3, 5, 7, 2, 3, 3, (1, 1)),
@@ -35,11 +35,11 @@ def pack_bits(sg):
     return (bits.reshape(n, h, w, kw_, 32) << np.arange(32, dtype=np.uint64)).sum(axis=-1).astype(np.uint32)
 
 
-def run(g, W, K, alpha, in_hw, pad, algo, with_dot=True):
+def run(g, W, K, alpha, in_hw, pad, algo, with_dot=True, stride=(1, 1)):
     n, k, ho, wo = g.shape
     _, c, kh, kw = W.shape
     h, w = in_hw
-    desc = xnor.make_desc(n, c, h, w, k, kh, kw, (1, 1), pad)
+    desc = xnor.make_desc(n, c, h, w, k, kh, kw, stride, pad)
     assert xnor.output_hw(desc) == (ho, wo)
     dev = "cuda"
     wtbits = torch.empty((c, kh * kw, xnor.words_per_pixel(k)), dtype=torch.int32, device=dev)
@@ -59,8 +59,8 @@ def run(g, W, K, alpha, in_hw, pad, algo, with_dot=True):
             "dot": None if dot is None else dot.cpu().numpy(), "ones": ones.cpu().numpy()}
 
 
-def check(r, g, W, K, alpha, in_hw, pad):
-    ref = xo.binary_grad_input(g, W, K, alpha, (1, 1), pad, in_hw=in_hw)
+def check(r, g, W, K, alpha, in_hw, pad, stride=(1, 1)):
+    ref = xo.binary_grad_input(g, W, K, alpha, stride, pad, in_hw=in_hw)
     assert np.array_equal(r["gbits"], pack_bits(ref["sg"]))
     assert np.array_equal(r["gmax"], ref["gmax"])
     assert (r["ones"] == 1.0).all()
@@ -87,6 +87,31 @@ def test_bingrad_matches_oracle(case, algo):
     check(r, g, W, K, alpha, (h, w), pad)
 
 
+# n, c, h, w, k_out, kh, kw, stride, pad: strided forward layers (the gradient is staged with zeros between pixels)
+STRIDED = [
+    (2, 3, 9, 9, 4, 3, 3, (2, 2), (1, 1)),
+    (1, 40, 11, 14, 70, 3, 3, (2, 1), (0, 1)),          # uncovered input rows at the bottom: (11 - 3) % 2 = 0, (14 + 2 - 3) % 1 = 0
+    (3, 33, 12, 13, 31, 4, 2, (2, 2), (1, 0)),          # (12 + 2 - 4) % 2 = 0, (13 - 2) % 2 = 1: one uncovered column
+    (2, 64, 28, 28, 128, 3, 3, (2, 2), (1, 1)),         # ResNet down-sampling geometry
+    (1, 20, 17, 9, 10, 5, 3, (3, 2), (2, 1)),
+    (2, 96, 16, 16, 130, 1, 1, (2, 2), (0, 0)),         # strided 1x1 (projection shortcut)
+]
+
+
+@pytest.mark.parametrize("algo", ["mfma_i8", "mfma_f4", "auto"])
+@pytest.mark.parametrize("case", STRIDED)
+def test_bingrad_strided_layers(case, algo):
+    n, c, h, w, k, kh, kw, stride, pad = case
+    print("case", case, algo, flush=True)
+    x, W = wl.random_conv_case(171 + c + k, n, c, h, w, k, kh, kw)
+    ho, wo = xo.out_hw(h, w, kh, kw, stride, pad)
+    g = np.random.default_rng(15 + c).standard_normal((n, k, ho, wo)).astype(np.float32)
+    fwd = xo.binary_conv2d(x, W, stride, pad)
+    K, alpha = fwd["K"].astype(np.float32), fwd["alpha"].astype(np.float32)
+    r = run(g, W, K, alpha, (h, w), pad, algo, stride=stride)
+    check(r, g, W, K, alpha, (h, w), pad, stride=stride)
+
+
 def test_without_K_and_alpha_the_gradient_itself_is_binarised():
     rng = np.random.default_rng(8)
     g = rng.standard_normal((2, 45, 6, 9)).astype(np.float32)
@@ -109,7 +134,7 @@ def test_all_zero_and_nan_gradients():
 
 def test_errors():
     dev = "cuda"
-    desc = xnor.make_desc(1, 8, 9, 9, 8, 3, 3, (2, 2), (1, 1))        # stride 2: not built
+    desc = xnor.make_desc(1, 8, 9, 9, 8, 3, 3, (2, 2), (1, 1))        # stride 2 on the vector-ALU path: not built
     t = lambda *s, dt=torch.float32: torch.zeros(s, dtype=dt, device=dev)
     import ctypes
     L = xnor.lib()
