@@ -68,18 +68,17 @@ def test_random_shapes_binary_gradient():
     from tests.test_bingrad_gpu import check as check_bg, run as run_bg
     done = 0
     for idx, (n, c, h, w, k_out, kh, kw, stride, pad) in enumerate(SHAPES):
-        if stride != (1, 1):
-            continue
         print("shape", idx, (n, c, h, w, k_out, kh, kw, stride, pad), "bingrad", flush=True)
         x, wt = wl.random_conv_case(3900 + idx, n, c, h, w, k_out, kh, kw)
         ho, wo = xo.out_hw(h, w, kh, kw, stride, pad)
         g = np.random.default_rng(idx).standard_normal((n, k_out, ho, wo)).astype(np.float32)
         fwd = xo.binary_conv2d(x, wt, stride, pad)
         K, alpha = fwd["K"].astype(np.float32), fwd["alpha"].astype(np.float32)
-        algo = ("popcount", "mfma_i8", "mfma_f4")[idx % 3]
-        check_bg(run_bg(g, wt, K, alpha, (h, w), pad, algo), g, wt, K, alpha, (h, w), pad)
+        # strided layers run on the matrix-core paths only
+        algo = ("popcount", "mfma_i8", "mfma_f4")[idx % 3] if stride == (1, 1) else ("mfma_i8", "mfma_f4", "auto")[idx % 3]
+        check_bg(run_bg(g, wt, K, alpha, (h, w), pad, algo, stride=stride), g, wt, K, alpha, (h, w), pad, stride=stride)
         done += 1
-    assert done >= 5
+    assert done >= 20
 
 
 def test_random_shapes_kbit():
