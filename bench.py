@@ -184,17 +184,14 @@ def report(args):
             else:
                 row += " - | - | - |"
             # 2-bit inputs x 2-bit weights (inputs scaled into [-1, 1])
-            cw32 = xnor.words_per_pixel(c)
             xs = torch.tanh(x)
-            xpl = torch.empty((2, n, h, w_, cw32), dtype=torch.int32, device="cuda")
-            wb2 = torch.empty((2 * k, kh * kw, cw32), dtype=torch.int32, device="cuda")
-            wm2, ones2 = u8(xnor.wmfma_bytes(2 * k, c, kh, kw)), torch.empty((2 * k,), device="cuda")
-            ws2 = u8(xnor.kbit_workspace_bytes(desc, 2, 2))
-            xnor.xnor_kbit_pack_weights(torch.tanh(wt), wb2, ones2, wm2, 2, k, c, kh, kw)
-            kp_us = median_us(lambda: xnor.xnor_kbit_pack_input(xs, xpl, 2, n, c, h, w_))
-            kc_us = median_us(lambda: xnor.xnor_kbit_conv2d(xpl, wb2, wm2, ones2, ws2, out, None, desc, 2, 2))
+            xq, wq2 = u8(xnor.kbit_input_bytes(n, c, h, w_)), u8(xnor.kbit_wimg_bytes(k, c, kh, kw))
+            scale2 = torch.empty((k,), device="cuda")
+            xnor.xnor_kbit_pack_weights(torch.tanh(wt), scale2, wq2, 2, 2, k, c, kh, kw)
+            kp_us = median_us(lambda: xnor.xnor_kbit_pack_input(xs, xq, 2, n, c, h, w_))
+            kc_us = median_us(lambda: xnor.xnor_kbit_conv2d(xq, wq2, scale2, out, None, desc, 2, 2))
             row += f" {kp_us:.1f} | {kc_us:.1f} |"
-            del xpl, wb2, wm2, ws2
+            del xq, wq2
             # max-pool 3x3 stride 2 of this layer's output fused into the next block's BinActiv
             if ho >= 3 and wo >= 3:
                 hp_, wp_ = (ho - 3) // 2 + 1, (wo - 3) // 2 + 1

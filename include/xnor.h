@@ -263,27 +263,28 @@ int xnor_bingrad_conv2d(const uint32_t *gbits, const uint32_t *wtbits, const voi
 /*
  * k-bit quantisation (sec. 3.2, paragraph "k-bit Quantization"): q_k(x) = 2*([(2^k-1)(x+1)/2]/(2^k-1) - 1/2) in
  * place of sign(), x in [-1, 1] (values outside are clamped, NaN counts as -1; halves round up, so q_1 = sign
- * with sign(0) = +1; the level is decided in float32 as floor(((x + 1) * 0.5) * (2^k - 1) + 0.5)).  A k-bit
- * tensor is k weighted +-1 tensors (its bit planes), so the convolution of ka-bit inputs with kw-bit weights
- * runs as one binary convolution over ka*n images and kw*k_out filters plus a weighted sum:
+ * with sign(0) = +1; the level is decided in float32 as u = floor(((x + 1) * 0.5) * (2^k - 1) + 0.5)).
+ * q_k = (2u - L)/L with L = 2^k - 1, so the convolution of ka-bit inputs with kw-bit weights is an exact integer
+ * sum of numerator products divided by La * Lw; it runs on the int8 matrix cores:
  *   out[n][k_out][h_out][w_out] = sum q_ka(x) * q_kw(w) over the in-bounds window, no K, no alpha.
- * ka, kw in 1..8.  Device pointers, 16-byte aligned, caller-owned; enqueued on hip_stream.
- *   xnor_kbit_pack_input    x float32 [n][c][h][w] -> xplanes uint32 [ka][n][h][w][ceil(c/32)]
- *   xnor_kbit_pack_weights  w float32 [k_out][c][kh][kw] -> wbits uint32 [kw*k_out][kh*kw][ceil(c/32)],
- *                           wmfma = xnor_wmfma_bytes(kw*k_out, c, kh, kw) bytes (may be NULL), ones float32
- *                           [kw*k_out] (written with 1.0); once per layer
- *   xnor_kbit_conv2d        workspace = xnor_kbit_workspace_bytes(d, ka, kw) bytes of scratch (overwritten);
- *                           num_out int32 [n][k_out][h_out][w_out] (may be NULL) = the integer numerator
- *                           sum (2u_x - La)(2u_w - Lw), out = num / (La * Lw) with La = 2^ka - 1, Lw = 2^kw - 1.
- *                           XNOR_ERR_UNSUPPORTED when La * Lw * c * kh * kw does not fit 31 bits.
+ * ka, kw in 1..7 (the numerators of 7-bit levels, -127..127, are the widest that fit int8).  Device pointers,
+ * 16-byte aligned, caller-owned; enqueued on hip_stream.
+ *   xnor_kbit_pack_input    x float32 [n][c][h][w] -> xq, xnor_kbit_input_bytes(n, c, h, w) bytes: the numerators
+ *                           2u - La as int8, [n][h][w][ceil(c/32)][32], 0 past the last channel
+ *   xnor_kbit_pack_weights  w float32 [k_out][c][kh][kw] -> wq, xnor_kbit_wimg_bytes(k_out, c, kh, kw) bytes
+ *                           (opaque), scale float32 [k_out] (written with 1 / (La * Lw)); once per layer
+ *   xnor_kbit_conv2d        num_out int32 [n][k_out][h_out][w_out] (may be NULL) = the integer numerator
+ *                           sum (2u_x - La)(2u_w - Lw), out = float(num) * scale (two float roundings: within
+ *                           2e-7 relative of num / (La * Lw)).  XNOR_ERR_UNSUPPORTED when La * Lw * c * kh * kw
+ *                           does not fit 31 bits.
  */
-size_t xnor_kbit_workspace_bytes(const xnor_conv_desc *d, int ka, int kw);
-int xnor_kbit_pack_input(const float *x, uint32_t *xplanes, int ka, int n, int c, int h, int w, void *hip_stream);
-int xnor_kbit_pack_weights(const float *w, uint32_t *wbits, float *ones, void *wmfma, int kw_bits,
+size_t xnor_kbit_input_bytes(int n, int c, int h, int w);
+size_t xnor_kbit_wimg_bytes(int k_out, int c, int kh, int kw);
+int xnor_kbit_pack_input(const float *x, void *xq, int ka, int n, int c, int h, int w, void *hip_stream);
+int xnor_kbit_pack_weights(const float *w, float *scale, void *wq, int ka, int kw_bits,
                            int k_out, int c, int kh, int kw, void *hip_stream);
-int xnor_kbit_conv2d(const uint32_t *xplanes, const uint32_t *wbits, const void *wmfma, const float *ones,
-                     void *workspace, float *out, int32_t *num_out, const xnor_conv_desc *d,
-                     int ka, int kw_bits, int algo, void *hip_stream);
+int xnor_kbit_conv2d(const void *xq, const void *wq, const float *scale, float *out, int32_t *num_out,
+                     const xnor_conv_desc *d, int ka, int kw_bits, void *hip_stream);
 
 /*
  * Fully connected layer = convolution whose filter covers the whole input (footnote of sec. 1).

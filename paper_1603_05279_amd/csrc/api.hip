@@ -372,72 +372,56 @@ int xnor_bingrad_conv2d(const uint32_t *gbits, const uint32_t *wtbits, const voi
     return conv_dispatch(g, gbits, wtbits, wtmfma, scale_plane, nullptr, ones, g_in, dot_out, algo, st);
 }
 
-namespace {
-// descriptor of the stacked binary convolution behind a k-bit one: ka*n images, kw*k_out filters
-xnor_status kbit_desc(const xnor_conv_desc *d, int ka, int kw, xnor_conv_desc *t)
+size_t xnor_kbit_input_bytes(int n, int c, int h, int w)
 {
-    if (!d) return XNOR_ERR_NULL;
-    if (ka < 1 || ka > 8 || kw < 1 || kw > 8) return XNOR_ERR_SHAPE;
-    if (d->n <= 0 || d->k_out <= 0 || d->n > 0x7fffffff / ka || d->k_out > 0x7fffffff / kw) return XNOR_ERR_SHAPE;
-    *t = *d;
-    t->n = d->n * ka;
-    t->k_out = d->k_out * kw;
-    return XNOR_OK;
-}
-}  // namespace
-
-size_t xnor_kbit_workspace_bytes(const xnor_conv_desc *d, int ka, int kw)
-{
-    xnor_conv_desc t;
-    ConvGeom g;
-    if (kbit_desc(d, ka, kw, &t) != XNOR_OK || make_geom(&t, &g) != XNOR_OK) return 0;
-    // a plane of ones [ka*n][h_out*w_out] (padded to 16 bytes), then the plane-pair dot products
-    // [ka*n][kw*k_out][h_out*w_out], floats
-    return (((size_t)g.m_total + 3) / 4 * 4 + (size_t)g.m_total * (size_t)g.k_out) * sizeof(float);
+    if (n <= 0 || c <= 0 || h <= 0 || w <= 0) return 0;
+    return (size_t)n * h * w * (size_t)((c + 31) / 32) * 32u;
 }
 
-int xnor_kbit_pack_input(const float *x, uint32_t *xplanes, int ka, int n, int c, int h, int w, void *hip_stream)
+size_t xnor_kbit_wimg_bytes(int k_out, int c, int kh, int kw)
 {
-    if (!x || !xplanes) return XNOR_ERR_NULL;
-    if (ka < 1 || ka > 8 || n <= 0 || c <= 0 || h <= 0 || w <= 0) return XNOR_ERR_SHAPE;
-    if ((long long)h * w > 0x7fffffffLL || (long long)ka * n * h * w * ((c + 31) / 32) > 0x7fffffffLL ||
+    if (k_out <= 0 || c <= 0 || kh <= 0 || kw <= 0 || (long long)kh * kw > 4096) return 0;
+    return wimg_i8_bytes(k_out, c, kh * kw);
+}
+
+int xnor_kbit_pack_input(const float *x, void *xq, int ka, int n, int c, int h, int w, void *hip_stream)
+{
+    if (!x || !xq) return XNOR_ERR_NULL;
+    if (ka < 1 || ka > 7 || n <= 0 || c <= 0 || h <= 0 || w <= 0) return XNOR_ERR_SHAPE;
+    if ((long long)h * w > 0x7fffffffLL || (long long)n * h * w * ((c + 31) / 32) > 0x7fffffffLL / 8 ||
         (long long)n * c > 0x7fffffffLL)
         return XNOR_ERR_SHAPE;
-    if (!aligned16(x) || !aligned16(xplanes)) return XNOR_ERR_ALIGN;
-    return launch_kbit_pack_input(x, xplanes, ka, n, c, h * w, (hipStream_t)hip_stream);
+    if (!aligned16(x) || !aligned16(xq)) return XNOR_ERR_ALIGN;
+    return launch_kbit_pack_input(x, static_cast<int8_t *>(xq), ka, n, c, h * w, (hipStream_t)hip_stream);
 }
 
-int xnor_kbit_pack_weights(const float *w, uint32_t *wbits, float *ones, void *wmfma, int kw_bits,
+int xnor_kbit_pack_weights(const float *w, float *scale, void *wq, int ka, int kw_bits,
                            int k_out, int c, int kh, int kw, void *hip_stream)
 {
-    if (!w || !wbits || !ones) return XNOR_ERR_NULL;
-    if (kw_bits < 1 || kw_bits > 8 || k_out <= 0 || c <= 0 || kh <= 0 || kw <= 0) return XNOR_ERR_SHAPE;
-    if ((long long)kh * kw > 4096 || (long long)kw_bits * k_out * kh * kw * ((c + 31) / 32) > 0x7fffffffLL ||
+    if (!w || !scale || !wq) return XNOR_ERR_NULL;
+    if (ka < 1 || ka > 7 || kw_bits < 1 || kw_bits > 7 || k_out <= 0 || c <= 0 || kh <= 0 || kw <= 0) return XNOR_ERR_SHAPE;
+    if ((long long)kh * kw > 4096 || (long long)k_out * kh * kw * ((c + 31) / 32) > 0x7fffffffLL ||
         (long long)c * kh * kw > 0x7fffffffLL)
         return XNOR_ERR_SHAPE;
-    if (!aligned16(w) || !aligned16(wbits) || !aligned16(ones) || !aligned16(wmfma)) return XNOR_ERR_ALIGN;
-    return launch_pack_weights(w, wbits, ones, wmfma, kw_bits * k_out, c, kh * kw, (hipStream_t)hip_stream, 2, kw_bits);
+    if (!aligned16(w) || !aligned16(scale) || !aligned16(wq)) return XNOR_ERR_ALIGN;
+    const double s = (double)((1 << ka) - 1) * (double)((1 << kw_bits) - 1);
+    return launch_pack_weights(w, nullptr, scale, wq, k_out, c, kh * kw, (hipStream_t)hip_stream, 3, kw_bits,
+                               (float)(1.0 / s));
 }
 
-int xnor_kbit_conv2d(const uint32_t *xplanes, const uint32_t *wbits, const void *wmfma, const float *ones,
-                     void *workspace, float *out, int32_t *num_out, const xnor_conv_desc *d,
-                     int ka, int kw_bits, int algo, void *hip_stream)
+int xnor_kbit_conv2d(const void *xq, const void *wq, const float *scale, float *out, int32_t *num_out,
+                     const xnor_conv_desc *d, int ka, int kw_bits, void *hip_stream)
 {
-    if (!xplanes || !wbits || !ones || !workspace || !out) return XNOR_ERR_NULL;
-    xnor_conv_desc t;
-    if (xnor_status s = kbit_desc(d, ka, kw_bits, &t)) return s;
+    if (!xq || !wq || !scale || !out) return XNOR_ERR_NULL;
+    if (ka < 1 || ka > 7 || kw_bits < 1 || kw_bits > 7) return XNOR_ERR_SHAPE;
     ConvGeom g;
-    if (xnor_status s = make_geom(&t, &g)) return s;
-    const long long scale = (long long)((1 << ka) - 1) * ((1 << kw_bits) - 1);
-    if (scale * g.c * g.taps > 0x7fffffffLL || (long long)g.c * g.taps >= (1ll << 24)) return XNOR_ERR_UNSUPPORTED;
-    if (!aligned16(workspace) || !aligned16(out) || !aligned16(num_out)) return XNOR_ERR_ALIGN;
-    hipStream_t st = (hipStream_t)hip_stream;
-    float *ones_plane = static_cast<float *>(workspace);
-    float *dots = ones_plane + ((size_t)g.m_total + 3) / 4 * 4;
-    if (xnor_status s = launch_fill_ones(ones_plane, (size_t)g.m_total, st)) return s;
-    // with K = 1 and alpha = 1 the binary convolution returns the +-1 dot products themselves (exact in float)
-    if (int s = xnor_conv2d(xplanes, wbits, wmfma, ones_plane, nullptr, ones, dots, nullptr, &t, algo, hip_stream)) return s;
-    return launch_kbit_combine(dots, out, num_out, d->n, d->k_out, g.ho * g.wo, ka, kw_bits, st);
+    if (xnor_status s = make_geom(d, &g)) return s;
+    const long long lw = (long long)((1 << ka) - 1) * ((1 << kw_bits) - 1);
+    if (lw * g.c * g.taps > 0x7fffffffLL) return XNOR_ERR_UNSUPPORTED;       // the int32 accumulator holds every sum
+    if (!aligned16(xq) || !aligned16(wq) || !aligned16(scale) || !aligned16(out) || !aligned16(num_out))
+        return XNOR_ERR_ALIGN;
+    return launch_conv_mfma(3, static_cast<const uint32_t *>(xq), wq, nullptr, nullptr, scale, out, num_out, g,
+                            (hipStream_t)hip_stream);
 }
 
 int xnor_linear(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,

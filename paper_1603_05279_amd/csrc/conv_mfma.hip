@@ -42,6 +42,8 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     float *__restrict__ out, int32_t *__restrict__ dot_out, ConvGeom g, MfmaPlan pl, FuseArgs fz)
 {
     typedef Enc<FMT> E;
+    // operands staged as they are (no sign bits to widen, no K): bfloat16 parts and int8 levels
+    constexpr bool RAW = FMT == 2 || FMT == 3;
     typedef typename E::acc_t acc_t;
     constexpr int NT = 64 * WF * WP;
     constexpr int FT = 32 * FW * WF;
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
                 dst[u] = it < items ? (int)(rr * pl.row_pitch + (px - rr * g.wp) * pl.ps + wl * E::BPB) : -1;
                 nch[u] = g.c - (wbase + wl) * 32;
                 bits[u] = 0;
-                if constexpr (FMT == 2) {
+                if constexpr (RAW) {
                     raw[u][0] = raw[u][1] = make_uint4(0, 0, 0, 0);
                     if (ok[u]) {
                         const uint4 *src = reinterpret_cast<const uint4 *>(xbits) +
@@ -229,7 +231,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
 #pragma unroll
             for (int u = 0; u < FB; ++u)
                 if (dst[u] >= 0) {
-                    if constexpr (FMT == 2) {
+                    if constexpr (RAW) {
                         *reinterpret_cast<uint4 *>(lds + dst[u]) = raw[u][0];
                         *reinterpret_cast<uint4 *>(lds + dst[u] + 16) = raw[u][1];
                     } else {
@@ -237,7 +239,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
                     }
                 }
         }
-        if (FMT != 2 && wbase == 0 && !K) {
+        if (!RAW && wbase == 0 && !K) {
             // stage the matrix A of the same input rows (0 in the halo) for the K of this tile
             for (int it = tid; it < nrows * g.wp; it += NT) {
                 const uint32_t rr = pl.div_wp.div((uint32_t)it);
@@ -249,7 +251,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         }
         __syncthreads();
         if (wbase == 0) XNOR_TL(2);
-        if (FMT != 2 && wbase == 0 && !K) for (int kt = tid; kt < PT; kt += NT) {
+        if (!RAW && wbase == 0 && !K) for (int kt = tid; kt < PT; kt += NT) {
             // K of output pixel m0 + tid: the kh x kw taps of A in row-major order over the staged
             // rows (halo entries add +0.0f, the same bits as skipping them), divided by kh*kw
             const uint32_t m = min(m0 + (uint32_t)kt, m_end - 1u);
@@ -284,7 +286,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     // epilogue: out = float(dot) * K * alpha; result register v of a lane is filter row
     // 8*(v/4) + 4*half + v%4 of the 32-filter block, pixel column l32.  alpha of the lane's
     // filter rows is fetched once (clamped index, no branch), stores are predicated.
-    if (FMT != 2 && !K) __syncthreads();      // the K tile is complete
+    if (!RAW && !K) __syncthreads();      // the K tile is complete
     uint32_t pimg[PW], ppix[PW];
     float Km[PW];
     bool plive[PW];
@@ -296,7 +298,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         const uint32_t mc = plive[j] ? m : m_end - 1u;
         pimg[j] = g.div_howo.div(mc);
         ppix[j] = mc - pimg[j] * howo;
-        Km[j] = FMT == 2 ? 1.0f : (K ? K[mc] : ktile[pl_idx]);      // real activations carry no K
+        Km[j] = RAW ? 1.0f : (K ? K[mc] : ktile[pl_idx]);      // real and k-bit activations carry no K
     }
     // Float (and optional integer) results leave through buffer stores: the resource starts at the
     // tile's first image, a lane's vector offset names its pixel (plus its half-wave's four rows),
@@ -545,7 +547,7 @@ static const int LDS_LIMIT = 160 * 1024;
 // par_bytes: alpha (fused epilogue: also scale and shift) of the workgroup's filters
 // channel words per K-step and bytes of the widening table of an operand format (Enc<fmt>::BPS, LUT_BYTES)
 static constexpr int fmt_bps(int fmt) { return fmt == 1 ? 2 : fmt == 2 ? 3 : 1; }
-static constexpr int fmt_lut_bytes(int fmt) { return fmt == 0 ? 512 * 8 : fmt == 1 ? 512 * 4 : 0; }
+static constexpr int fmt_lut_bytes(int fmt) { return fmt == 0 ? 512 * 8 : fmt == 1 ? 512 * 4 : 0; }     // 2, 3: none
 static size_t plan_lds_bytes(const MfmaPlan &pl, int fmt, int wp, int PT, int fuse_rows, int par_bytes)
 {
     const size_t rest = (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 +
@@ -802,14 +804,14 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
     // (the bfloat16-parts format is built for the default tilings only, and without the fused epilogue)
 #define XNOR_TILE(ID, FW, PW, WF, WP)                                                                     \
     case ID:                                                                                              \
-        if constexpr (FMT == 2) return XNOR_ERR_UNSUPPORTED;                                              \
+        if constexpr (FMT >= 2) return XNOR_ERR_UNSUPPORTED;                                              \
         else {                                                                                            \
             if (fz) return XNOR_ERR_UNSUPPORTED;                                                          \
             return launch_cfg<FMT, FW, PW, WF, WP, false>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, nullptr); \
         }
 #define XNOR_TILE_F(ID, FW, PW, WF, WP)                                                                   \
     case ID:                                                                                              \
-        if constexpr (FMT != 2) {                                                                         \
+        if constexpr (FMT < 2) {                                                                          \
             if (fz) return launch_cfg<FMT, FW, PW, WF, WP, true>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, fz); \
         }                                                                                                 \
         return launch_cfg<FMT, FW, PW, WF, WP, false>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, nullptr);
@@ -837,7 +839,7 @@ xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, 
                              const float *alpha, float *out, int32_t *dot_out,
                              const ConvGeom &g, hipStream_t stream, const FuseArgs *fz)
 {
-    if (g_tile_override == 10 && !fz && fmt != 2 && g.dil_h == 1 && g.dil_w == 1) {      // persistent kernel where its LDS plan fits, tiled kernel otherwise
+    if (g_tile_override == 10 && !fz && fmt < 2 && g.dil_h == 1 && g.dil_w == 1) {      // persistent kernel where its LDS plan fits, tiled kernel otherwise
         const xnor_status s = launch_conv_mfma_pipe(fmt, xbits, wmfma, K, A, alpha, out, dot_out, g, stream);
         if (s != XNOR_ERR_UNSUPPORTED) return s;
     }
@@ -845,6 +847,8 @@ xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, 
     // fmt 2: real activations in bfloat16 parts (xbits = 32-byte words, g.c = 32 x words per pixel,
     // wmfma = the +-1 bfloat16 record image alone); no K, no fused epilogue
     if (fmt == 2) return fz ? XNOR_ERR_UNSUPPORTED : launch_fmt<2>(xbits, img, nullptr, nullptr, alpha, out, nullptr, g, stream, nullptr);
+    // fmt 3: int8 level numerators (xbits = 32-byte words of 32 channels, wmfma = an int8 record image); no K
+    if (fmt == 3) return fz ? XNOR_ERR_UNSUPPORTED : launch_fmt<3>(xbits, img, nullptr, nullptr, alpha, out, dot_out, g, stream, nullptr);
     // float accumulation of the 4-bit path is exact while every sum stays below 2^24
     if (fmt != 0 && (long long)g.c * g.taps >= (1ll << 24)) return XNOR_ERR_UNSUPPORTED;
     if (fmt == 0) return launch_fmt<0>(xbits, img, K, A, alpha, out, dot_out, g, stream, fz);

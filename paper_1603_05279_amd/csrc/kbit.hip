@@ -1,12 +1,11 @@
 // k-bit quantisation (sec. 3.2, paragraph "k-bit Quantization"): q_k(x) = 2*([(2^k - 1)(x + 1)/2]/(2^k - 1) - 1/2)
-// in place of sign().  With L = 2^k - 1 and the level index u = [L (x + 1)/2] = sum_p 2^p u_p (bits u_p),
-// q_k = (2u - L)/L = sum_p 2^p s_p / L with s_p = 2 u_p - 1 = +-1: a k-bit tensor is k weighted +-1 tensors.
-// The convolution of a ka-bit input with kw-bit weights is therefore ka*kw binary convolutions, run as
-// ONE launch of the binary kernel over ka*n "images" and kw*k_out "filters" (bit planes stacked along the
-// batch and filter axes), followed by the weighted sum of the plane pairs.  Zero padding stays exact
-// (every plane contributes 0 there).
+// in place of sign().  With L = 2^k - 1 and the level index u = [L (x + 1)/2], q_k = (2u - L)/L: an odd integer
+// in [-L, L] over L.  The convolution of ka-bit inputs with kw-bit weights is therefore an integer contraction
+// of the numerators divided by La*Lw, and runs as ONE int8 matrix-core convolution (conv_mfma.hip, operand
+// format 3: int32 accumulation, exact) on the numerators stored as int8; zero padding stays exact.
+// (The same sum could be formed from ka*kw binary convolutions of the bit planes, q_k = sum_p 2^p s_p / L; on
+// this chip the int8 contraction is ka*kw times less matrix work at half the 4-bit rate.)
 #include "xnor_internal.h"
-#include <algorithm>
 
 namespace xnor {
 
@@ -20,128 +19,55 @@ __device__ __forceinline__ int qk_level(float x, int L)
     return min(max((int)__builtin_floorf(v), 0), L);
 }
 
-// x [n][c][hw] float -> planes [k][n][hw][cw] uint32: bit j of word wd of plane p = bit p of the level index
-// of channel wd*32 + j.  Work split of the BinActiv kernel: one workgroup = 64 consecutive pixels of one
-// image x all channels, lanes along pixels, the 4 waves share the channels in groups of 8 (one byte of a
-// packed word per plane), words assembled in LDS ([plane][pixel][word]) and written as k contiguous runs.
-template <int KB>
-__global__ __launch_bounds__(256) void kbit_pack_kernel(const float *__restrict__ x, uint32_t *__restrict__ planes,
-                                                        int n, int c, int hw, int cw, int tiles_per_image)
+// x [n][c][hw] float -> xq [n][hw][cw][32] int8: byte j of word wd = 2u - L of channel wd*32 + j (0 past the
+// last channel).  One workgroup = 64 consecutive pixels of one image x 8 channel words; lanes along pixels
+// (every channel row is read as coalesced 256-byte segments), the 4 waves share the 32 groups of 8 channels,
+// a group's 8 bytes go to LDS (row stride 8*32 + 16 bytes: neighbouring lanes fall on different banks), from
+// where each pixel's words leave as one contiguous run, 16 bytes per lane.
+constexpr int KB_WORDS = 8, KB_ROW = KB_WORDS * 32 + 16;
+__global__ __launch_bounds__(256) void kbit_levels_kernel(const float *__restrict__ x, int8_t *__restrict__ xq,
+                                                          int c, int hw, int cw, int L)
 {
-    extern __shared__ __attribute__((aligned(16))) uint8_t wbytes[];      // [KB][64 px][cw words][4 bytes]
+    __shared__ __attribute__((aligned(16))) uint8_t stage[64 * KB_ROW];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const unsigned b = blockIdx.x, win = (b >> 6) << 6;
-    const int blk = (int)(win + 64u <= gridDim.x ? win + ((b & 7u) << 3) + ((b >> 3) & 7u) : b);
-    const int img = blk / tiles_per_image;
-    const int p0 = (blk - img * tiles_per_image) * 64;
+    const int p0 = blockIdx.x * 64, w0 = blockIdx.y * KB_WORDS, img = blockIdx.z;
+    const int nwords = min(KB_WORDS, cw - w0);
     const int pc = min(p0 + lane, hw - 1);
     const float *xi = x + (size_t)img * c * hw + pc;
-    const int groups = (c + 7) >> 3;
-    constexpr int L = (1 << KB) - 1;
-    const int plane_bytes = 64 * cw * 4;
 #pragma unroll 2
-    for (int gidx = wave; gidx < groups; gidx += 4) {
-        const int ch0 = gidx * 8;
+    for (int gidx = wave; gidx < nwords * 4; gidx += 4) {           // groups of 8 channels of this workgroup
+        const int ch0 = w0 * 32 + gidx * 8;
         float v[8];
 #pragma unroll
         for (int j = 0; j < 8; ++j) v[j] = xi[(size_t)min(ch0 + j, c - 1) * hw];
-        uint32_t byte[KB];
-#pragma unroll
-        for (int p = 0; p < KB; ++p) byte[p] = 0;
+        uint32_t lo = 0, hi = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int u = ch0 + j < c ? qk_level(v[j], L) : 0;
-#pragma unroll
-            for (int p = 0; p < KB; ++p) byte[p] |= ((uint32_t)(u >> p) & 1u) << j;
+            const int a = ch0 + j < c ? 2 * qk_level(v[j], L) - L : 0;
+            if (j < 4) lo |= ((uint32_t)a & 255u) << (8 * j);
+            else hi |= ((uint32_t)a & 255u) << (8 * (j - 4));
         }
-#pragma unroll
-        for (int p = 0; p < KB; ++p) wbytes[p * plane_bytes + (lane * cw) * 4 + gidx] = (uint8_t)byte[p];
+        *reinterpret_cast<uint2 *>(stage + lane * KB_ROW + gidx * 8) = make_uint2(lo, hi);
     }
     __syncthreads();
+    const int upp = nwords * 2;                       // 16-byte units per pixel
     const int npx = min(64, hw - p0);
-    const int nwords = npx * cw;
-    const uint32_t tail_mask = 0xFFFFFFFFu >> (8 * (cw * 4 - groups));      // bytes of the last word no group wrote
-#pragma unroll
-    for (int p = 0; p < KB; ++p) {
-        const uint32_t *wsrc = reinterpret_cast<const uint32_t *>(wbytes + p * plane_bytes);
-        uint32_t *dst = planes + (((size_t)p * n + img) * hw + p0) * cw;
-        for (int i = tid; i < nwords; i += 256) {
-            uint32_t word = wsrc[i];
-            if (i % cw == cw - 1) word &= tail_mask;
-            dst[i] = word;
-        }
+    int8_t *out = xq + (((size_t)img * hw + p0) * cw + w0) * 32;
+    for (int i = tid; i < npx * upp; i += 256) {
+        const int px = i / upp, u = i - px * upp;
+        *reinterpret_cast<uint4 *>(out + (size_t)px * cw * 32 + u * 16) =
+            *reinterpret_cast<const uint4 *>(stage + px * KB_ROW + u * 16);
     }
 }
 
-xnor_status launch_kbit_pack_input(const float *x, uint32_t *planes, int k, int n, int c, int hw, hipStream_t stream)
+xnor_status launch_kbit_pack_input(const float *x, int8_t *xq, int k, int n, int c, int hw, hipStream_t stream)
 {
     const int cw = (c + 31) / 32;
-    const int tiles = (hw + 63) / 64;
-    const size_t lds = (size_t)k * 64 * cw * 4;
-    if (lds > 64 * 1024 || (long long)n * tiles > 0x7fffffffLL) return XNOR_ERR_UNSUPPORTED;
-    const dim3 grid((unsigned)(n * tiles)), block(256);
-#define XNOR_KB(B) case B: kbit_pack_kernel<B><<<grid, block, lds, stream>>>(x, planes, n, c, hw, cw, tiles); break
-    switch (k) {
-        XNOR_KB(1); XNOR_KB(2); XNOR_KB(3); XNOR_KB(4); XNOR_KB(5); XNOR_KB(6); XNOR_KB(7); XNOR_KB(8);
-    default: return XNOR_ERR_UNSUPPORTED;
-    }
-#undef XNOR_KB
-    return hip_status(hipGetLastError());
-}
-
-// dots [ka*n][kw*k_out][howo]: the +-1 dot products of the plane pairs as floats (exact integers below 2^24).
-// num = sum_{p,q} 2^(p+q) dots[p*n + img][q*k_out + f], out = num / (La * Lw) with one rounding.
-constexpr int COMBINE_PLANES = 4;
-__global__ __launch_bounds__(256) void kbit_combine_kernel(const float *__restrict__ dots, float *__restrict__ out,
-                                                           int32_t *__restrict__ num_out, int n, int k_out, int howo,
-                                                           int ka, int kw, double scale, int fgroups)
-{
-    // one workgroup per image and group of 4 filters: no index divisions per element, and the loads of
-    // the 4 output planes are independent (small planes would otherwise leave a wave one load deep)
-    const int img = blockIdx.x / fgroups, f0 = (blockIdx.x - img * fgroups) * COMBINE_PLANES;
-    const size_t kk = (size_t)kw * k_out;
-    for (int pix = threadIdx.x; pix < howo; pix += 256) {
-        int num[COMBINE_PLANES];                        // fits: the host checked La * Lw * c * taps < 2^31
-#pragma unroll
-        for (int u = 0; u < COMBINE_PLANES; ++u) num[u] = 0;
-        for (int p = 0; p < ka; ++p)
-            for (int q = 0; q < kw; ++q) {
-                const float *src = dots + (((size_t)p * n + img) * kk + (size_t)q * k_out) * howo + pix;
-#pragma unroll
-                for (int u = 0; u < COMBINE_PLANES; ++u)
-                    num[u] += (int)src[(size_t)min(f0 + u, k_out - 1) * howo] << (p + q);
-            }
-#pragma unroll
-        for (int u = 0; u < COMBINE_PLANES; ++u)
-            if (f0 + u < k_out) {
-                const size_t o = ((size_t)img * k_out + f0 + u) * howo + pix;
-                if (num_out) num_out[o] = num[u];
-                out[o] = (float)((double)num[u] / scale);
-            }
-    }
-}
-
-xnor_status launch_kbit_combine(const float *dots, float *out, int32_t *num_out, int n, int k_out, int howo,
-                                int ka, int kw, hipStream_t stream)
-{
-    const int fgroups = (k_out + COMBINE_PLANES - 1) / COMBINE_PLANES;
-    if ((long long)n * fgroups > 0x7fffffffLL) return XNOR_ERR_UNSUPPORTED;
-    const double scale = (double)((1 << ka) - 1) * (double)((1 << kw) - 1);
-    kbit_combine_kernel<<<dim3((unsigned)(n * fgroups)), dim3(256), 0, stream>>>(dots, out, num_out, n, k_out, howo, ka,
-                                                                                kw, scale, fgroups);
-    return hip_status(hipGetLastError());
-}
-
-__global__ __launch_bounds__(256) void fill_ones_kernel(float *__restrict__ p, size_t count)
-{
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (size_t)gridDim.x * 256) p[i] = 1.0f;
-}
-
-xnor_status launch_fill_ones(float *p, size_t count, hipStream_t stream)
-{
-    const unsigned blocks = (unsigned)std::min<size_t>((count + 255) / 256, 4096);
-    fill_ones_kernel<<<dim3(blocks), dim3(256), 0, stream>>>(p, count);
+    const int wblocks = (cw + KB_WORDS - 1) / KB_WORDS;
+    if (wblocks > 65535 || n > 65535) return XNOR_ERR_UNSUPPORTED;
+    dim3 grid((unsigned)((hw + 63) / 64), (unsigned)wblocks, (unsigned)n);
+    kbit_levels_kernel<<<grid, dim3(256), 0, stream>>>(x, xq, c, hw, cw, (1 << k) - 1);
     return hip_status(hipGetLastError());
 }
 

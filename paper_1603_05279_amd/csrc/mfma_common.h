@@ -230,6 +230,14 @@ template <> struct Enc<2> {
     static __device__ __forceinline__ void build_lut(uint8_t *, int, int) {}
 };
 
+// k-bit quantised operands (sec. 3.2, "k-bit Quantization"): activations and weights arrive as the odd-integer
+// numerators 2u - L of their levels in int8 (32 channels = one 32-byte word per pixel, 0 past the last
+// channel), so the int8 matrix instruction accumulates the exact integer sum of products; nothing to widen.
+template <> struct Enc<3> : Enc<0> {
+    static constexpr int LUT_BYTES = 0;
+    static __device__ __forceinline__ void build_lut(uint8_t *, int, int) {}
+};
+
 // Steps the offset table is padded by beyond the last K-step (copies of the last entry): operand
 // prefetches run ahead of the loop's end by at most one turn plus the activation depth.
 constexpr int KLOOP_TABLE_PAD = 12;

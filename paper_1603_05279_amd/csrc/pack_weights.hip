@@ -18,10 +18,10 @@ namespace xnor {
 // Gradient"), read straight out of the forward tensor W [c][k_out][taps] (c = forward filters, k_out =
 // forward channels in this kernel's naming): filter k, channel ch, tap t is W[ch][k][taps - 1 - t], the
 // forward filter rotated by 180 degrees with the two channel axes exchanged.
-// MODE 2 (bit planes of k-bit quantised weights, sec. 3.2 "k-bit Quantization"): the kernel's k_out counts
-// planes x filters; "filter" p * (k_out / aux) + f is plane p of filter f: +1 where bit p of the level index
-// of q_aux(w) is set, -1 where it is clear (q_k = sum_p 2^p s_p / (2^k - 1) with s_p = +-1).
-// In both modes alpha is written as 1 (the scaling of those convolutions is applied elsewhere).
+// MODE 3 (k-bit quantised weights as int8 levels): the int8 image alone is written, its bytes the odd-integer
+// numerators 2u - L of q_aux(w) (L = 2^aux - 1) instead of +-1; wbits may be NULL; alpha[k] = `alpha_fill`
+// (the caller's 1 / (La * Lw)).
+// In mode 1 alpha is written as 1 (the scaling of that convolution is applied elsewhere).
 __device__ __forceinline__ int qk_level_index(float x, int L)
 {
     // level index u = floor(((x + 1) * 0.5) * L + 0.5) of q_k, x clamped to [-1, 1] (NaN -> -1); every
@@ -35,7 +35,7 @@ __device__ __forceinline__ int qk_level_index(float x, int L)
 template <int MODE>
 __global__ __launch_bounds__(256) void pack_weights_kernel(
     const float *__restrict__ w, uint32_t *__restrict__ wbits, float *__restrict__ alpha,
-    int8_t *__restrict__ wmfma, int k_out, int c, int taps, int cw, int aux, int stage)
+    int8_t *__restrict__ wmfma, int k_out, int c, int taps, int cw, int aux, int stage, float alpha_fill)
 {
     constexpr bool TRANSPOSED = MODE == 1;
     __shared__ float red[256];
@@ -44,22 +44,20 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
     const bool real = k < k_out;
     const size_t n = (size_t)c * taps;
     const int kk = real ? k : 0;
-    const int nfilt = MODE == 2 ? k_out / aux : k_out;      // filters of the tensor w
-    const int plane = MODE == 2 ? kk / nfilt : 0;
-    const int kf = MODE == 2 ? kk - plane * nfilt : kk;
+    const int kf = kk;
     // element (channel ch, tap t) of this filter, read from the tensor in the mode's order
     struct Source {
         const float *base;
         size_t ch_stride;
-        int taps, plane, L;
+        int taps, L;
         __device__ float operator()(int ch, int t) const
         {
-            if (MODE == 2) return ((qk_level_index(base[(size_t)ch * ch_stride + t], L) >> plane) & 1) ? 1.0f : -1.0f;
+            if (MODE == 3) return (float)(2 * qk_level_index(base[(size_t)ch * ch_stride + t], L) - L);
             return TRANSPOSED ? base[(size_t)ch * ch_stride + (taps - 1 - t)] : base[(size_t)ch * ch_stride + t];
         }
     };
     const Source src{TRANSPOSED ? w + (size_t)kf * taps : w + (size_t)kf * n,
-                     TRANSPOSED ? (size_t)k_out * taps : (size_t)taps, taps, plane, (1 << aux) - 1};
+                     TRANSPOSED ? (size_t)k_out * taps : (size_t)taps, taps, (1 << aux) - 1};
     // The four images below each walk the whole filter with a 32-channel stride per thread.  When the
     // filter fits the staging buffer it is first copied to LDS in [channel][tap] order (one coalesced pass
     // in mode 0) and every later access reads LDS; larger filters are read from memory each time.
@@ -79,7 +77,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
     };
     const Filter wk{src, stage ? staged : nullptr, taps};
 
-    if (real) {
+    if (real && wbits) {
         for (int item = tid; item < taps * cw; item += 256) {
             const int t = item / cw, wd = item - t * cw;
             const int nch = min(32, c - wd * 32);
@@ -88,8 +86,10 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
                 word |= (wk(wd * 32 + j, t) >= 0.0f ? 1u : 0u) << j;
             wbits[((size_t)k * taps + t) * cw + wd] = word;
         }
+    }
+    if (real) {
         if (MODE != 0) {
-            if (tid == 0) alpha[k] = 1.0f;
+            if (tid == 0) alpha[k] = MODE == 3 ? alpha_fill : 1.0f;
         } else {
             float s = 0.0f;
             for (size_t i = tid; i < n; i += 256) s += __builtin_fabsf(stage ? staged[i] : src.base[i]);
@@ -113,11 +113,16 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 int8_t s = 0;
-                if (real && ch0 + j < c) s = (wk(ch0 + j, t) >= 0.0f) ? 1 : -1;
+                if (real && ch0 + j < c) s = MODE == 3 ? (int8_t)wk(ch0 + j, t) : (wk(ch0 + j, t) >= 0.0f) ? 1 : -1;
                 u.b[j] = s;
             }
             const size_t rec = ((size_t)fb * taps + t) * cw + wd;
             *reinterpret_cast<uint4 *>(wmfma + rec * 1024 + (size_t)(row + 32 * half) * 16) = u.v;
+        }
+        if (MODE == 3) {        // the int8 image alone: its trailing all-zero record, then done
+            if (k == 0 && tid < 64)
+                *reinterpret_cast<uint4 *>(wmfma + wimg_i8_bytes(k_out, c, taps) - 1024 + (size_t)tid * 16) = make_uint4(0, 0, 0, 0);
+            return;
         }
         int8_t *w4 = wmfma + wimg_i8_bytes(k_out, c, taps);
         const int nblk = taps * cw, nrec = (nblk + 1) / 2;
@@ -159,7 +164,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(
 }
 
 xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
-                                int k_out, int c, int taps, hipStream_t stream, int mode, int aux)
+                                int k_out, int c, int taps, hipStream_t stream, int mode, int aux, float alpha_fill)
 {
     const int cw = (c + 31) / 32;
     const int kpad = (k_out + 31) / 32 * 32;
@@ -167,12 +172,11 @@ xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, v
     const size_t fbytes = (size_t)c * taps * sizeof(float);
     const int stage = fbytes <= 60 * 1024 ? 1 : 0;
     const size_t lds = stage ? fbytes : 0;
-    if (mode == 1)
-        pack_weights_kernel<1><<<grid, block, lds, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, 1, stage);
-    else if (mode == 2)
-        pack_weights_kernel<2><<<grid, block, lds, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, aux, stage);
-    else
-        pack_weights_kernel<0><<<grid, block, lds, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, 1, stage);
+#define XNOR_PACK(M, AUX) pack_weights_kernel<M><<<grid, block, lds, stream>>>(w, wbits, alpha, (int8_t *)wmfma, k_out, c, taps, cw, AUX, stage, alpha_fill)
+    if (mode == 1) XNOR_PACK(1, 1);
+    else if (mode == 3) XNOR_PACK(3, aux);
+    else XNOR_PACK(0, 1);
+#undef XNOR_PACK
     return hip_status(hipGetLastError());
 }
 

@@ -84,15 +84,12 @@ xnor_status launch_pool_binactiv(const float *x, const float *bn_scale, const fl
                                  int sh, int sw, int pad_h, int pad_w, int relu, hipStream_t stream);
 xnor_status launch_boxfilter(const float *A, float *K, const ConvGeom &g, hipStream_t stream);
 xnor_status launch_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
-                                int k_out, int c, int taps, hipStream_t stream, int mode = 0, int aux = 1);
-// (mode 0: sign(W) and alpha; 1: transposed, rotated filters of the backward convolution; 2: bit planes of
-// the aux-bit quantised weights, k_out = planes x filters)
-// k-bit quantisation (kbit.hip): bit planes of q_k(x) packed like xbits, [plane][n][hw][Cw]; combination of
-// the plane-pair dot products
-xnor_status launch_kbit_pack_input(const float *x, uint32_t *planes, int k, int n, int c, int hw, hipStream_t stream);
-xnor_status launch_kbit_combine(const float *dots, float *out, int32_t *num_out, int n, int k_out, int howo,
-                                int ka, int kw, hipStream_t stream);
-xnor_status launch_fill_ones(float *p, size_t count, hipStream_t stream);
+                                int k_out, int c, int taps, hipStream_t stream, int mode = 0, int aux = 1,
+                                float alpha_fill = 1.0f);
+// (mode 0: sign(W) and alpha; 1: transposed, rotated filters of the backward convolution; 3: int8 level
+// numerators of the aux-bit quantised weights, int8 image only, alpha = alpha_fill)
+// k-bit quantisation (kbit.hip): int8 level numerators of q_k(x), [n][hw][Cw][32] (channels innermost)
+xnor_status launch_kbit_pack_input(const float *x, int8_t *xq, int k, int n, int c, int hw, hipStream_t stream);
 // Binary gradient (bingrad.hip): sign words of gd = g * alpha_k * K over the filters + per-image max |gd|;
 // a plane [n][hw] filled with each image's maximum
 xnor_status launch_bingrad_binarize(const float *g, const float *K, const float *alpha, uint32_t *gbits,

@@ -24,7 +24,8 @@ EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor
            "xnor_bwn_conv2d",
            "xnor_bingrad_pack_weights", "xnor_bingrad_binarize", "xnor_bingrad_conv2d",
            "xnor_conv2d_pool",
-           "xnor_kbit_workspace_bytes", "xnor_kbit_pack_input", "xnor_kbit_pack_weights", "xnor_kbit_conv2d"]
+           "xnor_kbit_input_bytes", "xnor_kbit_wimg_bytes", "xnor_kbit_pack_input", "xnor_kbit_pack_weights",
+           "xnor_kbit_conv2d"]
 
 
 class XnorError(RuntimeError):
@@ -96,13 +97,15 @@ def lib():
         L.xnor_bingrad_conv2d.restype = ip
         L.xnor_conv2d_pool.argtypes = [vp] * 6 + [ctypes.POINTER(ConvDesc)] + [ip] * 5 + [vp]
         L.xnor_conv2d_pool.restype = ip
-        L.xnor_kbit_workspace_bytes.argtypes = [ctypes.POINTER(ConvDesc), ip, ip]
-        L.xnor_kbit_workspace_bytes.restype = ctypes.c_size_t
+        L.xnor_kbit_input_bytes.argtypes = [ip, ip, ip, ip]
+        L.xnor_kbit_input_bytes.restype = ctypes.c_size_t
+        L.xnor_kbit_wimg_bytes.argtypes = [ip, ip, ip, ip]
+        L.xnor_kbit_wimg_bytes.restype = ctypes.c_size_t
         L.xnor_kbit_pack_input.argtypes = [vp, vp, ip, ip, ip, ip, ip, vp]
         L.xnor_kbit_pack_input.restype = ip
-        L.xnor_kbit_pack_weights.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, ip, vp]
+        L.xnor_kbit_pack_weights.argtypes = [vp, vp, vp, ip, ip, ip, ip, ip, ip, vp]
         L.xnor_kbit_pack_weights.restype = ip
-        L.xnor_kbit_conv2d.argtypes = [vp] * 7 + [ctypes.POINTER(ConvDesc), ip, ip, ip, vp]
+        L.xnor_kbit_conv2d.argtypes = [vp] * 5 + [ctypes.POINTER(ConvDesc), ip, ip, vp]
         L.xnor_kbit_conv2d.restype = ip
         _lib = L
     return _lib
@@ -234,27 +237,29 @@ def xnor_bingrad_conv2d(gbits, wtbits, wtmfma, gmax, ones, scale_plane, g_in, do
         _ptr(dot_out, torch.int32), ctypes.byref(desc), int(algo), _stream(stream)))
 
 
-def kbit_workspace_bytes(desc, ka, kw_bits):
-    return int(lib().xnor_kbit_workspace_bytes(ctypes.byref(desc), int(ka), int(kw_bits)))
+def kbit_input_bytes(n, c, h, w):
+    return int(lib().xnor_kbit_input_bytes(n, c, h, w))
 
 
-def xnor_kbit_pack_input(x, xplanes, ka, n, c, h, w, stream=None):
+def kbit_wimg_bytes(k_out, c, kh, kw):
+    return int(lib().xnor_kbit_wimg_bytes(k_out, c, kh, kw))
+
+
+def xnor_kbit_pack_input(x, xq, ka, n, c, h, w, stream=None):
     _check("xnor_kbit_pack_input", lib().xnor_kbit_pack_input(
-        _ptr(x, torch.float32), _ptr(xplanes, torch.int32), int(ka), n, c, h, w, _stream(stream)))
+        _ptr(x, torch.float32), _ptr(xq, torch.uint8), int(ka), n, c, h, w, _stream(stream)))
 
 
-def xnor_kbit_pack_weights(w, wbits, ones, wmfma, kw_bits, k_out, c, kh, kw, stream=None):
+def xnor_kbit_pack_weights(w, scale, wq, ka, kw_bits, k_out, c, kh, kw, stream=None):
     _check("xnor_kbit_pack_weights", lib().xnor_kbit_pack_weights(
-        _ptr(w, torch.float32), _ptr(wbits, torch.int32), _ptr(ones, torch.float32), _ptr(wmfma, torch.uint8),
-        int(kw_bits), k_out, c, kh, kw, _stream(stream)))
+        _ptr(w, torch.float32), _ptr(scale, torch.float32), _ptr(wq, torch.uint8), int(ka), int(kw_bits),
+        k_out, c, kh, kw, _stream(stream)))
 
 
-def xnor_kbit_conv2d(xplanes, wbits, wmfma, ones, workspace, out, num_out, desc, ka, kw_bits, algo=XNOR_ALGO_AUTO,
-                     stream=None):
+def xnor_kbit_conv2d(xq, wq, scale, out, num_out, desc, ka, kw_bits, stream=None):
     _check("xnor_kbit_conv2d", lib().xnor_kbit_conv2d(
-        _ptr(xplanes, torch.int32), _ptr(wbits, torch.int32), _ptr(wmfma, torch.uint8), _ptr(ones, torch.float32),
-        _ptr(workspace, torch.uint8), _ptr(out, torch.float32), _ptr(num_out, torch.int32), ctypes.byref(desc),
-        int(ka), int(kw_bits), int(algo), _stream(stream)))
+        _ptr(xq, torch.uint8), _ptr(wq, torch.uint8), _ptr(scale, torch.float32), _ptr(out, torch.float32),
+        _ptr(num_out, torch.int32), ctypes.byref(desc), int(ka), int(kw_bits), _stream(stream)))
 
 
 def xnor_pack_weights(w, wbits, alpha, wmfma, k_out, c, kh, kw, stream=None):

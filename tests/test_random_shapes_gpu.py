@@ -83,16 +83,16 @@ def test_random_shapes_binary_gradient():
 
 def test_random_shapes_kbit():
     from oracle import xnor_oracle as xo
-    from tests.test_kbit_gpu import planes_of, run as run_kbit
+    from tests.test_kbit_gpu import levels_image, run as run_kbit
     rng = np.random.default_rng(77)
     for idx, (n, c, h, w, k_out, kh, kw, stride, pad) in enumerate(SHAPES[1::3]):
         ka, kb = int(rng.integers(1, 5)), int(rng.integers(1, 4))
         print("shape", idx, (n, c, h, w, k_out, kh, kw, stride, pad), "kbit", ka, kb, flush=True)
         x = rng.uniform(-1.1, 1.1, (n, c, h, w)).astype(np.float32)
         wt = rng.uniform(-1, 1, (k_out, c, kh, kw)).astype(np.float32)
-        out, num, xplanes = run_kbit(x, wt, stride, pad, ka, kb, "auto")
+        out, num, xq = run_kbit(x, wt, stride, pad, ka, kb)
         r = xo.kbit_conv2d(x, wt, ka, kb, stride, pad)
-        assert np.array_equal(xplanes, planes_of(xo.qk_levels(x, ka), ka))
+        assert np.array_equal(xq, levels_image(xo.qk_levels(x, ka)))
         assert np.array_equal(num.astype(np.int64), r["num"])
         np.testing.assert_allclose(out, r["out"], rtol=1e-6, atol=0)
 

@@ -110,12 +110,12 @@ def test_graph_replays_of_the_widened_entry_points():
     xnor.xnor_bingrad_pack_weights(wt, wtbits, ones, wtmfma, k, c, 3, 3)
     wimg, alpha_b = u8(xnor.bwn_wimg_bytes(k, c, 3, 3)), f32(k)
     xnor.xnor_bwn_pack_weights(wt, alpha_b, wimg, k, c, 3, 3)
-    wb2, wm2, ones2 = i32(2 * k, 9, cw32), u8(xnor.wmfma_bytes(2 * k, c, 3, 3)), f32(2 * k)
-    xnor.xnor_kbit_pack_weights(torch.tanh(wt * 10), wb2, ones2, wm2, 2, k, c, 3, 3)
+    wq2, scale2 = u8(xnor.kbit_wimg_bytes(k, c, 3, 3)), f32(k)
+    xnor.xnor_kbit_pack_weights(torch.tanh(wt * 10), scale2, wq2, 2, 2, k, c, 3, 3)
     xs = torch.tanh(x)
     out = {"gbits": i32(n, h, w, kw32), "gmax": f32(n), "plane": f32(n, h, w), "gin": f32(n, c, h, w),
            "parts": u8(xnor.bwn_parts_bytes(n, c, h, w)), "bwn": f32(n, k, h, w),
-           "xpl": i32(2, n, h, w, cw32), "ws": u8(xnor.kbit_workspace_bytes(desc, 2, 2)), "kb": f32(n, k, h, w),
+           "xq": u8(xnor.kbit_input_bytes(n, c, h, w)), "kb": f32(n, k, h, w),
            "pool": f32(n, k, 6, 6)}
 
     def sequence():
@@ -123,8 +123,8 @@ def test_graph_replays_of_the_widened_entry_points():
         xnor.xnor_bingrad_conv2d(out["gbits"], wtbits, wtmfma, out["gmax"], ones, out["plane"], out["gin"], None, desc)
         xnor.xnor_bwn_split(x, out["parts"], n, c, h, w)
         xnor.xnor_bwn_conv2d(out["parts"], wimg, alpha_b, out["bwn"], desc)
-        xnor.xnor_kbit_pack_input(xs, out["xpl"], 2, n, c, h, w)
-        xnor.xnor_kbit_conv2d(out["xpl"], wb2, wm2, ones2, out["ws"], out["kb"], None, desc, 2, 2)
+        xnor.xnor_kbit_pack_input(xs, out["xq"], 2, n, c, h, w)
+        xnor.xnor_kbit_conv2d(out["xq"], wq2, scale2, out["kb"], None, desc, 2, 2)
         xnor.xnor_conv2d_pool(bufs.xbits, pw.wmfma, bufs.K, None, pw.alpha, out["pool"], desc, (3, 3), (2, 2))
 
     checked = ("gbits", "gmax", "gin", "bwn", "kb", "pool")
@@ -142,7 +142,7 @@ def test_graph_replays_of_the_widened_entry_points():
         for name in ("gmax", "plane", "gin", "bwn", "kb", "pool"):
             out[name].fill_(777.0)                    # stale contents, e.g. a maximum larger than any |gd|
         out["gbits"].fill_(-1)
-        out["ws"].fill_(255)
+        out["xq"].fill_(255)
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
