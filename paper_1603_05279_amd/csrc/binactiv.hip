@@ -218,31 +218,43 @@ __global__ __launch_bounds__(64 * NW) void binactiv_kernel(
 }
 
 // hw == 1 (fully connected layers): the channels of one image are contiguous, so lanes run along
-// channels and a wave-wide comparison yields 64 sign bits (two packed words) at once.
-__global__ __launch_bounds__(256) void binactiv_vec_kernel(
+// channels and a wave-wide comparison yields 64 sign bits (two packed words) at once.  One workgroup of
+// NWV waves per image (16 for long rows: a batch is a few hundred workgroups, so the loads in flight per
+// CU come from the waves of one workgroup).
+template <int NWV>
+__global__ __launch_bounds__(64 * NWV) void binactiv_vec_kernel(
     const float *__restrict__ x, const float *__restrict__ bn_scale,
     const float *__restrict__ bn_shift, uint32_t *__restrict__ xbits, float *__restrict__ A,
     int c, int cw)
 {
-    __shared__ float part[4];
+    __shared__ float part[NWV];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int img = blockIdx.x;
     const float *xi = x + (size_t)img * c;
     const bool bn = bn_scale != nullptr;
     float asum = 0.0f;
-    for (int base = wave * 64; base < c; base += 256) {
-        const int ch = base + lane;
-        float y = -1.0f;
-        if (ch < c) {
-            y = xi[ch];
-            if (bn) y = __builtin_fmaf(y, bn_scale[ch], bn_shift[ch]);
-            asum += __builtin_fabsf(y);
+    // four 64-channel segments per wave and turn: the loads (clamped, unconditional) are all in flight together
+    for (int base0 = wave * 64; base0 < c; base0 += 256 * NWV) {
+        float v[4], sc[4], sh[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int chc = min(base0 + u * 64 * NWV + lane, c - 1);
+            v[u] = xi[chc];
+            sc[u] = bn ? bn_scale[chc] : 1.0f;
+            sh[u] = bn ? bn_shift[chc] : 0.0f;
         }
-        const unsigned long long mask = __ballot(ch < c && y >= 0.0f);
-        if (xbits) {
-            const int wd = base >> 5;
-            if (lane == 0) xbits[(size_t)img * cw + wd] = (uint32_t)mask;
-            if (lane == 1 && wd + 1 < cw) xbits[(size_t)img * cw + wd + 1] = (uint32_t)(mask >> 32);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int base = base0 + u * 64 * NWV, ch = base + lane;
+            const float y = bn ? __builtin_fmaf(v[u], sc[u], sh[u]) : v[u];
+            const bool ok = ch < c;
+            asum += ok ? __builtin_fabsf(y) : 0.0f;
+            const unsigned long long mask = __ballot(ok && y >= 0.0f);
+            if (xbits && base < c) {
+                const int wd = base >> 5;
+                if (lane == 0) xbits[(size_t)img * cw + wd] = (uint32_t)mask;
+                if (lane == 1 && wd + 1 < cw) xbits[(size_t)img * cw + wd + 1] = (uint32_t)(mask >> 32);
+            }
         }
     }
     if (A) {
@@ -250,7 +262,12 @@ __global__ __launch_bounds__(256) void binactiv_vec_kernel(
         for (int off = 32; off > 0; off >>= 1) asum += __shfl_xor(asum, off, 64);
         if (lane == 0) part[wave] = asum;
         __syncthreads();
-        if (tid == 0) A[img] = (((part[0] + part[1]) + part[2]) + part[3]) / (float)c;
+        if (tid == 0) {
+            float s = part[0];
+#pragma unroll
+            for (int q = 1; q < NWV; ++q) s += part[q];        // fixed order
+            A[img] = s / (float)c;
+        }
     }
 }
 
@@ -321,7 +338,10 @@ xnor_status launch_binactiv(const float *x, const float *bn_scale, const float *
 {
     if (hw == 1) {
         const int cw = (c + 31) / 32;
-        binactiv_vec_kernel<<<dim3((unsigned)n), dim3(256), 0, stream>>>(x, bn_scale, bn_shift, xbits, A, c, cw);
+        if (c >= 4096)
+            binactiv_vec_kernel<16><<<dim3((unsigned)n), dim3(1024), 0, stream>>>(x, bn_scale, bn_shift, xbits, A, c, cw);
+        else
+            binactiv_vec_kernel<4><<<dim3((unsigned)n), dim3(256), 0, stream>>>(x, bn_scale, bn_shift, xbits, A, c, cw);
         return hip_status(hipGetLastError());
     }
     return launch_binactiv_impl<false>(x, bn_scale, bn_shift, xbits, A, n, c, hw, PoolGeom{}, stream);
