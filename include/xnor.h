@@ -15,7 +15,11 @@
  *    The library allocates nothing, frees nothing and keeps no pointer after returning.
  *  - `hip_stream` is a hipStream_t (NULL = the default stream).  All work is enqueued on it
  *    asynchronously; no entry point synchronises.
- *  - Return value: XNOR_OK (0) or a negative xnor_status.  On error nothing was launched.
+ *  - Return value: XNOR_OK (0) or a negative xnor_status.  Arguments are validated before anything is
+ *    launched.  The entry points that enqueue two kernels (xnor_compute_K, xnor_binactiv with K,
+ *    xnor_bingrad_binarize, xnor_bingrad_conv2d, xnor_conv2d_binactiv) may have enqueued the first one
+ *    when the second reports XNOR_ERR_UNSUPPORTED (no kernel fits the shape) or XNOR_ERR_HIP; the first
+ *    kernel writes only that call's own outputs or scratch.
  *  - Real tensors are float32, NCHW, densely packed, row-major:
  *        x   [n][c][h_in][w_in]      w [k_out][c][kh][kw]      out [n][k_out][h_out][w_out]
  *    h_out = (h_in + 2*pad_h - kh)/stride_h + 1 (floor), same for w_out.
@@ -34,6 +38,9 @@
 
 #include <stddef.h>
 #include <stdint.h>
+
+/* Only the functions declared with XNOR_API are exported by the shared library. */
+#define XNOR_API __attribute__((visibility("default")))
 
 #ifdef __cplusplus
 extern "C" {
@@ -66,23 +73,16 @@ typedef struct {
 } xnor_conv_desc;
 
 /* Cw = ceil(c/32): uint32 words per pixel of a packed tensor. */
-int xnor_words_per_pixel(int c);
+XNOR_API int xnor_words_per_pixel(int c);
 
 /* Output extent of the convolution; returns XNOR_ERR_SHAPE if the descriptor is invalid. */
-int xnor_output_hw(const xnor_conv_desc *d, int *h_out, int *w_out);
+XNOR_API int xnor_output_hw(const xnor_conv_desc *d, int *h_out, int *w_out);
 
 /* Static string for a status code. */
-const char *xnor_status_string(int status);
+XNOR_API const char *xnor_status_string(int status);
 
 /* Bytes of the matrix-core weight image written by xnor_pack_weights (0 if the shape is invalid). */
-size_t xnor_wmfma_bytes(int k_out, int c, int kh, int kw);
-
-/*
- * Benchmarking hook (host state, not thread-safe): mfma_tile 1..9 and 11..14 force one workgroup tiling
- * of the matrix-core kernels, 10 the persistent role-split kernel, 0 restores the library's per-shape choice; lds_budget_bytes > 0 caps the
- * LDS image of a workgroup (0 keeps the current cap).  Results never depend on it.
- */
-int xnor_set_tuning(int mfma_tile, int lds_budget_bytes);
+XNOR_API size_t xnor_wmfma_bytes(int k_out, int c, int kh, int kw);
 
 /*
  * sign(I) packed to bits (BinActiv layer, sec. 3.2; sign rule of sec. 3.1).
@@ -91,7 +91,7 @@ int xnor_set_tuning(int mfma_tile, int lds_budget_bytes);
  *   x      in   float32 [n][c][h][w]
  *   xbits  out  uint32  [n][h][w][Cw]
  */
-int xnor_binarize_pack(const float *x, const float *bn_scale, const float *bn_shift,
+XNOR_API int xnor_binarize_pack(const float *x, const float *bn_scale, const float *bn_shift,
                        uint32_t *xbits, int n, int c, int h, int w, void *hip_stream);
 
 /*
@@ -100,7 +100,7 @@ int xnor_binarize_pack(const float *x, const float *bn_scale, const float *bn_sh
  *   A  out  float32 [n][h_in][w_in]      (required: K is computed from it)
  *   K  out  float32 [n][h_out][w_out]
  */
-int xnor_compute_K(const float *x, const float *bn_scale, const float *bn_shift,
+XNOR_API int xnor_compute_K(const float *x, const float *bn_scale, const float *bn_shift,
                    float *A, float *K, const xnor_conv_desc *d, void *hip_stream);
 
 /*
@@ -108,7 +108,7 @@ int xnor_compute_K(const float *x, const float *bn_scale, const float *bn_shift,
  * (bit-identical), reading the float input once.  K may be NULL when the following xnor_conv2d is
  * given A instead: it then derives K itself and the separate box-filter launch is saved.
  */
-int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
+XNOR_API int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
                   uint32_t *xbits, float *A, float *K, const xnor_conv_desc *d, void *hip_stream);
 
 /*
@@ -126,7 +126,7 @@ int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
  *   xbits  out  uint32  [n][h_out][w_out][Cw]
  *   A      out  float32 [n][h_out][w_out]
  */
-int xnor_pool_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
+XNOR_API int xnor_pool_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
                        uint32_t *xbits, float *A, int n, int c, int h_in, int w_in,
                        int pool_h, int pool_w, int stride_h, int stride_w, int pad_h, int pad_w, int relu,
                        void *hip_stream);
@@ -140,7 +140,7 @@ int xnor_pool_binactiv(const float *x, const float *bn_scale, const float *bn_sh
  *   wmfma  out  (nullable) xnor_wmfma_bytes(...) bytes: the same signs laid out for the matrix
  *               cores; required by the XNOR_ALGO_MFMA_* loops, opaque to the caller.
  */
-int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
+XNOR_API int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma,
                       int k_out, int c, int kh, int kw, void *hip_stream);
 
 /*
@@ -158,7 +158,7 @@ int xnor_pack_weights(const float *w, uint32_t *wbits, float *alpha, void *wmfma
  *   dot_out  out  (nullable) int32 same shape: the exact integer map, for verification
  *   algo          an xnor_algo
  */
-int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+XNOR_API int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
                 const float *K, const float *A, const float *alpha, float *out, int32_t *dot_out,
                 const xnor_conv_desc *d, int algo, void *hip_stream);
 
@@ -180,8 +180,8 @@ int xnor_conv2d(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
  *                   filter tiles), contents undefined afterwards; may be NULL when that size is 0
  *   algo            XNOR_ALGO_AUTO, XNOR_ALGO_MFMA_I8 or XNOR_ALGO_MFMA_F4 (XNOR_ERR_UNSUPPORTED otherwise)
  */
-size_t xnor_conv2d_binactiv_workspace_bytes(const xnor_conv_desc *d);
-int xnor_conv2d_binactiv(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+XNOR_API size_t xnor_conv2d_binactiv_workspace_bytes(const xnor_conv_desc *d);
+XNOR_API int xnor_conv2d_binactiv(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
                          const float *K, const float *A, const float *alpha,
                          const float *bn_scale_next, const float *bn_shift_next,
                          uint32_t *xbits_next, float *A_next, float *out, void *workspace,
@@ -198,7 +198,7 @@ int xnor_conv2d_binactiv(const uint32_t *xbits, const uint32_t *wbits, const voi
  * out_pool float32 [n][k_out][h_pool][w_pool].  XNOR_ERR_UNSUPPORTED when the convolution rows under one
  * pooled row (pool_h rows of w_out pixels) exceed the largest pixel tile (192 pixels), or c*kh*kw >= 2^24.
  */
-int xnor_conv2d_pool(const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
+XNOR_API int xnor_conv2d_pool(const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
                      const float *alpha, float *out_pool, const xnor_conv_desc *d,
                      int pool_h, int pool_w, int pstride_h, int pstride_w, int relu, void *hip_stream);
 
@@ -218,12 +218,12 @@ int xnor_conv2d_pool(const uint32_t *xbits, const void *wmfma, const float *K, c
  * Differences between this result and one accumulated in double stay within float rounding of the
  * running sums (about 1e-7 * sqrt(c*kh*kw) of the magnitude of the terms).
  */
-size_t xnor_bwn_parts_bytes(int n, int c, int h, int w);
-size_t xnor_bwn_wimg_bytes(int k_out, int c, int kh, int kw);
-int xnor_bwn_split(const float *x, void *parts, int n, int c, int h, int w, void *hip_stream);
-int xnor_bwn_pack_weights(const float *w, float *alpha, void *wimg, int k_out, int c, int kh, int kw,
+XNOR_API size_t xnor_bwn_parts_bytes(int n, int c, int h, int w);
+XNOR_API size_t xnor_bwn_wimg_bytes(int k_out, int c, int kh, int kw);
+XNOR_API int xnor_bwn_split(const float *x, void *parts, int n, int c, int h, int w, void *hip_stream);
+XNOR_API int xnor_bwn_pack_weights(const float *w, float *alpha, void *wimg, int k_out, int c, int kh, int kw,
                           void *hip_stream);
-int xnor_bwn_conv2d(const void *parts, const void *wimg, const float *alpha, float *out,
+XNOR_API int xnor_bwn_conv2d(const void *parts, const void *wimg, const float *alpha, float *out,
                     const xnor_conv_desc *d, void *hip_stream);
 
 /*
@@ -252,18 +252,20 @@ int xnor_bwn_conv2d(const void *parts, const void *wimg, const float *alpha, flo
  * The straight-through factor of sign() on the forward input and the gradient through K are not part of
  * these calls.
  */
-int xnor_bingrad_pack_weights(const float *w, uint32_t *wtbits, float *ones, void *wtmfma,
+XNOR_API int xnor_bingrad_pack_weights(const float *w, uint32_t *wtbits, float *ones, void *wtmfma,
                               int k_out, int c, int kh, int kw, void *hip_stream);
-int xnor_bingrad_binarize(const float *g_out, const float *K, const float *alpha, uint32_t *gbits,
+XNOR_API int xnor_bingrad_binarize(const float *g_out, const float *K, const float *alpha, uint32_t *gbits,
                           float *gmax, const xnor_conv_desc *d, void *hip_stream);
-int xnor_bingrad_conv2d(const uint32_t *gbits, const uint32_t *wtbits, const void *wtmfma,
+XNOR_API int xnor_bingrad_conv2d(const uint32_t *gbits, const uint32_t *wtbits, const void *wtmfma,
                         const float *gmax, const float *ones, float *scale_plane, float *g_in,
                         int32_t *dot_out, const xnor_conv_desc *d, int algo, void *hip_stream);
 
 /*
  * k-bit quantisation (sec. 3.2, paragraph "k-bit Quantization"): q_k(x) = 2*([(2^k-1)(x+1)/2]/(2^k-1) - 1/2) in
  * place of sign(), x in [-1, 1] (values outside are clamped, NaN counts as -1; halves round up, so q_1 = sign
- * with sign(0) = +1; the level is decided in float32 as u = floor(((x + 1) * 0.5) * (2^k - 1) + 0.5)).
+ * with sign(0) = +1; the level is decided in float32 as u = floor(((x + 1) * 0.5) * (2^k - 1) + 0.5), except
+ * k = 1, which is decided by the comparison x >= 0 so that q_1 is the sign rule for every float, also for
+ * -2^-25 < x < 0 where x + 1 rounds to 1).
  * q_k = (2u - L)/L with L = 2^k - 1, so the convolution of ka-bit inputs with kw-bit weights is an exact integer
  * sum of numerator products divided by La * Lw; it runs on the int8 matrix cores:
  *   out[n][k_out][h_out][w_out] = sum q_ka(x) * q_kw(w) over the in-bounds window, no K, no alpha.
@@ -278,12 +280,12 @@ int xnor_bingrad_conv2d(const uint32_t *gbits, const uint32_t *wtbits, const voi
  *                           2e-7 relative of num / (La * Lw)).  XNOR_ERR_UNSUPPORTED when La * Lw * c * kh * kw
  *                           does not fit 31 bits.
  */
-size_t xnor_kbit_input_bytes(int n, int c, int h, int w);
-size_t xnor_kbit_wimg_bytes(int k_out, int c, int kh, int kw);
-int xnor_kbit_pack_input(const float *x, void *xq, int ka, int n, int c, int h, int w, void *hip_stream);
-int xnor_kbit_pack_weights(const float *w, float *scale, void *wq, int ka, int kw_bits,
+XNOR_API size_t xnor_kbit_input_bytes(int n, int c, int h, int w);
+XNOR_API size_t xnor_kbit_wimg_bytes(int k_out, int c, int kh, int kw);
+XNOR_API int xnor_kbit_pack_input(const float *x, void *xq, int ka, int n, int c, int h, int w, void *hip_stream);
+XNOR_API int xnor_kbit_pack_weights(const float *w, float *scale, void *wq, int ka, int kw_bits,
                            int k_out, int c, int kh, int kw, void *hip_stream);
-int xnor_kbit_conv2d(const void *xq, const void *wq, const float *scale, float *out, int32_t *num_out,
+XNOR_API int xnor_kbit_conv2d(const void *xq, const void *wq, const float *scale, float *out, int32_t *num_out,
                      const xnor_conv_desc *d, int ka, int kw_bits, void *hip_stream);
 
 /*
@@ -293,7 +295,7 @@ int xnor_kbit_conv2d(const void *xq, const void *wq, const float *scale, float *
  *   alpha [out_features], out / dot_out [batch][out_features]
  *   wmfma as in xnor_conv2d, packed with (k_out = out_features, c = in_features, 1, 1).
  */
-int xnor_linear(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+XNOR_API int xnor_linear(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
                 const float *Krow, const float *alpha, float *out, int32_t *dot_out,
                 int batch, int in_features, int out_features, int algo, void *hip_stream);
 

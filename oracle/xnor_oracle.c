@@ -272,7 +272,10 @@ void xo_bingrad(const float *g, const float *K, const float *alpha, const int8_t
  * q_k = (2u - L)/L: the odd integer a = 2u - L in [-L, L] over L.  Readings: inputs outside [-1, 1] are
  * clamped (NaN -> -1); [.] rounds halves up (u = floor(v + 1/2)), so that q_1 = sign with sign(0) = +1;
  * the level index is decided in float arithmetic in this order of operations, each rounded to float:
- * v = ((x + 1) * 0.5) * L + 0.5, u = floor(v), clamped to 0..L.  k in 1..8. */
+ * v = ((x + 1) * 0.5) * L + 0.5, u = floor(v), clamped to 0..L.  k in 1..8.
+ * k = 1 is decided by the comparison x >= 0 instead: the formula evaluated exactly gives -1 for every
+ * negative x, but in float x + 1 rounds to 1 for -2^-25 < x < 0 and would give +1; with the comparison
+ * q_1 is the sign function of sec. 3.1 for every float. */
 void xo_qk_levels(const float *x, int32_t *a, size_t count, int k)
 {
     const int L = (1 << k) - 1;
@@ -284,6 +287,7 @@ void xo_qk_levels(const float *x, int32_t *a, size_t count, int k)
         const float v = h * (float)L + 0.5f;
         int u = (int)floorf(v);
         u = u < 0 ? 0 : (u > L ? L : u);
+        if (k == 1) u = x[i] >= 0.0f ? 1 : 0;
         a[i] = 2 * u - L;
     }
 }

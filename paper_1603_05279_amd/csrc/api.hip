@@ -367,6 +367,13 @@ int xnor_bingrad_conv2d(const uint32_t *gbits, const uint32_t *wtbits, const voi
     g.real_h = fwd.ho; g.real_w = fwd.wo;
     g.div_dil_h = FastDiv::make((uint32_t)fwd.sh);
     g.div_dil_w = FastDiv::make((uint32_t)fwd.sw);
+    // what conv_dispatch would refuse for this algo, before the first launch touches scale_plane
+    const bool dilated = g.dil_h > 1 || g.dil_w > 1;
+    if (algo != XNOR_ALGO_AUTO && algo != XNOR_ALGO_POPCOUNT && algo != XNOR_ALGO_MFMA_I8 && algo != XNOR_ALGO_MFMA_F4)
+        return XNOR_ERR_UNSUPPORTED;
+    if (algo == XNOR_ALGO_POPCOUNT && dilated) return XNOR_ERR_UNSUPPORTED;
+    if ((algo == XNOR_ALGO_MFMA_I8 || algo == XNOR_ALGO_MFMA_F4) && !wtmfma) return XNOR_ERR_NULL;
+    if (algo == XNOR_ALGO_AUTO && dilated && !wtmfma) return XNOR_ERR_UNSUPPORTED;
     hipStream_t st = (hipStream_t)hip_stream;
     if (xnor_status s = launch_bingrad_scale_plane(gmax, scale_plane, fwd.n, fwd.h * fwd.w, st)) return s;
     return conv_dispatch(g, gbits, wtbits, wtmfma, scale_plane, nullptr, ones, g_in, dot_out, algo, st);

@@ -1,6 +1,7 @@
 // BinActiv layer (sec. 3.2): sign(I) packed to bits, A = channel mean of |I|, K = box filter of A.
 // Optional batch normalisation folded in front (block order BatchNorm -> BinActiv).
 #include "xnor_internal.h"
+#include <atomic>
 #include <algorithm>
 
 namespace xnor {
@@ -278,12 +279,12 @@ static xnor_status launch_binactiv_one(dim3 grid, size_t lds, hipStream_t stream
 {
     auto kern = binactiv_kernel<WB, WA, BN, POOL, NW, PH, PW>;
     if (lds > 48 * 1024) {      // the pooled form's staging buffer can pass the default dynamic LDS limit
-        static bool attr_done = false;
-        if (!attr_done) {
+        static std::atomic<bool> attr_done;      // false -> true only; a repeated attribute call is harmless
+        if (!attr_done.load(std::memory_order_acquire)) {
             if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
                                     160 * 1024) != hipSuccess)
                 return XNOR_ERR_HIP;
-            attr_done = true;
+            attr_done.store(true, std::memory_order_release);
         }
     }
     kern<<<grid, dim3(64 * NW), lds, stream>>>(x, bn_scale, bn_shift, xbits, A, c, hw, cw, tiles, blocks, pg);

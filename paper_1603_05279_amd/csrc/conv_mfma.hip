@@ -18,21 +18,10 @@
 // filter plane are contiguous across lanes.
 #include "mfma_common.h"
 #include <algorithm>
+#include <atomic>
 #include <type_traits>
 
 namespace xnor {
-
-#ifdef XNOR_TIMELINE
-// Development build only: per-workgroup phase timestamps (100 MHz wall clock) into a caller buffer.
-__device__ long long *g_timeline = nullptr;
-#define XNOR_TL(slot)                                                                         \
-    do {                                                                                      \
-        if (threadIdx.x == 0 && g_timeline)                                                   \
-            g_timeline[((size_t)blockIdx.y * gridDim.x + blockIdx.x) * 8 + (slot)] = wall_clock64(); \
-    } while (0)
-#else
-#define XNOR_TL(slot) do { } while (0)
-#endif
 
 // Accumulator tiles of up to 8 result blocks leave room for two waves per SIMD (256 registers each).
 template <int FMT, int FW, int PW, int WF, int WP, bool FUSE, bool LINEAR, bool POOL = false>
@@ -84,7 +73,6 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         ftile = blockIdx.y;
         if (ptile >= (uint32_t)pl.ptiles) return;
     }
-    XNOR_TL(0);
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int l32 = lane & 31, half = lane >> 5;
@@ -135,26 +123,23 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         const uint32_t img = pl.div_hp.div(R);
         const int y = (int)(R - img * g.hp) - g.ph;
         // first pixel of the (real) input row, -1 for padding rows and the zero rows of a dilated input
-        const uint32_t ry = g.div_dil_h.div((uint32_t)max(y, 0));
+        const uint32_t ry = g.div_dil_h.div_small((uint32_t)max(y, 0));
         const bool rv = y >= 0 && y < g.h && (int)ry * g.dil_h == y && (int)ry < g.real_h;
         rowinfo[rr] = rv ? (int)((img * g.real_h + ry) * g.real_w) : -1;
     }
-    XNOR_TL(5);
     // LDS offset of every channel block of a chunk relative to a pixel's window origin:
     // block b = tap * ccw + word  ->  (dy*wp + dx)*ps + word*BPB
     {
         const int nblk = g.taps * ccw;
         for (int b = tid; b < (nsteps + KLOOP_TABLE_PAD) * E::BPS; b += NT) {     // padding repeats the last block
             const uint32_t bb = (uint32_t)min(b, nblk - 1);
-            const uint32_t t = pl.div_ccw.div(bb);
+            const uint32_t t = pl.div_ccw.div_small(bb);
             const uint32_t wl = bb - t * ccw;
-            const uint32_t dy = g.div_kw.div(t);
+            const uint32_t dy = g.div_kw.div_small(t);
             const uint32_t dx = t - dy * g.kw;
             xoff_tab[b] = (int)(dy * pl.row_pitch + dx * pl.ps + wl * E::BPB);
         }
     }
-
-    XNOR_TL(6);
     // LDS byte offset of each of this lane's pixel columns (window origin in the padded frame)
     int pbase[PW];
 #pragma unroll
@@ -189,12 +174,9 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         for (int j = 0; j < PW; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
-
-    XNOR_TL(7);
     const int steps_per_tap = pl.tap_jump ? ccw / E::BPS : 0x7fffffff;
     for (int wbase = 0; wbase < g.cw; wbase += ccw) {
         __syncthreads();   // tables visible / previous chunk fully consumed
-        if (wbase == 0) XNOR_TL(1);
         const int items = nrows * g.wp * ccw;
         constexpr int FB = 4;                  // items in flight per thread: loads first, then widening
         for (int it0 = tid; it0 < items; it0 += NT * FB) {
@@ -206,11 +188,11 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
             for (int u = 0; u < FB; ++u) {
                 const int it = it0 + u * NT;
                 const uint32_t itc = (uint32_t)min(it, items - 1);
-                const uint32_t px = pl.div_ccw.div(itc);
+                const uint32_t px = pl.div_ccw.div_small(itc);
                 const int wl = (int)(itc - px * ccw);
-                const uint32_t rr = pl.div_wp.div(px);
+                const uint32_t rr = pl.div_wp.div_small(px);
                 const int xv = (int)(px - rr * g.wp) - g.pw;                 // column of the (virtual) input
-                const int xcol = (int)g.div_dil_w.div((uint32_t)max(xv, 0));  // column of the real tensor
+                const int xcol = (int)g.div_dil_w.div_small((uint32_t)max(xv, 0));  // column of the real tensor
                 const int rowbase = rowinfo[rr];
                 ok[u] = rowbase >= 0 && xv >= 0 && xv < g.w && xcol * g.dil_w == xv && xcol < g.real_w;
                 dst[u] = it < items ? (int)(rr * pl.row_pitch + (px - rr * g.wp) * pl.ps + wl * E::BPB) : -1;
@@ -242,7 +224,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         if (!RAW && wbase == 0 && !K) {
             // stage the matrix A of the same input rows (0 in the halo) for the K of this tile
             for (int it = tid; it < nrows * g.wp; it += NT) {
-                const uint32_t rr = pl.div_wp.div((uint32_t)it);
+                const uint32_t rr = pl.div_wp.div_small((uint32_t)it);
                 const int xcol = it - (int)rr * g.wp - g.pw;
                 const int rowbase = rowinfo[rr];
                 const bool ok = rowbase >= 0 && xcol >= 0 && xcol < g.w;
@@ -250,7 +232,6 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
             }
         }
         __syncthreads();
-        if (wbase == 0) XNOR_TL(2);
         if (!RAW && wbase == 0 && !K) for (int kt = tid; kt < PT; kt += NT) {
             // K of output pixel m0 + tid: the kh x kw taps of A in row-major order over the staged
             // rows (halo entries add +0.0f, the same bits as skipping them), divided by kh*kw
@@ -281,8 +262,6 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
             mfma_kloop<E, FW, PW, DW, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps);
         }
     }
-
-    XNOR_TL(3);
     // epilogue: out = float(dot) * K * alpha; result register v of a lane is filter row
     // 8*(v/4) + 4*half + v%4 of the 32-filter block, pixel column l32.  alpha of the lane's
     // filter rows is fetched once (clamped index, no branch), stores are predicated.
@@ -404,7 +383,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
             const int row0 = f0 + (wf * FW + i) * 32 + 16 * hq;
             const int nrow = min(16, g.k_out - row0);       // staged filters that exist (wave-uniform, may be <= 0)
             for (int q = pq; q < npool; q += pstep) {
-                const uint32_t py = pp.div_wpo.div((uint32_t)q);
+                const uint32_t py = pp.div_wpo.div_small((uint32_t)q);
                 const int px = q - (int)py * pp.wpo;
                 const float *win = ystage + (int)py * pp.sh * g.wo + px * pp.sw;
                 float *dst = pooled + ((size_t)pool_img * g.k_out + row0 + fo) * plane + (size_t)pool_py0 * pp.wpo + q;
@@ -531,15 +510,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         else fz.workspace[(size_t)ftile * g.m_total + m] = sum;
     }
     }
-    XNOR_TL(4);
 }
-
-#ifdef XNOR_TIMELINE
-extern "C" int xnor_debug_timeline(long long *buf)
-{
-    return hipMemcpyToSymbol(HIP_SYMBOL(g_timeline), &buf, sizeof(buf)) == hipSuccess ? 0 : -5;
-}
-#endif
 
 static const int LDS_LIMIT = 160 * 1024;
 
@@ -604,12 +575,24 @@ static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fu
     return false;
 }
 
-static int g_tile_override = 0;
-static int g_lds_budget = 64 * 1024;
+static std::atomic<int> g_tile_override{0};
+static std::atomic<int> g_lds_budget{64 * 1024};
 void set_mfma_tuning(int tile, int lds_budget)
 {
-    g_tile_override = tile;
-    if (lds_budget > 0) g_lds_budget = lds_budget;
+    g_tile_override.store(tile, std::memory_order_relaxed);
+    if (lds_budget > 0) g_lds_budget.store(lds_budget, std::memory_order_relaxed);
+}
+
+// Raises a kernel's dynamic LDS limit once per instantiation (the library drives one GPU per process).  Concurrent first calls may both
+// set the attribute (the call is idempotent); the flag only ever goes from false to true.
+template <class Kern> static xnor_status allow_full_lds(Kern kern, std::atomic<bool> &done)
+{
+    if (done.load(std::memory_order_acquire)) return XNOR_OK;
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            LDS_LIMIT) != hipSuccess)
+        return XNOR_ERR_HIP;
+    done.store(true, std::memory_order_release);
+    return XNOR_OK;
 }
 
 // second kernel of the fused epilogue when the filters span several workgroups:
@@ -635,7 +618,7 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     if ((PT / howo + 2) * g.k_out * howo * 4 >= 0x7ffffff0LL) return XNOR_ERR_UNSUPPORTED;
     MfmaPlan pl;
     constexpr int FROWS = FUSE ? WF + FT / 32 : 0, PARB = (FUSE ? 3 : 1) * FT * 4;
-    if (!make_plan(g, PT, FMT, g_lds_budget, FROWS, PARB, &pl)) return XNOR_ERR_UNSUPPORTED;
+    if (!make_plan(g, PT, FMT, g_lds_budget.load(std::memory_order_relaxed), FROWS, PARB, &pl)) return XNOR_ERR_UNSUPPORTED;
     const size_t lds = plan_lds_bytes(pl, FMT, g.wp, PT, FROWS, PARB);
     pl.lut_offset = plan_lut_offset(pl, FMT, g.wp, PT, FROWS, PARB);
     // two builds of every tiling: weight records consecutive (one chunk holds all channel words) or not
@@ -643,13 +626,8 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     const bool linear = pl.tap_jump == 0 || g.taps == 1;
     auto kern = linear ? conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, true>
                        : conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, false>;
-    static bool attr_done[2] = {false, false};   // per instantiation
-    if (!attr_done[linear]) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT) != hipSuccess)
-            return XNOR_ERR_HIP;
-        attr_done[linear] = true;
-    }
+    static std::atomic<bool> attr_done[2];       // per instantiation (zero-initialised: false)
+    if (xnor_status s = allow_full_lds(kern, attr_done[linear])) return s;
     pl.ptiles = (g.m_total + PT - 1) / PT;
     pl.ftiles = (g.k_out + FT - 1) / FT;
     // weight-heavy: the weight image outweighs the packed activations and there are filter tiles to spread
@@ -686,7 +664,7 @@ static xnor_status launch_cfg_pool(const uint32_t *xbits, const void *wimg, cons
     MfmaPlan pl;
     const int conv_rows = (pool.pr - 1) * pool.sh + pool.ph;          // convolution rows under a tile
     if (conv_rows * g.wo > PT) return XNOR_ERR_UNSUPPORTED;
-    if (!make_plan(g, PT, 1, g_lds_budget, 0, FT * 4, &pl, (conv_rows - 1) * g.sh + g.kh)) return XNOR_ERR_UNSUPPORTED;
+    if (!make_plan(g, PT, 1, g_lds_budget.load(std::memory_order_relaxed), 0, FT * 4, &pl, (conv_rows - 1) * g.sh + g.kh)) return XNOR_ERR_UNSUPPORTED;
     size_t lds = plan_lds_bytes(pl, 1, g.wp, PT, 0, FT * 4);
     pl.lut_offset = plan_lut_offset(pl, 1, g.wp, PT, 0, FT * 4);
     lds = std::max(lds, (size_t)WAVES * 16 * (PT + 1) * sizeof(float));       // the epilogue's per-wave y tiles
@@ -694,13 +672,8 @@ static xnor_status launch_cfg_pool(const uint32_t *xbits, const void *wimg, cons
     const bool linear = pl.tap_jump == 0 || g.taps == 1;
     auto kern = linear ? conv_mfma_kernel<1, FW, PW, WF, WP, false, true, true>
                        : conv_mfma_kernel<1, FW, PW, WF, WP, false, false, true>;
-    static bool attr_done[2] = {false, false};
-    if (!attr_done[linear]) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, LDS_LIMIT) != hipSuccess)
-            return XNOR_ERR_HIP;
-        attr_done[linear] = true;
-    }
+    static std::atomic<bool> attr_done[2];
+    if (xnor_status s = allow_full_lds(kern, attr_done[linear])) return s;
     const long long ptiles = (long long)g.n * pool.groups;
     if (ptiles > 0x7fffffffLL) return XNOR_ERR_UNSUPPORTED;
     pl.ptiles = (int)ptiles;
@@ -760,8 +733,8 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
                               const float *alpha, float *out, int32_t *dot_out, const ConvGeom &g,
                               hipStream_t stream, const FuseArgs *fz)
 {
-    int tile = g_tile_override;
-    if (tile == 0 || tile == 10) {
+    int tile = g_tile_override.load(std::memory_order_relaxed);
+    if (tile == 0) {
         // Measured rules (fp4, all benchmark layers).  Up to 64 filters: 64 x 256 when that still gives every
         // CU two workgroups, else 64 x 128; up to 128 filters: 128 x 64, else 64 x 128 (fused epilogue:
         // 64 x 256 or 128 x 128, so that one workgroup holds every filter).  129..256 filters: a tile that
@@ -839,10 +812,6 @@ xnor_status launch_conv_mfma(int fmt, const uint32_t *xbits, const void *wmfma, 
                              const float *alpha, float *out, int32_t *dot_out,
                              const ConvGeom &g, hipStream_t stream, const FuseArgs *fz)
 {
-    if (g_tile_override == 10 && !fz && fmt < 2 && g.dil_h == 1 && g.dil_w == 1) {      // persistent kernel where its LDS plan fits, tiled kernel otherwise
-        const xnor_status s = launch_conv_mfma_pipe(fmt, xbits, wmfma, K, A, alpha, out, dot_out, g, stream);
-        if (s != XNOR_ERR_UNSUPPORTED) return s;
-    }
     const uint8_t *img = static_cast<const uint8_t *>(wmfma);
     // fmt 2: real activations in bfloat16 parts (xbits = 32-byte words, g.c = 32 x words per pixel,
     // wmfma = the +-1 bfloat16 record image alone); no K, no fused epilogue

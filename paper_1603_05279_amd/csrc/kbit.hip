@@ -16,6 +16,8 @@ __device__ __forceinline__ int qk_level(float x, int L)
     float t = x >= -1.0f ? x : -1.0f;
     t = t <= 1.0f ? t : 1.0f;
     const float v = ((t + 1.0f) * 0.5f) * (float)L + 0.5f;
+    // one bit: the comparison of the sign rule (x + 1 rounds to 1 for -2^-25 < x < 0, which would give +1)
+    if (L == 1) return x >= 0.0f ? 1 : 0;
     return min(max((int)__builtin_floorf(v), 0), L);
 }
 

@@ -29,6 +29,7 @@ __device__ __forceinline__ int qk_level_index(float x, int L)
     float t = x >= -1.0f ? x : -1.0f;
     t = t <= 1.0f ? t : 1.0f;
     const float v = ((t + 1.0f) * 0.5f) * (float)L + 0.5f;
+    if (L == 1) return x >= 0.0f ? 1 : 0;      // one bit: the sign rule's comparison, for every float
     return min(max((int)__builtin_floorf(v), 0), L);
 }
 

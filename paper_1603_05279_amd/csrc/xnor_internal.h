@@ -3,23 +3,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "xnor.h"
+#include "xnor_tuning.h"
+#include "fastdiv.h"
 
 namespace xnor {
-
-// Exact unsigned division by a run-time constant: q = floor(x / d) for x*d < 2^32, branch-free:
-// q = mulhi(x, magic) + (x & pass) with magic = floor(2^32 / d) + 1, pass = 0 for d > 1 and
-// magic = 0, pass = ~0 for d == 1.
-struct FastDiv {
-    uint32_t magic;
-    uint32_t pass;
-    __host__ static FastDiv make(uint32_t d) {
-        FastDiv f;
-        f.magic = (d <= 1) ? 0u : (uint32_t)((0x100000000ull / d) + 1ull);
-        f.pass = (d <= 1) ? 0xFFFFFFFFu : 0u;
-        return f;
-    }
-    __device__ __forceinline__ uint32_t div(uint32_t x) const { return __umulhi(x, magic) + (x & pass); }
-};
 
 // Geometry handed to the convolution kernels (derived from xnor_conv_desc on the host).
 struct ConvGeom {
@@ -134,11 +121,6 @@ void set_mfma_tuning(int tile, int lds_budget);
 // Binary-Weight-Network preparation kernels (bwn.hip); the convolution itself is launch_conv_mfma with fmt 2
 xnor_status launch_bwn_split(const float *x, void *parts, int n, int c, int hw, hipStream_t stream);
 xnor_status launch_bwn_pack(const float *w, float *alpha, void *wimg, int k_out, int c, int taps, hipStream_t stream);
-// persistent, role-split form of the same kernel (conv_mfma_pipe.hip)
-xnor_status launch_conv_mfma_pipe(int fmt, const uint32_t *xbits, const void *wmfma, const float *K,
-                                  const float *A, const float *alpha, float *out, int32_t *dot_out,
-                                  const ConvGeom &g, hipStream_t stream);
-
 // Sizes of the two matrix-core weight images (int8 first, 4-bit float second), 1 KiB records;
 // each image ends with one all-zero record that padded K-steps multiply by.
 __host__ __device__ inline size_t wimg_i8_bytes(int k_out, int c, int taps)

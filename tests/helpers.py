@@ -31,10 +31,6 @@ def to_dev(a, dtype=None):
 
 def gpu_conv_block(x, w, stride, pad, bn_scale=None, bn_shift=None, algo="auto", fused=True):
     """Runs pack_weights + BinActiv + BinConv through the C ABI; returns numpy results."""
-    pipe = algo.endswith("_pipe")        # persistent role-split kernel instead of the tiled one
-    if pipe:
-        algo = algo[:-5]
-    xnor.set_tuning(10 if pipe else 0)
     n, c, h, wd = x.shape
     k_out, _, kh, kw = w.shape
     desc = xnor.make_desc(n, c, h, wd, k_out, kh, kw, stride, pad)
@@ -56,7 +52,6 @@ def gpu_conv_block(x, w, stride, pad, bn_scale=None, bn_shift=None, algo="auto",
         xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, None, pw.alpha, bufs.out, bufs.dot, desc,
                          xnor.ALGOS[algo])
     torch.cuda.synchronize()
-    xnor.set_tuning(0)
     return {
         "xbits": bufs.xbits.cpu().numpy().view(np.uint32),
         "wbits": pw.wbits.cpu().numpy().view(np.uint32),

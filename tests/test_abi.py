@@ -1,8 +1,10 @@
 """The C-ABI library loads, exports every function include/xnor.h declares, and turns invalid
 arguments into error codes before anything is launched (no GPU needed)."""
 import ctypes
+import glob
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -12,9 +14,11 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "xnor.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(xnor_[a-zA-Z0-9_]+)\s*\(", text)))
+    names = set()
+    for header in sorted(glob.glob(os.path.join(ROOT, "include", "*.h"))):
+        text = re.sub(r"/\*.*?\*/", "", open(header).read(), flags=re.S)
+        names |= set(re.findall(r"\b(xnor_[a-zA-Z0-9_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_library_exports_every_declared_function():
@@ -23,6 +27,14 @@ def test_library_exports_every_declared_function():
     L = xnor.lib()
     for name in names:
         assert getattr(L, name) is not None
+
+
+def test_library_exports_nothing_but_the_c_abi():
+    """Hidden visibility: the dynamic symbol table defines the declared xnor_* functions and no internal one."""
+    out = subprocess.run(["nm", "-D", "--defined-only", xnor._LIB_PATH], capture_output=True, text=True, check=True)
+    defined = {line.split()[-1] for line in out.stdout.splitlines() if line.split()[1:2] and line.split()[-2] in "TWtwV"}
+    ours = {s for s in defined if "xnor" in s}
+    assert ours == set(declared_functions()), ours ^ set(declared_functions())
 
 
 def test_small_queries():

@@ -438,6 +438,12 @@ def test_q1_is_sign_and_levels_are_uniform_and_clamped():
     x = rng.uniform(-1, 1, 1000).astype(np.float32)
     x[:4] = [0.0, -0.0, 1.0, -1.0]
     assert np.array_equal(xo.qk_levels(x, 1), xo.sign(x).astype(np.int32))       # k = 1: the sign function, sign(0) = +1
+    # negative inputs so small that x + 1 rounds to 1 in float: the formula evaluated exactly gives -1
+    tiny = np.array([-1e-9, -2.0 ** -26, -np.finfo(np.float32).tiny, 1e-9], np.float32)
+    assert xo.qk_levels(tiny, 1).tolist() == [-1, -1, -1, 1]
+    for v in tiny[:3]:
+        u = (Fraction(float(v)) + 1) / 2 + Fraction(1, 2)            # [(2^1 - 1)(x + 1)/2] with halves up
+        assert 2 * int(u.numerator // u.denominator) - 1 == -1
     for k in (2, 3, 8):
         L = (1 << k) - 1
         a = xo.qk_levels(x, k)

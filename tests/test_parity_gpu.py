@@ -10,7 +10,7 @@ from tests.helpers import RTOL, ATOL, assert_block_matches_oracle, gpu_conv_bloc
 
 pytestmark = pytest.mark.gpu
 
-ALGOS = ["popcount", "mfma_i8", "mfma_f4", "mfma_i8_pipe", "mfma_f4_pipe"]
+ALGOS = ["popcount", "mfma_i8", "mfma_f4"]
 
 # n, c, h, w, k_out, kh, kw, stride, pad — several tiles, ragged tails, odd channel counts
 SMALL = [
@@ -44,6 +44,19 @@ def test_config_tiny_full(algo):
     d = wl.conv_inputs(layer, wl.config_seed("tiny"))
     g = gpu_conv_block(d["x"], d["w"], (1, 1), (1, 1), algo=algo)
     assert_block_matches_oracle(g, d["x"], d["w"], (1, 1), (1, 1))
+
+
+@pytest.mark.parametrize("algo", ALGOS)
+def test_pixel_index_times_plane_size_beyond_32_bits(algo):
+    """260 images of 64 x 64 output pixels: from image 257 on, (flattened pixel index) x (plane size) passes
+    2^32, where a multiply-high division without its correction step names the wrong image."""
+    n, c, hw, k_out = 260, 32, 64, 32
+    x, wt = wl.random_conv_case(260, n, c, hw, hw, k_out, 3, 3)
+    print("large pixel index", algo, flush=True)
+    g = gpu_conv_block(x, wt, (1, 1), (1, 1), algo=algo)
+    assert_block_matches_oracle(g, x, wt, (1, 1), (1, 1))
+    g = gpu_conv_block(x, wt, (1, 1), (1, 1), algo=algo, fused=False)     # K from the stand-alone box filter
+    assert_block_matches_oracle(g, x, wt, (1, 1), (1, 1))
 
 
 def test_unfused_entry_points_give_identical_bits_and_K():
@@ -104,12 +117,9 @@ def test_linear_matches_oracle(algo):
     xnor.xnor_binactiv(xd.reshape(b, f, 1, 1), None, None, bufs.xbits, bufs.A, bufs.K, desc)
     out = torch.full((b, o), float("nan"), device="cuda")
     dot = torch.zeros((b, o), dtype=torch.int32, device="cuda")
-    pipe = algo.endswith("_pipe")
-    xnor.set_tuning(10 if pipe else 0)
     xnor.xnor_linear(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, out, dot, b, f, o,
-                     xnor.ALGOS[algo[:-5] if pipe else algo])
+                     xnor.ALGOS[algo])
     torch.cuda.synchronize()
-    xnor.set_tuning(0)
     assert np.array_equal(dot.cpu().numpy(), r["dot"])
     np.testing.assert_allclose(bufs.K.cpu().numpy().reshape(b), r["K"], rtol=RTOL, atol=ATOL)
     np.testing.assert_allclose(out.cpu().numpy(), r["out"], rtol=RTOL, atol=ATOL)
