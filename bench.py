@@ -1,11 +1,21 @@
 """Benchmark of the XNOR-Net binary convolution block on one MI355X.
 
-One step = one pass of the hot path over one batch resident in HBM:
-    xnor_binactiv (BatchNorm fold, sign + bit-pack, A)  ->  xnor_conv2d (binary dot, K from A, K*alpha).
-The weights are packed once before the timed region (at inference only B and alpha exist; the
-packing time is reported separately).  Prints ONE JSON line on stdout.
+One step = one pass of the hot path over one batch of every layer of the workload, inputs resident in HBM:
+    xnor_binactiv (BatchNorm fold, sign + bit-pack, A)  ->  xnor_conv2d / xnor_linear (binary dot, K from A, K*alpha).
+The default workload is all five benchmark configurations (ten layers).  Weights are packed once before the
+timed region (at inference only B and alpha exist; the packing time is reported separately).
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload alexnet_conv2] [--algo auto]
+Buffers: by default every layer owns a ring of input / packed / output buffer sets whose total exceeds three
+times the chip's 256 MB last-level cache and each step uses the next set, so that what is timed moves through
+HBM ("cold"); `--buffers fixed` re-uses one set (the "warm" figure is reported in the same line either way).
+
+Prints ONE JSON line on stdout:  value = whole-step throughput; `layers` = per-layer kernel times (HIP events
+around >= 50 back-to-back launches, independent of --steps) with their roofline fractions; `roofline` = the
+binary convolution kernel over all its launches of a step; `measured_peaks` = what this GPU delivers on the
+register-only inner loops and on streaming (xnor_ubench); `cpu_baseline` = the CPU oracle on the same inputs.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload all] [--buffers rotating]
+    python bench.py --report            # markdown tables instead of the JSON line
 """
 import argparse
 import json
@@ -17,232 +27,297 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
-# command (scaled by a 256 MiB copy: reads x2.00, writes x1.00), see profiles/; None where not measured.
-MEASURED_TRAFFIC = {("alexnet_conv2", "mfma_f4"): 1830.6 * 1024 * 2.0 + 49229.0 * 1024}
-
+HBM_PEAK_GBS = 8000.0
 PEAKS = {  # MI355X published dense peaks
-    "mfma_f4": {"bound": "mfma", "peak": 10100.0, "unit": "TFLOP/s"},     # fp4 10.1 PFLOP/s, 2 flops per MAC
-    "mfma_i8": {"bound": "mfma", "peak": 5000.0, "unit": "TOP/s"},        # int8 5.0 POP/s, 2 ops per MAC
-    # vector ALU bitcount: 2 instructions (XOR, bitcount-accumulate) per 32 binary MACs:
+    "mfma_f4": {"bound": "mfma", "peak": 10100.0, "unit": "TFLOP/s", "per_mac": 2.0},   # fp4 10.1 PFLOP/s
+    "mfma_i8": {"bound": "mfma", "peak": 5000.0, "unit": "TOP/s", "per_mac": 2.0},      # int8 5.0 POP/s
+    # vector ALU: 2 instructions (XOR, bitcount-accumulate) per 32 binary MACs:
     # 256 CUs x 64 lanes x 2.4 GHz x 16 MAC per lane-instruction
-    "popcount": {"bound": "alu", "peak": 256 * 64 * 2.4e9 * 16 / 1e12, "unit": "Tbinop/s"},
+    "popcount": {"bound": "alu", "peak": 256 * 64 * 2.4e9 * 16 / 1e12, "unit": "Tbinop/s", "per_mac": 1.0},
 }
+LLC_BYTES = 256 << 20          # last-level cache of the chip; rotating rings hold at least three times this
+WORKLOADS = ["all", "tiny", "alexnet_conv2", "alexnet_conv345", "resnet18", "fc"]
+
+# HBM bytes per launch of the convolution kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (each
+# scaled by the same counter over a plain copy of known size); source: the named file under profiles/.
+# None = not profiled.
+PROFILED_TRAFFIC = {}
+PROFILED_TRAFFIC_SOURCE = "profiles/conv_hbm_traffic.md"
 
 
-def algo_bytes(layer, fused=False):
-    """Bytes one xnor_conv2d launch must move: packed activations, matrix-core weight image (fp4),
-    A, alpha and the float output."""
-    cw = (layer.c + 31) // 32
-    taps = layer.kh * layer.kw
-    wimg = ((layer.k_out + 31) // 32) * ((taps * cw + 1) // 2) * 1024
-    m = layer.n * layer.h_out * layer.w_out
-    # result: the float tensor, or (fused epilogue) the next layer's sign words and A
-    result = m * ((layer.k_out + 31) // 32 * 4 + 4) if fused else m * layer.k_out * 4
-    return layer.n * layer.h * layer.w * (cw * 4 + 4) + wimg + layer.k_out * 4 + result
+class Shape:
+    """One layer as the kernels see it (a fully connected layer is the 1x1 image with in_features channels)."""
+
+    def __init__(self, cfg, idx, layer):
+        self.cfg, self.idx, self.layer, self.name = cfg, idx, layer, layer.name
+        self.fc = cfg == "fc"
+        if self.fc:
+            self.n, self.c, self.h, self.w = layer.batch, layer.in_features, 1, 1
+            self.k, self.kh, self.kw, self.stride, self.pad = layer.out_features, 1, 1, 1, 0
+        else:
+            self.n, self.c, self.h, self.w = layer.n, layer.c, layer.h, layer.w
+            self.k, self.kh, self.kw, self.stride, self.pad = layer.k_out, layer.kh, layer.kw, layer.stride, layer.pad
+        self.ho = (self.h + 2 * self.pad - self.kh) // self.stride + 1
+        self.wo = (self.w + 2 * self.pad - self.kw) // self.stride + 1
+        self.cw = (self.c + 31) // 32
+        self.macs = layer.bit_macs
+
+    def conv_bytes(self, fused=False):
+        """Algorithmic bytes of one xnor_conv2d launch: packed activations, packed 1-bit weights, the K map,
+        the float output (fused epilogue: the next block's sign words and A instead)."""
+        m = self.n * self.ho * self.wo
+        result = m * ((self.k + 31) // 32 * 4 + 4) if fused else m * self.k * 4
+        return self.n * self.h * self.w * self.cw * 4 + self.k * self.kh * self.kw * self.cw * 4 + m * 4 + result
+
+    def binactiv_bytes(self):
+        """Algorithmic bytes of one xnor_binactiv launch: the float input once, sign words and A out."""
+        px = self.n * self.h * self.w
+        return px * self.c * 4 + px * self.cw * 4 + px * 4
+
+    def roofs(self, seconds, algo="mfma_f4", fused=False):
+        pk = PEAKS[algo]
+        comp = {"bound": pk["bound"], "achieved": self.macs * pk["per_mac"] / seconds / 1e12, "peak": pk["peak"],
+                "unit": pk["unit"]}
+        hbm = {"bound": "hbm", "achieved": self.conv_bytes(fused) / seconds / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+        for r in (comp, hbm):
+            r["frac"] = r["achieved"] / r["peak"]
+        # the binding roof is the one with the longer floor time, i.e. the larger fraction at the same duration
+        return (hbm, comp) if hbm["frac"] >= comp["frac"] else (comp, hbm)
 
 
-def cpu_baseline(layers, inputs):
-    """The oracle as it stands, whole block, on this machine's host cores."""
+def workload_shapes(wl, name):
+    cfgs = ["tiny", "alexnet_conv2", "alexnet_conv345", "resnet18", "fc"] if name == "all" else [name]
+    return [Shape(c, i, l) for c in cfgs for i, l in enumerate(wl.config_layers(c))]
+
+
+class LayerState:
+    """Device tensors of one layer: the synthetic input, packed weights and a ring of buffer sets."""
+
+    def __init__(self, torch, wl, xnor, sh, ring_bytes):
+        seed = wl.config_seed(sh.cfg, sh.idx)
+        self.sh = sh
+        if sh.fc:
+            d = wl.linear_inputs(sh.layer, seed)
+            x = torch.from_numpy(d["x"]).reshape(sh.n, sh.c, 1, 1)
+            w = torch.from_numpy(d["w"]).reshape(sh.k, sh.c, 1, 1)
+            d = {"x": d["x"], "w": d["w"], "bn_scale": None, "bn_shift": None}
+        else:
+            d = wl.conv_inputs(sh.layer, seed)
+            x, w = torch.from_numpy(d["x"]), torch.from_numpy(d["w"])
+        self.host = d
+        self.sc = torch.from_numpy(d["bn_scale"]).cuda() if d["bn_scale"] is not None else None
+        self.sf = torch.from_numpy(d["bn_shift"]).cuda() if d["bn_shift"] is not None else None
+        self.desc = xnor.make_desc(sh.n, sh.c, sh.h, sh.w, sh.k, sh.kh, sh.kw, sh.stride, sh.pad)
+        wdev = w.cuda()
+        pw = xnor.PackedWeights(wdev)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        xnor.xnor_pack_weights(wdev, pw.wbits, pw.alpha, pw.wmfma, *pw.shape)
+        e0.record()
+        xnor.xnor_pack_weights(wdev, pw.wbits, pw.alpha, pw.wmfma, *pw.shape)
+        e1.record()
+        torch.cuda.synchronize()
+        self.pack_ms = e0.elapsed_time(e1)
+        per_set = x.numel() * 4 + sh.n * sh.h * sh.w * (sh.cw * 4 + 4) + sh.n * sh.k * sh.ho * sh.wo * 4
+        w_bytes = pw.wmfma.numel() + pw.wbits.numel() * 4
+        rotate_w = ring_bytes > 0 and w_bytes > per_set            # weight-heavy layers (FC) rotate their weights too
+        if rotate_w:
+            per_set += w_bytes
+        self.ring = 1 if ring_bytes <= 0 else max(2, min(24, -(-ring_bytes // per_set)))
+        xd = x.cuda()
+        self.x = [xd] + [xd.clone() for _ in range(self.ring - 1)]
+        self.bufs = [xnor.ConvBuffers(self.desc) for _ in range(self.ring)]
+        self.pw = [pw]
+        for _ in range(self.ring - 1 if rotate_w else 0):
+            q = xnor.PackedWeights(wdev)
+            q.wbits.copy_(pw.wbits), q.alpha.copy_(pw.alpha), q.wmfma.copy_(pw.wmfma)
+            self.pw.append(q)
+        del wdev
+        self.xnor = xnor
+
+    def binactiv(self, r):
+        b = self.bufs[r % self.ring]
+        self.xnor.xnor_binactiv(self.x[r % self.ring], self.sc, self.sf, b.xbits, b.A, None, self.desc)
+
+    def conv(self, r, algo):
+        b, pw, sh, xn = self.bufs[r % self.ring], self.pw[r % len(self.pw)], self.sh, self.xnor
+        if sh.fc:       # K of a 1x1 filter over a 1x1 image is A itself
+            xn.xnor_linear(b.xbits, pw.wbits, pw.wmfma, b.A, pw.alpha, b.out, None, sh.n, sh.c, sh.k, algo)
+        else:
+            xn.xnor_conv2d(b.xbits, pw.wbits, pw.wmfma, None, b.A, pw.alpha, b.out, None, self.desc, algo)
+
+
+def event_us(torch, fn, launches):
+    """Average duration of `launches` back-to-back calls fn(i) between two HIP events on the current stream."""
+    for i in range(min(10, launches)):
+        fn(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(launches):
+        fn(i)
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / launches
+
+
+def measured_peaks(torch, xnor):
+    """What this GPU delivers on the register-only inner loops and on streaming (xnor_ubench), next to the
+    published peaks the fractions are quoted against."""
+    buf = torch.empty((1 << 30) + (256 << 20), dtype=torch.uint8, device="cuda")
+    out = {}
+    wgs, iters = 2048, 2000            # two waves per SIMD, about 0.3 ms per launch
+    us = event_us(torch, lambda i: xnor.ubench("mfma_f4", wgs, iters, buf), 20)
+    out["mfma_f4_TFLOP_s"] = wgs * 4 * iters * 8 * 2.0 * 32 * 32 * 64 / us / 1e6
+    us = event_us(torch, lambda i: xnor.ubench("mfma_i8", wgs, iters, buf), 20)
+    out["mfma_i8_TOP_s"] = wgs * 4 * iters * 8 * 2.0 * 32 * 32 * 32 / us / 1e6
+    us = event_us(torch, lambda i: xnor.ubench("popcount", wgs, 500, buf), 20)
+    out["valu_xor_bitcount_Tbinop_s"] = wgs * 256 * 500 * 128 * 32.0 / us / 1e6
+    for name, nbytes in (("48MiB_llc_resident", 48 << 20), ("1GiB_through_hbm", 1 << 30)):
+        for kind, moved in (("fill", nbytes), ("read", nbytes), ("copy", nbytes)):
+            us = event_us(torch, lambda i: xnor.ubench(kind, 4096, 0, buf, nbytes), 30)
+            out[f"{kind}_{name}_GB_s"] = moved / us / 1e3
+    out["note"] = ("copy moves bytes/2 from the first half to the second (read + write counted); the 48 MiB figures "
+                   "stay in the 256 MB last-level cache, the 1 GiB ones pass through HBM")
+    del buf
+    return out
+
+
+def cpu_baseline(states):
+    """The oracle as it stands, whole block per layer, on this machine's host cores."""
     from oracle import xnor_oracle as xo
-    xo.binary_conv2d(inputs[0]["x"][:1], inputs[0]["w"], (1, 1), (0, 0))   # load + warm the library
+    first = states[0]
+    xo.binary_conv2d(first.host["x"].reshape(first.sh.n, first.sh.c, first.sh.h, first.sh.w)[:1],
+                     first.host["w"].reshape(first.sh.k, first.sh.c, first.sh.kh, first.sh.kw), (1, 1), (0, 0))
     t0 = time.perf_counter()
     macs = 0
-    for layer, d in zip(layers, inputs):
-        xo.binary_conv2d(d["x"], d["w"], (layer.stride,) * 2, (layer.pad,) * 2, d["bn_scale"], d["bn_shift"])
-        macs += layer.bit_macs
+    for st in states:
+        sh, d = st.sh, st.host
+        if sh.fc:
+            xo.binary_linear(d["x"], d["w"])
+        else:
+            xo.binary_conv2d(d["x"], d["w"], (sh.stride,) * 2, (sh.pad,) * 2, d["bn_scale"], d["bn_shift"])
+        macs += sh.macs
     dt = time.perf_counter() - t0
     return {"value": macs / dt / 1e9, "unit": "Gbinop/s", "cores": xo.threads(), "kind": "oracle",
-            "sample": f"full workload ({len(layers)} layer(s), batch {layers[0].n}), {dt:.2f} s wall"}
+            "sample": f"the full workload once ({len(states)} layer(s), {macs / 1e9:.1f} G binop), {dt:.2f} s wall"}
 
 
-def report(args):
-    """Per-layer table over all five configurations (markdown on stdout): median of `--steps` HIP-event
-    timed launches after warm-up (L2 not flushed between launches), for the convolution alone with each
-    inner loop, BinActiv alone, and the whole block; throughput, algorithmic GB/s and roofline fractions
-    of the fastest loop; the weight packing once; the CPU oracle on the same inputs."""
-    import statistics
+def chain_config3(torch, wl, xnor, launches):
+    """Config 3 as the chain it is: block i+1 consumes block i's output.  Layer by layer (xnor_binactiv +
+    xnor_conv2d per block) against the fused form (one xnor_binactiv, then xnor_conv2d_binactiv emits the next
+    block's sign words and A; the float tensor between the blocks is never written)."""
+    shapes = workload_shapes(wl, "alexnet_conv345")
+    sts = [LayerState(torch, wl, xnor, sh, 0) for sh in shapes]
+    ws = [torch.empty((max(16, xnor.conv2d_binactiv_workspace_bytes(s.desc)),), dtype=torch.uint8, device="cuda")
+          for s in sts]
+    f4 = xnor.XNOR_ALGO_MFMA_F4
 
-    import torch
-    from paper_1603_05279_amd import workloads as wl
-    from paper_1603_05279_amd import xnor
+    def layerwise(_):
+        for i, s in enumerate(sts):
+            b = s.bufs[0]
+            xnor.xnor_binactiv(s.x[0] if i == 0 else sts[i - 1].bufs[0].out, s.sc, s.sf, b.xbits, b.A, None, s.desc)
+            xnor.xnor_conv2d(b.xbits, s.pw[0].wbits, s.pw[0].wmfma, None, b.A, s.pw[0].alpha, b.out, None, s.desc, f4)
 
-    torch.cuda.set_device(0)
-    runs = max(args.steps, 50)
+    def fused(_):
+        s0 = sts[0]
+        xnor.xnor_binactiv(s0.x[0], s0.sc, s0.sf, s0.bufs[0].xbits, s0.bufs[0].A, None, s0.desc)
+        for i, s in enumerate(sts):
+            b, pw = s.bufs[0], s.pw[0]
+            if i + 1 < len(sts):
+                nx = sts[i + 1]
+                xnor.xnor_conv2d_binactiv(b.xbits, pw.wbits, pw.wmfma, None, b.A, pw.alpha, nx.sc, nx.sf,
+                                          nx.bufs[0].xbits, nx.bufs[0].A, None, ws[i], s.desc, f4)
+            else:
+                xnor.xnor_conv2d(b.xbits, pw.wbits, pw.wmfma, None, b.A, pw.alpha, b.out, None, s.desc, f4)
 
-    def median_us(fn):
-        for _ in range(5):
-            fn()
-        torch.cuda.synchronize()
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(runs)]
-        for a, b in ev:
-            a.record()
-            fn()
-            b.record()
-        torch.cuda.synchronize()
-        return statistics.median(a.elapsed_time(b) for a, b in ev) * 1e3
+    macs = sum(s.sh.macs for s in sts)
+    res = {"G_binop": macs / 1e9}
+    for name, fn in (("layerwise", layerwise), ("fused", fused)):
+        us = event_us(torch, fn, launches)
+        res[name + "_us"] = us
+        res[name + "_Tbinop_s"] = macs / us / 1e6
+    # the fused convolution kernel alone (no float output: bound by the matrix cores)
+    per = []
+    for i, s in enumerate(sts[:-1]):
+        b, pw, nx = s.bufs[0], s.pw[0], sts[i + 1]
+        us = event_us(torch, lambda _: xnor.xnor_conv2d_binactiv(b.xbits, pw.wbits, pw.wmfma, None, b.A, pw.alpha, nx.sc,
+                                                                 nx.sf, nx.bufs[0].xbits, nx.bufs[0].A, None, ws[i],
+                                                                 s.desc, f4), launches)
+        bind, other = s.sh.roofs(us * 1e-6, "mfma_f4", fused=True)
+        per.append({"layer": s.sh.name, "conv2d_binactiv_us": us, "bound": bind["bound"], "frac": bind["frac"],
+                    "other_frac": other["frac"]})
+    res["conv2d_binactiv"] = per
+    return res
 
-    # streaming copy: the practical HBM rate the fractions below are also quoted against
-    src = torch.empty(256 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda").normal_()
-    dst = torch.empty_like(src)
-    copy_us = median_us(lambda: dst.copy_(src))
-    copy_gbs = 2 * src.numel() * 4 / (copy_us * 1e-6) / 1e9
-    del src, dst
-    print(f"Streaming copy 256 MiB: {copy_us:.1f} us = {copy_gbs:.0f} GB/s (read + write); published peak 8000 GB/s.")
-    print(f"Every figure: median of {runs} single launches bracketed by HIP events (the bracket itself adds "
-          "about 3 us of dispatch latency to a launch); L2 not flushed between launches.\n")
-    print("| config / layer | G binop | conv fp4 us | conv int8 us | conv popcount us | BinActiv us | block us | "
-          "Tbinop/s (conv fp4) | alg. GB/s | % fp4 peak | % HBM peak | % attainable | pack us | oracle Gbinop/s |")
+
+def measure_layers(torch, xnor, states, launches, compare_algos=True):
+    """Per-layer kernel times, independent of --steps: `launches` back-to-back launches between HIP events."""
+    rows = []
+    f4 = xnor.XNOR_ALGO_MFMA_F4
+    for st in states:
+        sh = st.sh
+        for r in range(st.ring):
+            st.binactiv(r)
+        row = {"config": sh.cfg, "layer": sh.name, "G_binop": sh.macs / 1e9, "ring": st.ring}
+        row["conv_us"] = event_us(torch, lambda i: st.conv(i, f4), launches)                    # through the ring
+        row["conv_us_warm"] = event_us(torch, lambda i: st.conv(0, f4), launches)               # one buffer set
+        row["binactiv_us"] = event_us(torch, lambda i: st.binactiv(i), launches)
+        row["binactiv_us_warm"] = event_us(torch, lambda i: st.binactiv(0), launches)
+        if compare_algos:
+            row["conv_us_warm_mfma_i8"] = event_us(torch, lambda i: st.conv(0, xnor.XNOR_ALGO_MFMA_I8), launches)
+            row["conv_us_warm_popcount"] = event_us(torch, lambda i: st.conv(0, xnor.XNOR_ALGO_POPCOUNT), launches)
+        sec = row["conv_us"] * 1e-6
+        bind, other = sh.roofs(sec)
+        row.update({"Tbinop_s": sh.macs / sec / 1e12, "algorithmic_bytes": sh.conv_bytes(),
+                    "flop": 2.0 * sh.macs, "bound": bind["bound"], "frac": bind["frac"],
+                    "other_roof": other["bound"], "other_frac": other["frac"],
+                    "frac_warm": sh.roofs(row["conv_us_warm"] * 1e-6)[0]["frac"],
+                    "binactiv_GB_s": sh.binactiv_bytes() / row["binactiv_us"] / 1e3,
+                    "pack_weights_ms_once": st.pack_ms,
+                    "profiled_hbm_bytes": PROFILED_TRAFFIC.get(sh.name)})
+        rows.append(row)
+    return rows
+
+
+def print_report(rows, peaks, chain, cpu):
+    print("Measured peaks (xnor_ubench): " + ", ".join(f"{k} {v:.0f}" for k, v in peaks.items() if k != "note"))
+    print("\n| config / layer | G binop | conv fp4 us (ring) | conv fp4 us (one set) | conv int8 us | conv popcount us | "
+          "BinActiv us (ring) | Tbinop/s | alg. MB | bound | frac of bound | frac of other roof | BinActiv GB/s | pack ms |")
     print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
-    from oracle import xnor_oracle as xo
-    for cfg in ("tiny", "alexnet_conv2", "alexnet_conv345", "resnet18", "fc"):
-        for i, layer in enumerate(wl.config_layers(cfg)):
-            seed = wl.config_seed(cfg, i)
-            if cfg == "fc":
-                d = wl.linear_inputs(layer, seed)
-                n, c, h, w_, k, kh, kw, st, pd = layer.batch, layer.in_features, 1, 1, layer.out_features, 1, 1, 1, 0
-                x = torch.from_numpy(d["x"]).cuda().reshape(n, c, 1, 1)
-                wt = torch.from_numpy(d["w"]).cuda().reshape(k, c, 1, 1)
-                sc = sf = None
-            else:
-                d = wl.conv_inputs(layer, seed)
-                n, c, h, w_, k, kh, kw, st, pd = (layer.n, layer.c, layer.h, layer.w, layer.k_out, layer.kh,
-                                                  layer.kw, layer.stride, layer.pad)
-                x, wt = torch.from_numpy(d["x"]).cuda(), torch.from_numpy(d["w"]).cuda()
-                sc = torch.from_numpy(d["bn_scale"]).cuda() if d["bn_scale"] is not None else None
-                sf = torch.from_numpy(d["bn_shift"]).cuda() if d["bn_shift"] is not None else None
-            desc = xnor.make_desc(n, c, h, w_, k, kh, kw, st, pd)
-            pw = xnor.PackedWeights(wt)
-            bufs = xnor.ConvBuffers(desc)
-            pack_us = median_us(lambda: xnor.xnor_pack_weights(wt, pw.wbits, pw.alpha, pw.wmfma, k, c, kh, kw))
-            ba_us = median_us(lambda: xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, None, desc))
-            conv = {a: median_us(lambda a=a: xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha,
-                                                               bufs.out, None, desc, xnor.ALGOS[a]))
-                    for a in ("mfma_f4", "mfma_i8", "popcount")}
-
-            def block():
-                xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, None, desc)
-                xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha, bufs.out, None, desc,
-                                 xnor.XNOR_ALGO_MFMA_F4)
-            block_us = median_us(block)
-            macs = layer.bit_macs
-            ho, wo = xnor.output_hw(desc)
-            cw = (c + 31) // 32
-            nbytes = (n * h * w_ * (cw * 4 + 4) + ((k + 31) // 32) * ((kh * kw * cw + 1) // 2) * 1024 + k * 4 +
-                      n * k * ho * wo * 4)
-            t = conv["mfma_f4"] * 1e-6
-            tb, gbs = macs / t / 1e12, nbytes / t / 1e9
-            attain = max(2 * macs / 10.1e15, nbytes / 8e12) / t        # against min(peak, AI x BW)
-            t0 = time.perf_counter()
-            if cfg == "fc":
-                xo.binary_linear(d["x"], d["w"])
-            else:
-                xo.binary_conv2d(d["x"], d["w"], (st, st), (pd, pd), d["bn_scale"], d["bn_shift"])
-            orc = macs / (time.perf_counter() - t0) / 1e9
-            print(f"| {cfg} / {layer.name} | {macs / 1e9:.2f} | {conv['mfma_f4']:.1f} | {conv['mfma_i8']:.1f} | "
-                  f"{conv['popcount']:.1f} | {ba_us:.1f} | {block_us:.1f} | {tb:.0f} | {gbs:.0f} | "
-                  f"{100 * 2 * tb / 10100:.1f} | {100 * gbs / 8000:.1f} | {100 * attain:.1f} | {pack_us:.1f} | "
-                  f"{orc:.1f} |", flush=True)
-    # the widened rows: Binary-Weight-Network convolution and binary-gradient backward convolution
-    print("\n| config / layer | BWN split us | BWN conv us | bf16 TFLOP/s (3 parts) | % bf16 peak | fp32-equiv TFLOP/s | "
-          "grad binarize us | grad conv us | Tbinop/s (grad conv) | 2-bit pack us | 2x2-bit conv us | "
-          "pool 3x3/2 + BinActiv of the output us |")
-    print("|---|---|---|---|---|---|---|---|---|---|---|---|")
-    for cfg in ("alexnet_conv2", "alexnet_conv345", "resnet18"):
-        for i, layer in enumerate(wl.config_layers(cfg)):
-            n, c, h, w_, k, kh, kw, st, pd = (layer.n, layer.c, layer.h, layer.w, layer.k_out, layer.kh, layer.kw,
-                                              layer.stride, layer.pad)
-            gen = torch.Generator(device="cuda")
-            gen.manual_seed(wl.config_seed(cfg, i))
-            x = torch.randn((n, c, h, w_), device="cuda", generator=gen)
-            wt = torch.randn((k, c, kh, kw), device="cuda", generator=gen)
-            desc = xnor.make_desc(n, c, h, w_, k, kh, kw, st, pd)
-            ho, wo = xnor.output_hw(desc)
-            u8 = lambda nbytes: torch.empty((nbytes,), dtype=torch.uint8, device="cuda")
-            parts, wimg = u8(xnor.bwn_parts_bytes(n, c, h, w_)), u8(xnor.bwn_wimg_bytes(k, c, kh, kw))
-            alpha = torch.empty((k,), device="cuda")
-            out = torch.empty((n, k, ho, wo), device="cuda")
-            xnor.xnor_bwn_pack_weights(wt, alpha, wimg, k, c, kh, kw)
-            split_us = median_us(lambda: xnor.xnor_bwn_split(x, parts, n, c, h, w_))
-            bwn_us = median_us(lambda: xnor.xnor_bwn_conv2d(parts, wimg, alpha, out, desc))
-            flops = 2.0 * layer.bit_macs
-            row = (f"| {cfg} / {layer.name} | {split_us:.1f} | {bwn_us:.1f} | {3 * flops / bwn_us / 1e6:.0f} | "
-                   f"{100 * 3 * flops / bwn_us / 1e6 / 2500:.1f} | {flops / bwn_us / 1e6:.0f} |")
-            if st == 1:
-                Kp = torch.rand((n, ho, wo), device="cuda", generator=gen) + 0.5
-                kw32 = xnor.words_per_pixel(k)
-                wtbits = torch.empty((c, kh * kw, kw32), dtype=torch.int32, device="cuda")
-                wtmfma = u8(xnor.wmfma_bytes(c, k, kh, kw))
-                ones, gmax = torch.empty((c,), device="cuda"), torch.empty((n,), device="cuda")
-                gbits = torch.empty((n, ho, wo, kw32), dtype=torch.int32, device="cuda")
-                plane, gin = torch.empty((n, h, w_), device="cuda"), torch.empty((n, c, h, w_), device="cuda")
-                xnor.xnor_bingrad_pack_weights(wt, wtbits, ones, wtmfma, k, c, kh, kw)
-                gb_us = median_us(lambda: xnor.xnor_bingrad_binarize(out, Kp, alpha, gbits, gmax, desc))
-                gc_us = median_us(lambda: xnor.xnor_bingrad_conv2d(gbits, wtbits, wtmfma, gmax, ones, plane, gin, None,
-                                                                   desc, xnor.XNOR_ALGO_AUTO))
-                row += f" {gb_us:.1f} | {gc_us:.1f} | {layer.bit_macs / gc_us / 1e6:.0f} |"
-            else:
-                row += " - | - | - |"
-            # 2-bit inputs x 2-bit weights (inputs scaled into [-1, 1])
-            xs = torch.tanh(x)
-            xq, wq2 = u8(xnor.kbit_input_bytes(n, c, h, w_)), u8(xnor.kbit_wimg_bytes(k, c, kh, kw))
-            scale2 = torch.empty((k,), device="cuda")
-            xnor.xnor_kbit_pack_weights(torch.tanh(wt), scale2, wq2, 2, 2, k, c, kh, kw)
-            kp_us = median_us(lambda: xnor.xnor_kbit_pack_input(xs, xq, 2, n, c, h, w_))
-            kc_us = median_us(lambda: xnor.xnor_kbit_conv2d(xq, wq2, scale2, out, None, desc, 2, 2))
-            row += f" {kp_us:.1f} | {kc_us:.1f} |"
-            del xq, wq2
-            # max-pool 3x3 stride 2 of this layer's output fused into the next block's BinActiv
-            if ho >= 3 and wo >= 3:
-                hp_, wp_ = (ho - 3) // 2 + 1, (wo - 3) // 2 + 1
-                pb = torch.empty((n, hp_, wp_, xnor.words_per_pixel(k)), dtype=torch.int32, device="cuda")
-                pa = torch.empty((n, hp_, wp_), device="cuda")
-                pl_us = median_us(lambda: xnor.xnor_pool_binactiv(out, None, None, pb, pa, n, k, ho, wo, (3, 3), (2, 2)))
-                row += f" {pl_us:.1f} |"
-            else:
-                row += " - |"
-            print(row, flush=True)
-    # the oracle on one thread, tiny configuration (the other oracle figures use every host thread)
-    import ctypes
-    gomp = ctypes.CDLL("libgomp.so.1")
-    nthreads = xo.threads()
-    tiny = wl.config_layers("tiny")[0]
-    dt_in = wl.conv_inputs(tiny, wl.config_seed("tiny"))
-    gomp.omp_set_num_threads(1)
-    t0 = time.perf_counter()
-    for _ in range(20):
-        xo.binary_conv2d(dt_in["x"], dt_in["w"], (tiny.stride, tiny.stride), (tiny.pad, tiny.pad))
-    one = 20 * tiny.bit_macs / (time.perf_counter() - t0) / 1e9
-    gomp.omp_set_num_threads(nthreads)
-    print(f"\nOracle on one thread, tiny configuration: {one:.2f} Gbinop/s.  One binop = one +-1 multiply-accumulate; "
-          "counting XNOR and bitcount as two operations doubles every Tbinop/s figure above.")
-    print(f"Oracle: {xo.threads()} host threads.  % attainable = floor time at min(fp4 peak, arithmetic "
-          "intensity x 8 TB/s) / measured time.  The paper's own figures: 58x measured, 62.27x modelled speed-up of "
-          "binary over float convolution on its CPU, memory access excluded (sec. 4.1).")
+    for r in rows:
+        print(f"| {r['config']} / {r['layer']} | {r['G_binop']:.2f} | {r['conv_us']:.1f} | {r['conv_us_warm']:.1f} | "
+              f"{r.get('conv_us_warm_mfma_i8', float('nan')):.1f} | {r.get('conv_us_warm_popcount', float('nan')):.1f} | "
+              f"{r['binactiv_us']:.1f} | {r['Tbinop_s']:.0f} | {r['algorithmic_bytes'] / 1e6:.1f} | {r['bound']} | "
+              f"{r['frac']:.3f} | {r['other_frac']:.3f} | {r['binactiv_GB_s']:.0f} | {r['pack_weights_ms_once']:.3f} |")
+    if chain:
+        print(f"\nConfig 3 as a chain ({chain['G_binop']:.2f} G binop): layer by layer {chain['layerwise_us']:.1f} us, "
+              f"fused {chain['fused_us']:.1f} us; xnor_conv2d_binactiv alone: " +
+              ", ".join(f"{p['layer']} {p['conv2d_binactiv_us']:.1f} us ({p['bound']} {p['frac']:.3f})"
+                        for p in chain["conv2d_binactiv"]))
+    if cpu:
+        print(f"\nCPU oracle: {cpu['value']:.1f} Gbinop/s on {cpu['cores']} threads ({cpu['sample']}).")
+    print("\nring = rotating buffer sets (HBM), one set = re-used buffers (last-level cache).  frac = achieved / "
+          "published peak of the binding roof (HBM 8 TB/s on algorithmic bytes, or fp4 matrix cores 10.1 PFLOP/s).  "
+          "One binop = one +-1 multiply-accumulate.  The paper's own figures: 58x measured, 62.27x modelled "
+          "speed-up of binary over float convolution on its CPU, memory access excluded (sec. 4.1).")
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="alexnet_conv2",
-                    choices=["tiny", "alexnet_conv2", "alexnet_conv345", "resnet18"])
-    ap.add_argument("--algo", default="fastest", choices=["fastest", "popcount", "mfma_i8", "mfma_f4"],
-                    help="inner loop of the binary convolution; 'fastest' times all three and keeps the winner")
-    ap.add_argument("--chain", default="none", choices=["none", "layerwise", "fused"],
-                    help="alexnet_conv345 only: feed each layer the previous layer's output instead of its own "
-                         "synthetic input; 'layerwise' = xnor_binactiv + xnor_conv2d per layer, 'fused' = one "
-                         "xnor_binactiv, then xnor_conv2d_binactiv emits the next layer's bits and A directly")
-    ap.add_argument("--report", action="store_true",
-                    help="print a per-layer table over all configurations instead of the one JSON line")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="all", choices=WORKLOADS)
+    ap.add_argument("--algo", default="mfma_f4", choices=["auto", "popcount", "mfma_i8", "mfma_f4"],
+                    help="inner loop of the binary convolution in the timed step")
+    ap.add_argument("--buffers", default="rotating", choices=["rotating", "fixed"],
+                    help="rotating: each step uses the next of a ring of buffer sets larger than the last-level cache")
+    ap.add_argument("--launches", type=int, default=60, help="back-to-back launches per per-layer kernel timing")
+    ap.add_argument("--report", action="store_true", help="markdown tables instead of the JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run a plain 256 MiB device copy, so a rocprofv3 --pmc run of this command holds "
-                         "a kernel of known HBM traffic to scale FETCH_SIZE / WRITE_SIZE by")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip measured peaks, the inner-loop comparison and the config-3 chain (profiling runs)")
     args = ap.parse_args()
-    if args.chain != "none" and args.workload != "alexnet_conv345":
-        sys.exit("bench.py: --chain needs --workload alexnet_conv345 (the only workload whose layers feed each other)")
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (the path shards over the batch with no "
                  "exchange step, each GPU running these same kernels on its share of the images). Run with --gpus 1.")
@@ -253,138 +328,90 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
-    if args.report:
-        report(args)
-        return
     torch.cuda.set_device(0)
-    layers = wl.config_layers(args.workload)
-    inputs = [wl.conv_inputs(l, wl.config_seed(args.workload, i)) for i, l in enumerate(layers)]
+    shapes = workload_shapes(wl, args.workload)
+    ring_bytes = 3 * LLC_BYTES if args.buffers == "rotating" else 0
+    states = [LayerState(torch, wl, xnor, sh, ring_bytes) for sh in shapes]
+    algo = xnor.ALGOS[args.algo]
 
-    # device state: inputs, packed weights, preallocated activation buffers
-    dev = []
-    pack_ms = 0.0
-    for layer, d in zip(layers, inputs):
-        x = torch.from_numpy(d["x"]).cuda()
-        w = torch.from_numpy(d["w"]).cuda()
-        sc = torch.from_numpy(d["bn_scale"]).cuda() if d["bn_scale"] is not None else None
-        sf = torch.from_numpy(d["bn_shift"]).cuda() if d["bn_shift"] is not None else None
-        desc = xnor.make_desc(layer.n, layer.c, layer.h, layer.w, layer.k_out, layer.kh, layer.kw,
-                              layer.stride, layer.pad)
-        pw = xnor.PackedWeights(w)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        xnor.xnor_pack_weights(w, pw.wbits, pw.alpha, pw.wmfma, *pw.shape)
-        e1.record()
+    def step(s):
+        for st in states:
+            st.binactiv(s)
+            st.conv(s, algo)
+
+    def timed(nsteps, offset):
         torch.cuda.synchronize()
-        pack_ms += e0.elapsed_time(e1)
-        dev.append((x, sc, sf, pw, xnor.ConvBuffers(desc)))
-
-    def conv_only_ms(name, iters=10):
-        """Average conv-kernel time of one pass over all layers with inner loop `name` (HIP events)."""
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        for it in range(iters + 2):
-            if it == 2:
-                e0.record()
-            for (x, sc, sf, pw, bufs) in dev:
-                xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha, bufs.out, None, bufs.desc,
-                                 xnor.ALGOS[name])
-        e1.record()
+        t0 = time.perf_counter()
+        for s in range(nsteps):
+            step(offset + s)
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / iters
+        return time.perf_counter() - t0
 
-    for (x, sc, sf, pw, bufs) in dev:
-        xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, None, bufs.desc)
-    compare = {name: conv_only_ms(name) for name in ("popcount", "mfma_i8", "mfma_f4")}
-    used = min(compare, key=compare.get) if args.algo == "fastest" else args.algo
-    if args.chain == "fused" and used == "popcount":
-        sys.exit("bench.py: the fused epilogue exists in the matrix-core kernels only (--algo mfma_f4 or mfma_i8)")
-    algo = xnor.ALGOS[used]
-
-    workspaces = [torch.empty((max(16, xnor.conv2d_binactiv_workspace_bytes(b.desc)),), dtype=torch.uint8,
-                              device="cuda") for (_, _, _, _, b) in dev] if args.chain == "fused" else None
-
-    def step(events=None):
-        for i, (x, sc, sf, pw, bufs) in enumerate(dev):
-            last = i + 1 == len(dev)
-            if args.chain == "none":
-                xnor.xnor_binactiv(x, sc, sf, bufs.xbits, bufs.A, None, bufs.desc)
-            elif args.chain == "layerwise" or i == 0:
-                src = x if i == 0 else dev[i - 1][4].out
-                xnor.xnor_binactiv(src, sc, sf, bufs.xbits, bufs.A, None, bufs.desc)
-            if events is not None:
-                events[i][0].record()
-            if args.chain == "fused" and not last:
-                nxt = dev[i + 1]
-                xnor.xnor_conv2d_binactiv(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha, nxt[1], nxt[2],
-                                          nxt[4].xbits, nxt[4].A, None, workspaces[i], bufs.desc, algo)
-            else:
-                xnor.xnor_conv2d(bufs.xbits, pw.wbits, pw.wmfma, None, bufs.A, pw.alpha, bufs.out, None, bufs.desc,
-                                 algo)
-            if events is not None:
-                events[i][1].record()
-
-    if args.copy_calibration:
-        src = torch.empty(256 * 1024 * 1024 // 4, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-
-    for _ in range(args.warmup):
-        step()
+    for s in range(args.warmup):
+        step(s)
+    dt = timed(args.steps, args.warmup)
+    macs = sum(sh.macs for sh in shapes)
+    # the same steps on one buffer set (served by the last-level cache where the layer fits it)
+    for s in range(min(args.warmup, 5)):
+        for st in states:
+            st.binactiv(0), st.conv(0, algo)
     torch.cuda.synchronize()
-    # HIP events around the convolution launch on every 8th step only: an event record is a stream
-    # command of its own and costs about 3 us, which would otherwise inflate every step by 6 us
-    sampled = [s for s in range(args.steps) if s % 8 == 0]
-    ev = {s: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in dev]
-          for s in sampled}
     t0 = time.perf_counter()
     for s in range(args.steps):
-        step(ev.get(s))
+        for st in states:
+            st.binactiv(0), st.conv(0, algo)
     torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
+    dt_warm = time.perf_counter() - t0
 
-    macs = sum(l.bit_macs for l in layers)
-    ms_per_step = dt / args.steps * 1e3
-    # dominant kernel = the binary convolution; average launch duration from the HIP events
-    conv_ms = [sum(ev[s][i][0].elapsed_time(ev[s][i][1]) for s in sampled) / len(sampled)
-               for i in range(len(dev))]
-    dom = max(range(len(dev)), key=lambda i: conv_ms[i])
-    pk = PEAKS[used]
-    per_mac = 1.0 if used == "popcount" else 2.0
-    sec = conv_ms[dom] * 1e-3
-    compute = {"bound": pk["bound"], "achieved": layers[dom].bit_macs * per_mac / sec / 1e12, "peak": pk["peak"],
-               "unit": pk["unit"]}
-    dom_fused = args.chain == "fused" and dom + 1 < len(dev)
-    hbm = {"bound": "hbm", "achieved": algo_bytes(layers[dom], dom_fused) / sec / 1e9, "peak": 8000.0,
-           "unit": "GB/s"}
-    for r in (compute, hbm):
+    rows = measure_layers(torch, xnor, states, max(50, args.launches), compare_algos=not args.no_extras)
+    peaks = None if args.no_extras else measured_peaks(torch, xnor)
+    chain = None if args.no_extras else chain_config3(torch, wl, xnor, max(50, args.launches))
+    cpu = None if args.no_cpu_baseline else cpu_baseline(states)
+    if args.report:
+        print_report(rows, peaks or {}, chain, cpu)
+        return
+
+    # dominant kernel: the binary convolution, over all its launches of one step
+    conv_s = sum(r["conv_us"] for r in rows) * 1e-6
+    nbytes, flop = sum(r["algorithmic_bytes"] for r in rows), sum(r["flop"] for r in rows)
+    hbm = {"bound": "hbm", "achieved": nbytes / conv_s / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    mfma = {"bound": "mfma", "achieved": flop / conv_s / 1e12, "peak": PEAKS["mfma_f4"]["peak"], "unit": "TFLOP/s"}
+    for r in (hbm, mfma):
         r["frac"] = r["achieved"] / r["peak"]
-    # the binding roof is the one whose floor time at the published peak is longer; at the same measured
-    # duration that is the one with the larger fraction.  The other one is reported next to it.
-    bind, other = (hbm, compute) if hbm["frac"] >= compute["frac"] else (compute, hbm)
+    bind, other = (hbm, mfma) if hbm["frac"] >= mfma["frac"] else (mfma, hbm)
+    traffic = [r["profiled_hbm_bytes"] for r in rows]
     roofline = dict(bind)
-    roofline.update({"traffic": MEASURED_TRAFFIC.get((args.workload, used)),
-                     "algorithmic_bytes": algo_bytes(layers[dom], dom_fused),
-                     "kernel": f"{'xnor_conv2d_binactiv' if dom_fused else 'xnor_conv2d'}[{layers[dom].name}]",
-                     "other_roof": other})
+    roofline.update({
+        "traffic": sum(traffic) if all(t is not None for t in traffic) else None,
+        "traffic_source": PROFILED_TRAFFIC_SOURCE + " (rocprofv3 FETCH_SIZE / WRITE_SIZE, not measured in this run)",
+        "kernel": "conv_mfma_kernel (xnor_conv2d / xnor_linear, 4-bit-float matrix instructions), all launches of one step",
+        "launches_per_step": len(rows), "algorithmic_bytes": nbytes, "flop": flop,
+        "avg_launch_us": conv_s * 1e6 / len(rows), "timing": f"HIP events around {max(50, args.launches)} back-to-back "
+        "launches per layer, rotating buffer sets" if args.buffers == "rotating" else "HIP events, one buffer set",
+        "other_roof": other})
     out = {
         "metric": "binary conv throughput (Gbinop/s) + % of popcount/MFMA roofline",
         "value": macs / (dt / args.steps) / 1e9, "unit": "Gbinop/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {"mfma_f4": "fp4", "mfma_i8": "i8", "popcount": "u32"}[used], "data": "synthetic",
-        "config": {"workload": args.workload, "layers": [l.name for l in layers], "batch": layers[0].n,
-                   "algo": used, "algo_conv_ms": compare, "step": {"none": "xnor_binactiv + xnor_conv2d per layer, each layer on its own synthetic input",
-                            "layerwise": "xnor_binactiv + xnor_conv2d per layer, each layer on the previous output",
-                            "fused": "xnor_binactiv, then xnor_conv2d_binactiv per layer (plain xnor_conv2d last)"
-                            }[args.chain],
-                   "conv_ms": conv_ms, "pack_weights_ms_once": pack_ms,
-                   "conv_only_Gbinop_s": [l.bit_macs / (t * 1e-3) / 1e9 for l, t in zip(layers, conv_ms)]},
+        "dtype": {"mfma_f4": "fp4", "mfma_i8": "i8", "popcount": "u32", "auto": "fp4"}[args.algo], "data": "synthetic",
+        "config": {"workload": "all_five_configs" if args.workload == "all" else args.workload,
+                   "layers": [sh.name for sh in shapes], "algo": args.algo,
+                   "step": "xnor_binactiv + xnor_conv2d (xnor_linear) per layer, each layer on its own synthetic input",
+                   "buffers": (f"rotating rings, >= {3 * LLC_BYTES >> 20} MB per layer (through HBM)"
+                               if args.buffers == "rotating" else "one buffer set per layer"),
+                   "bn_eps": wl.BN_EPS},
+        "value_one_buffer_set": macs / (dt_warm / args.steps) / 1e9,
+        "ms_per_step_one_buffer_set": dt_warm / args.steps * 1e3,
+        "layers": rows,
         "roofline": roofline,
     }
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(layers, inputs)
+    if peaks:
+        out["measured_peaks"] = peaks
+    if chain:
+        out["chain_config3"] = chain
+    if cpu:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
 
 

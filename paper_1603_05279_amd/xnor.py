@@ -16,7 +16,7 @@ ALGOS = {"auto": XNOR_ALGO_AUTO, "popcount": XNOR_ALGO_POPCOUNT, "mfma_i8": XNOR
          "mfma_f4": XNOR_ALGO_MFMA_F4}
 
 EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor_wmfma_bytes",
-           "xnor_set_tuning",
+           "xnor_set_tuning", "xnor_ubench",
            "xnor_binarize_pack", "xnor_compute_K", "xnor_binactiv", "xnor_pack_weights",
            "xnor_conv2d", "xnor_linear",
            "xnor_conv2d_binactiv_workspace_bytes", "xnor_conv2d_binactiv", "xnor_pool_binactiv",
@@ -61,6 +61,8 @@ def lib():
         L.xnor_wmfma_bytes.restype = ctypes.c_size_t
         L.xnor_set_tuning.argtypes = [ip, ip]
         L.xnor_set_tuning.restype = ip
+        L.xnor_ubench.argtypes = [ip, ip, ip, vp, ctypes.c_size_t, vp]
+        L.xnor_ubench.restype = ip
         L.xnor_binarize_pack.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp]
         L.xnor_binarize_pack.restype = ip
         L.xnor_compute_K.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(ConvDesc), vp]
@@ -109,6 +111,16 @@ def lib():
         L.xnor_kbit_conv2d.restype = ip
         _lib = L
     return _lib
+
+
+UBENCH = {"mfma_f4": 0, "mfma_i8": 1, "popcount": 2, "fill": 3, "read": 4, "copy": 5}
+
+
+def ubench(kind, workgroups, iters, buf, nbytes=None, stream=None):
+    """One microbenchmark launch (include/xnor_ubench.h); buf is a torch uint8 device tensor."""
+    nbytes = buf.numel() * buf.element_size() if nbytes is None else nbytes
+    _check("xnor_ubench", lib().xnor_ubench(UBENCH[kind], int(workgroups), int(iters), ctypes.c_void_p(buf.data_ptr()),
+                                            ctypes.c_size_t(nbytes), _stream(stream)))
 
 
 def status_string(status):
