@@ -188,6 +188,27 @@ XNOR_API int xnor_conv2d_binactiv(const uint32_t *xbits, const uint32_t *wbits, 
                          const xnor_conv_desc *d, int algo, void *hip_stream);
 
 /*
+ * xnor_conv2d_binactiv for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * launches as xnor_conv2d_binactiv, minus `workspace`: the partial |z| sums go to a buffer of
+ * XNOR_NOALLOC_SCRATCH_BYTES that lives in the library's device image (every GPU the process uses holds one
+ * until the process ends).  The call allocates and frees nothing.
+ *   - XNOR_ERR_UNSUPPORTED when xnor_conv2d_binactiv_workspace_bytes(d) exceeds XNOR_NOALLOC_SCRATCH_BYTES
+ *     (4 MiB: every layer of the AlexNet / ResNet-18 shapes at batch 256 needs at most 3.2 MiB).
+ *   - All calls on one GPU share that buffer: calls that may overlap on one GPU (different streams, or
+ *     graphs replayed concurrently) race on it and must be serialised by the caller.  Nothing in it needs
+ *     clearing between calls.
+ *   - XNOR_ERR_HIP when the buffer's device address cannot be obtained (asked once per device, at the first
+ *     call with that device current).
+ */
+#define XNOR_NOALLOC_SCRATCH_BYTES (4u << 20)
+XNOR_API int xnor_conv2d_binactiv_noalloc(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+                                          const float *K, const float *A, const float *alpha,
+                                          const float *bn_scale_next, const float *bn_shift_next,
+                                          uint32_t *xbits_next, float *A_next, float *out,
+                                          const xnor_conv_desc *d, int algo, void *hip_stream);
+
+/*
  * Binary convolution with the block's pooling layer applied in the epilogue (block order BinConv -> Pool,
  * with the optional ReLU after BinConv; sec. 3.2):
  *   out_pool[n][k][py][px] = max over the pool_h x pool_w window at (py*pstride_h, px*pstride_w) of

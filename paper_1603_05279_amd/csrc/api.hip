@@ -1,5 +1,6 @@
 // C ABI of libxnor: argument validation and dispatch.  Declarations and contracts: include/xnor.h.
 #include "xnor_internal.h"
+#include <mutex>
 
 using namespace xnor;
 
@@ -261,6 +262,54 @@ int xnor_conv2d_binactiv(const uint32_t *xbits, const uint32_t *wbits, const voi
         if (s != XNOR_ERR_UNSUPPORTED || algo == XNOR_ALGO_MFMA_F4) return s;
     }
     return launch_conv_mfma(0, xbits, wmfma, K, A, alpha, out, nullptr, g, st, &fz);
+}
+
+/* ---- xnor_conv2d_binactiv for callers that cannot allocate ------------------------------------------ */
+
+}  // extern "C" (file-scope device memory and its host-side bookkeeping follow)
+
+// Library-owned scratch for the partial |z| sums of xnor_conv2d_binactiv_noalloc.  Every GPU the library
+// runs on holds its own copy at its own address until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress: kernels are given the address that call returns.
+static __device__ __align__(256) unsigned char scratch[XNOR_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[MAX_DEVICES];          // device address of `scratch` per device ordinal, NULL = not asked yet
+
+// Address of the current device's copy of `scratch` (asked once per device, with that device current).
+xnor_status scratch_address(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return XNOR_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return XNOR_ERR_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return XNOR_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int xnor_conv2d_binactiv_noalloc(const uint32_t *xbits, const uint32_t *wbits, const void *wmfma,
+                                 const float *K, const float *A, const float *alpha,
+                                 const float *bn_scale_next, const float *bn_shift_next,
+                                 uint32_t *xbits_next, float *A_next, float *out,
+                                 const xnor_conv_desc *d, int algo, void *hip_stream)
+{
+    const size_t need = xnor_conv2d_binactiv_workspace_bytes(d);     // 0 also for an invalid descriptor: caught below
+    if (need > (size_t)XNOR_NOALLOC_SCRATCH_BYTES) return XNOR_ERR_UNSUPPORTED;
+    void *ws = nullptr;
+    if (xnor_status s = scratch_address(&ws)) return s;
+    // Nothing in the scratch has to start at zero: the second kernel reads only the partial sums the first
+    // one wrote in this call.
+    return xnor_conv2d_binactiv(xbits, wbits, wmfma, K, A, alpha, bn_scale_next, bn_shift_next, xbits_next, A_next,
+                                out, ws, d, algo, hip_stream);
 }
 
 /* ---- Binary-Weight-Network convolution: real activations, +-1 weights (sec. 3.1) ------------------ */

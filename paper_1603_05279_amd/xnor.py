@@ -19,7 +19,8 @@ EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor
            "xnor_set_tuning", "xnor_ubench",
            "xnor_binarize_pack", "xnor_compute_K", "xnor_binactiv", "xnor_pack_weights",
            "xnor_conv2d", "xnor_linear",
-           "xnor_conv2d_binactiv_workspace_bytes", "xnor_conv2d_binactiv", "xnor_pool_binactiv",
+           "xnor_conv2d_binactiv_workspace_bytes", "xnor_conv2d_binactiv", "xnor_conv2d_binactiv_noalloc",
+           "xnor_pool_binactiv",
            "xnor_bwn_parts_bytes", "xnor_bwn_wimg_bytes", "xnor_bwn_split", "xnor_bwn_pack_weights",
            "xnor_bwn_conv2d",
            "xnor_bingrad_pack_weights", "xnor_bingrad_binarize", "xnor_bingrad_conv2d",
@@ -79,6 +80,8 @@ def lib():
         L.xnor_conv2d_binactiv_workspace_bytes.restype = ctypes.c_size_t
         L.xnor_conv2d_binactiv.argtypes = [vp] * 12 + [ctypes.POINTER(ConvDesc), ip, vp]
         L.xnor_conv2d_binactiv.restype = ip
+        L.xnor_conv2d_binactiv_noalloc.argtypes = [vp] * 11 + [ctypes.POINTER(ConvDesc), ip, vp]
+        L.xnor_conv2d_binactiv_noalloc.restype = ip
         L.xnor_pool_binactiv.argtypes = [vp] * 5 + [ip] * 11 + [vp]
         L.xnor_pool_binactiv.restype = ip
         L.xnor_bwn_parts_bytes.argtypes = [ip, ip, ip, ip]
@@ -314,6 +317,19 @@ def xnor_conv2d_binactiv(xbits, wbits, wmfma, K, A, alpha, bn_scale_next, bn_shi
         _ptr(bn_scale_next, torch.float32), _ptr(bn_shift_next, torch.float32),
         _ptr(xbits_next, torch.int32), _ptr(A_next, torch.float32), _ptr(out, torch.float32),
         _ptr(workspace, torch.uint8), ctypes.byref(desc), int(algo), _stream(stream)))
+
+
+NOALLOC_SCRATCH_BYTES = 4 << 20      # XNOR_NOALLOC_SCRATCH_BYTES of include/xnor.h
+
+
+def xnor_conv2d_binactiv_noalloc(xbits, wbits, wmfma, K, A, alpha, bn_scale_next, bn_shift_next, xbits_next,
+                                 A_next, out, desc, algo=XNOR_ALGO_AUTO, stream=None):
+    _check("xnor_conv2d_binactiv_noalloc", lib().xnor_conv2d_binactiv_noalloc(
+        _ptr(xbits, torch.int32), _ptr(wbits, torch.int32), _ptr(wmfma, torch.uint8),
+        _ptr(K, torch.float32), _ptr(A, torch.float32), _ptr(alpha, torch.float32),
+        _ptr(bn_scale_next, torch.float32), _ptr(bn_shift_next, torch.float32),
+        _ptr(xbits_next, torch.int32), _ptr(A_next, torch.float32), _ptr(out, torch.float32),
+        ctypes.byref(desc), int(algo), _stream(stream)))
 
 
 # ---------------------------------------------------------------------------------------------
