@@ -121,131 +121,27 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     const int r_hi = (int)(img_b * g.hp + oy_b * g.sh) + g.kh - 1;
     const int nrows = r_hi - r_lo + 1;
 
-    // ---- requests that depend on nothing but the tile index leave first: the first DW weight records of this
-    // wave's filter blocks and alpha (fused epilogue: also scale and shift) of the workgroup's filters.  Their
-    // latency (L2 or HBM, a microsecond when cold) then runs under everything up to the K loop.
-    // weight records of this wave's filter blocks: record index = fblk * recs_per_fblock + step record
-    const int recs_per_fb = (g.taps * g.cw + E::BPS - 1) / E::BPS;
-    // Weight records are fetched with buffer loads: scalar record offset + the lane's 16-byte slot,
-    // so the K loop spends no vector registers or ALU work on weight addresses.
-    const __amdgpu_buffer_rsrc_t wrsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<v4i *>(wimg), 0, (int)wimg_bytes, 0x00020000);
-    const int wlane = lane * 16;
-    const int zero_rec = (int)(wimg_bytes >> 10) - 1;      // the image ends with an all-zero record
-    int wrec0[FW];
-#pragma unroll
-    for (int i = 0; i < FW; ++i) {
-        const int fb = min(f0 / 32 + wf * FW + i, g.fblocks - 1);
-        wrec0[i] = __builtin_amdgcn_readfirstlane(fb * recs_per_fb);
-    }
-    const int steps_per_tap = pl.tap_jump ? ccw / E::BPS : 0x7fffffff;
-    // record of step s of the chunk that starts at channel word wbase: rec0 + wbase / BPS + s + (s / steps_per_tap) * tap_jump
-    typedef typename std::conditional<LINEAR, WStreamLinear<FW>, WStreamChunked<FW>>::type WS;
-    auto make_ws = [&](int wbase) -> WS {
-        if constexpr (LINEAR) return WS(wimg, wrec0, wbase / E::BPS, nsteps, wlane);
-        else return WS(wrsrc, wrec0, zero_rec, wbase / E::BPS, nsteps, steps_per_tap, pl.tap_jump, wlane);
-    };
-    WS ws = make_ws(0);
-    v4i wring[DW + 1][FW];
-    kloop_prefetch_w<FW, DW>(wring, ws);
-    // alpha (and the next block's scale and shift) travel in registers until the tables are built; filters past
-    // the last one repeat it and are masked later
-    constexpr int PARI = (FT + NT - 1) / NT;
-    float par_reg[PARI][FUSE ? 3 : 1];
-#pragma unroll
-    for (int q = 0; q < PARI; ++q) {
-        const int kc = min(f0 + min(tid + q * NT, FT - 1), g.k_out - 1);
-        par_reg[q][0] = alpha[kc];
+    E::build_lut(lds + pl.lut_offset, tid, NT);
+    // alpha (fused epilogue: also scale and shift) of this workgroup's filters, staged once behind the
+    // widening table ([FT] each); filters past the last one repeat it and are masked later
+    float *par_lds = reinterpret_cast<float *>(lds + pl.lut_offset + E::LUT_BYTES);
+    for (int t = tid; t < FT; t += NT) {
+        const int kc = min(f0 + t, g.k_out - 1);
+        par_lds[t] = alpha[kc];
         if constexpr (FUSE) {
-            par_reg[q][1] = fz.bn_scale ? fz.bn_scale[kc] : 1.0f;
-            par_reg[q][2] = fz.bn_scale ? fz.bn_shift[kc] : 0.0f;
+            par_lds[FT + t] = fz.bn_scale ? fz.bn_scale[kc] : 1.0f;
+            par_lds[2 * FT + t] = fz.bn_scale ? fz.bn_shift[kc] : 0.0f;
         }
     }
-    // first pixel of the (real) input row behind padded row r_lo + rr of the tile: -1 for padding rows and the
-    // zero rows of a dilated input
-    auto row_base = [&](uint32_t rr) -> int {
-        const uint32_t R = (uint32_t)r_lo + rr;
+    for (int rr = tid; rr < nrows; rr += NT) {
+        const uint32_t R = (uint32_t)(r_lo + rr);
         const uint32_t img = pl.div_hp.div(R);
         const int y = (int)(R - img * g.hp) - g.ph;
+        // first pixel of the (real) input row, -1 for padding rows and the zero rows of a dilated input
         const uint32_t ry = g.div_dil_h.div_small((uint32_t)max(y, 0));
         const bool rv = y >= 0 && y < g.h && (int)ry * g.dil_h == y && (int)ry < g.real_h;
-        return rv ? (int)((img * g.real_h + ry) * g.real_w) : -1;
-    };
-
-    // ---- activation staging: packed words (or raw operand words) of the padded rows go to LDS, FB items in
-    // flight per thread: loads first, then widening.  The first batch of the first chunk and the first words of
-    // the matrix A are requested here, before the tables below are built, so that their latency overlaps too.
-    constexpr int FB = 4;                      // items in flight per thread
-    struct Batch {
-        uint32_t bits[FB];
-        uint4 raw[RAW ? FB : 1][2];            // FMT 2, 3: the 32-byte word itself
-        int dst[FB], nch[FB];
-        bool ok[FB];
-    };
-    const int items = nrows * g.wp * ccw;
-    // (`direct`: the row's base is computed instead of read from the row table, which is not built yet when the
-    // first batch leaves)
-    auto fill_load = [&](int wbase, int it0, Batch &b, bool direct) {
-#pragma unroll
-        for (int u = 0; u < FB; ++u) {
-            const int it = it0 + u * NT;
-            const uint32_t itc = (uint32_t)min(it, items - 1);
-            const uint32_t px = pl.div_ccw.div_small(itc);
-            const int wl = (int)(itc - px * ccw);
-            const uint32_t rr = pl.div_wp.div_small(px);
-            const int xv = (int)(px - rr * g.wp) - g.pw;                 // column of the (virtual) input
-            const int xcol = (int)g.div_dil_w.div_small((uint32_t)max(xv, 0));  // column of the real tensor
-            const int rowbase = direct ? row_base(rr) : rowinfo[rr];
-            b.ok[u] = rowbase >= 0 && xv >= 0 && xv < g.w && xcol * g.dil_w == xv && xcol < g.real_w;
-            b.dst[u] = it < items ? (int)(rr * pl.row_pitch + (px - rr * g.wp) * pl.ps + wl * E::BPB) : -1;
-            b.nch[u] = g.c - (wbase + wl) * 32;
-            b.bits[u] = 0;
-            if constexpr (RAW) {
-                b.raw[u][0] = b.raw[u][1] = make_uint4(0, 0, 0, 0);
-                if (b.ok[u]) {
-                    const uint4 *src = reinterpret_cast<const uint4 *>(xbits) +
-                                       (((size_t)rowbase + xcol) * g.cw + wbase + wl) * 2;
-                    b.raw[u][0] = src[0];
-                    b.raw[u][1] = src[1];
-                }
-            } else {
-                if (b.ok[u]) b.bits[u] = xbits[((size_t)rowbase + xcol) * g.cw + wbase + wl];
-            }
-        }
-    };
-    auto fill_store = [&](const Batch &b) {
-#pragma unroll
-        for (int u = 0; u < FB; ++u)
-            if (b.dst[u] >= 0) {
-                if constexpr (RAW) {
-                    *reinterpret_cast<uint4 *>(lds + b.dst[u]) = b.raw[u][0];
-                    *reinterpret_cast<uint4 *>(lds + b.dst[u] + 16) = b.raw[u][1];
-                } else {
-                    E::widen_word_lut(lds + b.dst[u], lut, b.bits[u], b.ok[u], b.nch[u]);
-                }
-            }
-    };
-    Batch b0;
-    fill_load(0, tid, b0, true);
-    // matrix A of the same input rows (0 in the halo), for the K of this tile
-    const bool needK = !RAW && !K;
-    constexpr int FA = 2;
-    const int a_items = nrows * g.wp;
-    auto a_load = [&](int it, bool direct) -> float {
-        const uint32_t rr = pl.div_wp.div_small((uint32_t)it);
-        const int xcol = it - (int)rr * g.wp - g.pw;
-        const int rowbase = direct ? row_base(rr) : rowinfo[rr];
-        const bool ok = rowbase >= 0 && xcol >= 0 && xcol < g.w;
-        return ok ? A[(size_t)rowbase + xcol] : 0.0f;
-    };
-    float a_reg[FA];
-#pragma unroll
-    for (int u = 0; u < FA; ++u) a_reg[u] = (needK && tid + u * NT < a_items) ? a_load(tid + u * NT, true) : 0.0f;
-
-    // ---- tables, built while those requests travel
-    for (int rr = tid; rr < nrows; rr += NT) rowinfo[rr] = row_base((uint32_t)rr);
-    E::build_lut(lds + pl.lut_offset, tid, NT);
-    float *par_lds = reinterpret_cast<float *>(lds + pl.lut_offset + E::LUT_BYTES);      // [FT] each, behind the widening table
+        rowinfo[rr] = rv ? (int)((img * g.real_h + ry) * g.real_w) : -1;
+    }
     // LDS offset of every channel block of a chunk relative to a pixel's window origin:
     // block b = tap * ccw + word  ->  (dy*wp + dx)*ps + word*BPB
     {
@@ -270,23 +166,21 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         pbase[j] = ((int)(img * g.hp + oy * g.sh) - r_lo) * pl.row_pitch + (int)ox * g.sw * pl.ps +
                    (E::HALF_SPLIT ? 16 * half : 0);
     }
+    // weight records of this wave's filter blocks: record index = fblk * recs_per_fblock + step record
+    const int recs_per_fb = (g.taps * g.cw + E::BPS - 1) / E::BPS;
+    // Weight records are fetched with buffer loads: scalar record offset + the lane's 16-byte slot,
+    // so the K loop spends no vector registers or ALU work on weight addresses.
+    const __amdgpu_buffer_rsrc_t wrsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<v4i *>(wimg), 0, (int)wimg_bytes, 0x00020000);
+    const int wlane = lane * 16;
+    const int zero_rec = (int)(wimg_bytes >> 10) - 1;      // the image ends with an all-zero record
+    int wrec0[FW];
+#pragma unroll
+    for (int i = 0; i < FW; ++i) {
+        const int fb = min(f0 / 32 + wf * FW + i, g.fblocks - 1);
+        wrec0[i] = __builtin_amdgcn_readfirstlane(fb * recs_per_fb);
+    }
     const int tab_lane = (E::HALF_SPLIT ? 0 : half);
-#pragma unroll
-    for (int q = 0; q < PARI; ++q) {
-        const int t = tid + q * NT;
-        if (t < FT) {
-            par_lds[t] = par_reg[q][0];
-            if constexpr (FUSE) {
-                par_lds[FT + t] = par_reg[q][1];
-                par_lds[2 * FT + t] = par_reg[q][2];
-            }
-        }
-    }
-    if (needK) {
-#pragma unroll
-        for (int u = 0; u < FA; ++u)
-            if (tid + u * NT < a_items) a_lds[tid + u * NT] = a_reg[u];
-    }
 
     acc_t acc[FW][PW];
 #pragma unroll
@@ -295,58 +189,103 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         for (int j = 0; j < PW; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
-
+    const int steps_per_tap = pl.tap_jump ? ccw / E::BPS : 0x7fffffff;
     for (int wbase = 0; wbase < g.cw; wbase += ccw) {
-        __syncthreads();   // widening table visible / previous chunk fully consumed
-        int it_first = tid;
-        if (wbase == 0) {
-            fill_store(b0);
-            it_first += NT * FB;
-            if (needK)
-                for (int it = tid + FA * NT; it < a_items; it += NT) a_lds[it] = a_load(it, false);
-        } else {
-            ws = make_ws(wbase);
-        }
-        for (int it0 = it_first; it0 < items; it0 += NT * FB) {
-            Batch b;
-            fill_load(wbase, it0, b, false);
-            fill_store(b);
-        }
-        __syncthreads();
-        if (needK && wbase == 0) {
-            // K of the tile's output pixels, an equal share per wave: the kh x kw taps of A in row-major order
-            // over the staged rows (halo entries add +0.0f, the same bits as skipping them), divided by kh*kw
-            constexpr int KPW = (PT + WF * WP - 1) / (WF * WP);
-            for (int kt = wave * KPW + lane; kt < min((wave + 1) * KPW, PT); kt += 64) {
-                const uint32_t m = min(m0 + (uint32_t)kt, m_end - 1u);
-                const uint32_t img = g.div_howo.div(m);
-                const uint32_t pix = m - img * howo;
-                const uint32_t oy = g.div_wo.div(pix), ox = pix - oy * g.wo;
-                const float *ap = a_lds + ((int)(img * g.hp + oy * g.sh) - r_lo) * g.wp + (int)ox * g.sw;
-                // the common filters with every tap's read in flight at once (one LDS latency instead of one per
-                // group of four taps); the additions keep the row-major order either way
-                float s;
-                if (g.kh == 3 && g.kw == 3) s = box_sum_lds<3, 3>(ap, g.wp);
-                else if (g.kh == 5 && g.kw == 5) s = box_sum_lds<5, 5>(ap, g.wp);
-                else if (g.kh == 1 && g.kw == 1) s = 0.0f + ap[0];
-                else {
-                    s = 0.0f;
-                    for (int dy = 0; dy < g.kh; ++dy, ap += g.wp)
-                        for (int dx0 = 0; dx0 < g.kw; dx0 += 4) {
-                            float a[4];
+        __syncthreads();   // tables visible / previous chunk fully consumed
+        const int items = nrows * g.wp * ccw;
+        constexpr int FB = RAW ? 4 : 8;        // items in flight per thread: loads first, then widening (every batch costs one round trip to L2 or HBM)
+        for (int it0 = tid; it0 < items; it0 += NT * FB) {
+            uint32_t bits[FB];
+            uint4 raw[FB][2];              // FMT 2: the 32-byte word itself
+            int dst[FB], nch[FB];
+            bool ok[FB];
 #pragma unroll
-                            for (int u = 0; u < 4; ++u) a[u] = ap[min(dx0 + u, g.kw - 1)];
-#pragma unroll
-                            for (int u = 0; u < 4; ++u) s += dx0 + u < g.kw ? a[u] : 0.0f;
-                        }
+            for (int u = 0; u < FB; ++u) {
+                const int it = it0 + u * NT;
+                const uint32_t itc = (uint32_t)min(it, items - 1);
+                const uint32_t px = pl.div_ccw.div_small(itc);
+                const int wl = (int)(itc - px * ccw);
+                const uint32_t rr = pl.div_wp.div_small(px);
+                const int xv = (int)(px - rr * g.wp) - g.pw;                 // column of the (virtual) input
+                const int xcol = (int)g.div_dil_w.div_small((uint32_t)max(xv, 0));  // column of the real tensor
+                const int rowbase = rowinfo[rr];
+                ok[u] = rowbase >= 0 && xv >= 0 && xv < g.w && xcol * g.dil_w == xv && xcol < g.real_w;
+                dst[u] = it < items ? (int)(rr * pl.row_pitch + (px - rr * g.wp) * pl.ps + wl * E::BPB) : -1;
+                nch[u] = g.c - (wbase + wl) * 32;
+                bits[u] = 0;
+                if constexpr (RAW) {
+                    raw[u][0] = raw[u][1] = make_uint4(0, 0, 0, 0);
+                    if (ok[u]) {
+                        const uint4 *src = reinterpret_cast<const uint4 *>(xbits) +
+                                           (((size_t)rowbase + xcol) * g.cw + wbase + wl) * 2;
+                        raw[u][0] = src[0];
+                        raw[u][1] = src[1];
+                    }
+                } else {
+                    if (ok[u]) bits[u] = xbits[((size_t)rowbase + xcol) * g.cw + wbase + wl];
                 }
-                ktile[kt] = s / (float)(g.kh * g.kw);
+            }
+#pragma unroll
+            for (int u = 0; u < FB; ++u)
+                if (dst[u] >= 0) {
+                    if constexpr (RAW) {
+                        *reinterpret_cast<uint4 *>(lds + dst[u]) = raw[u][0];
+                        *reinterpret_cast<uint4 *>(lds + dst[u] + 16) = raw[u][1];
+                    } else {
+                        E::widen_word_lut(lds + dst[u], lut, bits[u], ok[u], nch[u]);
+                    }
+                }
+        }
+        if (!RAW && wbase == 0 && !K) {
+            // stage the matrix A of the same input rows (0 in the halo) for the K of this tile
+            for (int it = tid; it < nrows * g.wp; it += NT) {
+                const uint32_t rr = pl.div_wp.div_small((uint32_t)it);
+                const int xcol = it - (int)rr * g.wp - g.pw;
+                const int rowbase = rowinfo[rr];
+                const bool ok = rowbase >= 0 && xcol >= 0 && xcol < g.w;
+                a_lds[it] = ok ? A[(size_t)rowbase + xcol] : 0.0f;
             }
         }
-        // ---- software-pipelined K loop over this chunk's steps (the first chunk's first records are on their way)
-        mfma_kloop<E, FW, PW, DW, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps, wring, wbase == 0);
-    }
+        __syncthreads();
+        // K of the tile's output pixels, an equal share per wave: the kh x kw taps of A in row-major order over the
+        // staged rows (halo entries add +0.0f, the same bits as skipping them), divided by kh*kw
+        constexpr int KPW = (PT + WF * WP - 1) / (WF * WP);
+        if (!RAW && wbase == 0 && !K) for (int kt = wave * KPW + lane; kt < min((wave + 1) * KPW, PT); kt += 64) {
+            const uint32_t m = min(m0 + (uint32_t)kt, m_end - 1u);
+            const uint32_t img = g.div_howo.div(m);
+            const uint32_t pix = m - img * howo;
+            const uint32_t oy = g.div_wo.div(pix), ox = pix - oy * g.wo;
+            const float *ap = a_lds + ((int)(img * g.hp + oy * g.sh) - r_lo) * g.wp + (int)ox * g.sw;
+            // the common filters with every tap's read in flight at once (one LDS latency instead of one per group
+            // of four taps); the additions keep the row-major order either way
+            float s;
+            if (g.kh == 3 && g.kw == 3) s = box_sum_lds<3, 3>(ap, g.wp);
+            else if (g.kh == 5 && g.kw == 5) s = box_sum_lds<5, 5>(ap, g.wp);
+            else if (g.kh == 1 && g.kw == 1) s = 0.0f + ap[0];
+            else {
+                s = 0.0f;
+                for (int dy = 0; dy < g.kh; ++dy, ap += g.wp)
+                    for (int dx0 = 0; dx0 < g.kw; dx0 += 4) {
+                        float a[4];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) a[u] = ap[min(dx0 + u, g.kw - 1)];
+#pragma unroll
+                        for (int u = 0; u < 4; ++u) s += dx0 + u < g.kw ? a[u] : 0.0f;
+                    }
+            }
+            ktile[kt] = s / (float)(g.kh * g.kw);
+        }
 
+        // ---- software-pipelined K loop over this chunk's steps --------------------------------
+        // record of step s: rec0 + s + (s / steps_per_tap) * tap_jump
+        if constexpr (LINEAR) {      // the chunk holds every channel word: consecutive records
+            WStreamLinear<FW> ws(wimg, wrec0, wbase / E::BPS, nsteps, wlane);
+            mfma_kloop<E, FW, PW, DW, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps);
+        } else {
+            WStreamChunked<FW> ws(wrsrc, wrec0, zero_rec, wbase / E::BPS, nsteps, steps_per_tap, pl.tap_jump, wlane);
+            mfma_kloop<E, FW, PW, DW, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps);
+        }
+    }
     // epilogue: out = float(dot) * K * alpha; result register v of a lane is filter row
     // 8*(v/4) + 4*half + v%4 of the 32-filter block, pixel column l32.  alpha of the lane's
     // filter rows is fetched once (clamped index, no branch), stores are predicated.
@@ -617,7 +556,7 @@ static int plan_lut_offset(const MfmaPlan &pl, int fmt, int wp, int PT, int fuse
 }
 
 static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fuse_rows, int par_bytes, MfmaPlan *pl,
-                      int rows_override = 0)
+                      int rows_override = 0, bool lone = false)
 {
     const int bps = fmt_bps(fmt), bpb = fmt == 1 ? 16 : 32;
     const int rows = rows_override ? rows_override : worst_region_rows(g, PT, PT);
@@ -648,7 +587,9 @@ static bool make_plan(const ConvGeom &g, int PT, int fmt, int lds_budget, int fu
         const bool last = ccw <= bps;
         // one chunk with all channel words keeps the weight records consecutive (the K loop without
         // bookkeeping) and saves the refills: worth up to half the CU's LDS (two workgroups per CU)
-        const long long budget = ccw == g.cw ? (lds_budget > 80 * 1024 ? lds_budget : 80 * 1024) : lds_budget;
+        // (`lone`: the launch has at most one workgroup per CU, which may then take nearly all of the CU's LDS)
+        const long long whole = lone ? 156 * 1024 : 80 * 1024;
+        const long long budget = ccw == g.cw ? (lds_budget > whole ? lds_budget : whole) : lds_budget;
         if (total > budget && !last) continue;
         if (total > LDS_LIMIT) return false;
         pl->div_wp = FastDiv::make((uint32_t)g.wp);
@@ -703,7 +644,9 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     if ((PT / howo + 2) * g.k_out * howo * 4 >= 0x7ffffff0LL) return XNOR_ERR_UNSUPPORTED;
     MfmaPlan pl;
     constexpr int FROWS = FUSE ? WF + FT / 32 : 0, PARB = (FUSE ? 3 : 1) * FT * 4;
-    if (!make_plan(g, PT, FMT, g_lds_budget.load(std::memory_order_relaxed), FROWS, PARB, &pl)) return XNOR_ERR_UNSUPPORTED;
+    const long long wg_count = (long long)((g.m_total + PT - 1) / PT) * ((g.k_out + FT - 1) / FT);
+    if (!make_plan(g, PT, FMT, g_lds_budget.load(std::memory_order_relaxed), FROWS, PARB, &pl, 0, wg_count <= 256))
+        return XNOR_ERR_UNSUPPORTED;
     const size_t lds = plan_lds_bytes(pl, FMT, g.wp, PT, FROWS, PARB);
     pl.lut_offset = plan_lut_offset(pl, FMT, g.wp, PT, FROWS, PARB);
     // two builds of every tiling: weight records consecutive (one chunk holds all channel words) or not

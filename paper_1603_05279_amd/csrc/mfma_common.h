@@ -315,20 +315,10 @@ template <int FW> struct WStreamChunked {
 // The scheduling barriers pin the order written here (next operands requested, then the current
 // step's matrix instructions interleaved with those requests), which the compiler otherwise
 // regroups into one burst of loads followed by one burst of MFMAs with the latencies exposed.
-// The weight ring `w` belongs to the caller, so that the first DW records of a tile can be requested at
-// the very start of the kernel (kloop_prefetch_w), long before the activations are staged; `preloaded`
-// says whether that has happened for this chunk.
-template <int FW, int DW, class WS>
-__device__ __forceinline__ void kloop_prefetch_w(v4i (&w)[DW + 1][FW], WS &ws)
-{
-#pragma unroll
-    for (int u = 0; u < DW; ++u) ws.load(w[u]);
-}
-
 template <class E, int FW, int PW, int DW, int DX, class WS>
 __device__ __forceinline__ void mfma_kloop(typename E::acc_t (&acc)[FW][PW], const uint8_t *lds_x,
                                            const int (&pbase)[PW], const int *xoff_tab, int tab_lane, WS &ws,
-                                           int nsteps, v4i (&w)[DW + 1][FW], bool preloaded)
+                                           int nsteps)
 {
     constexpr int RW = DW + 1, RX = DX + 1;
     constexpr int TURN = ring_lcm(RW, RX);     // sub-steps after which both rings are back at slot 0
@@ -354,9 +344,10 @@ __device__ __forceinline__ void mfma_kloop(typename E::acc_t (&acc)[FW][PW], con
                 for (int i = 0; i < FW; ++i) acc[i][j] = E::mfma(w[i], x[j][q], acc[i][j]);
     };
 
-    v4i x[RX][PW][NX];
+    v4i w[RW][FW], x[RX][PW][NX];
     int tq[2];
-    if (!preloaded) kloop_prefetch_w<FW, DW>(w, ws);
+#pragma unroll
+    for (int u = 0; u < DW; ++u) load_w(w[u]);
 #pragma unroll
     for (int u = 0; u < DX; ++u) load_x(x[u], load_t(u));
     tq[0] = load_t(DX);

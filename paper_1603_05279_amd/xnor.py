@@ -9,7 +9,8 @@ import os
 
 import torch
 
-_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libxnor.so")
+# XNOR_LIBRARY selects another build of the library (development: comparing builds); default: the in-tree one
+_LIB_PATH = os.environ.get("XNOR_LIBRARY") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libxnor.so")
 
 XNOR_ALGO_AUTO, XNOR_ALGO_POPCOUNT, XNOR_ALGO_MFMA_I8, XNOR_ALGO_MFMA_F4 = 0, 1, 2, 3
 ALGOS = {"auto": XNOR_ALGO_AUTO, "popcount": XNOR_ALGO_POPCOUNT, "mfma_i8": XNOR_ALGO_MFMA_I8,
