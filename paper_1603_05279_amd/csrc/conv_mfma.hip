@@ -55,7 +55,9 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     // Weight prefetch depth.  Five steps pay off on long K loops; the 64-filter tiles serve layers
     // with short K loops and many workgroups, and the fused epilogue needs registers of its own:
     // there three steps keep more waves resident.
-    constexpr int DW = (FUSE || FT <= 64 || FMT == 2) ? 3 : 5;      // (bfloat16 parts: a step is three times as long)
+    // A wave tile of a single result block (fully connected layers: few output tiles, long K) issues one matrix
+    // instruction per KiB of weights: only a deep ring keeps enough bytes in flight to cover the L2 latency.
+    constexpr int DW = (FW * PW == 1 && FMT < 2 && !FUSE) ? 7 : (FUSE || FT <= 64 || FMT == 2) ? 3 : 5;      // (bfloat16 parts: a step is three times as long)
     extern __shared__ __attribute__((aligned(16))) uint8_t lds[];
     int *rowinfo = reinterpret_cast<int *>(lds + pl.region_bytes);
     int *xoff_tab = rowinfo + pl.max_rows;     // [(nsteps + KLOOP_TABLE_PAD) * BPS]
@@ -192,6 +194,53 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     const int steps_per_tap = pl.tap_jump ? ccw / E::BPS : 0x7fffffff;
     for (int wbase = 0; wbase < g.cw; wbase += ccw) {
         __syncthreads();   // tables visible / previous chunk fully consumed
+        // the first words of the matrix A are requested before the activation words, so that the two round trips
+        // to memory overlap
+        constexpr int FA = FW * PW > 4 ? 2 : 0;       // (small tiles: the registers are worth more as a fourth wave per SIMD)
+        float a_reg[FA + 1];
+        const bool stageA = !RAW && wbase == 0 && !K;
+        auto a_load = [&](int it) -> float {
+            const uint32_t rr = pl.div_wp.div_small((uint32_t)it);
+            const int xcol = it - (int)rr * g.wp - g.pw;
+            const int rowbase = rowinfo[rr];
+            const bool ok = rowbase >= 0 && xcol >= 0 && xcol < g.w;
+            return ok ? A[(size_t)rowbase + xcol] : 0.0f;
+        };
+#pragma unroll
+        for (int u = 0; u < FA; ++u) a_reg[u] = (stageA && tid + u * NT < nrows * g.wp) ? a_load(tid + u * NT) : 0.0f;
+        if (!RAW && pl.dense) {
+          if constexpr (!RAW) {
+            // 1x1 filter without padding: the tile's pixels are consecutive pixels of the input and their packed
+            // words one contiguous, 16-byte aligned run of memory: four words per load, up to twelve loads in flight
+            // (a fully connected layer's 36 words per thread in one round trip)
+            constexpr int FD = FW * PW == 1 ? 12 : 4;     // (the one-block wave tiles of fully connected layers have the registers)
+            const int nwords = (int)(m_end - m0) * ccw;
+            const uint4 *src = reinterpret_cast<const uint4 *>(xbits + (size_t)m0 * g.cw);
+            for (int i0 = tid * 4; i0 < nwords; i0 += NT * 4 * FD) {
+                uint4 v[FD];
+#pragma unroll
+                for (int u = 0; u < FD; ++u) {
+                    const int i = i0 + u * NT * 4;
+                    v[u] = src[min(i, nwords - 4) >> 2];
+                }
+#pragma unroll
+                for (int u = 0; u < FD; ++u) {
+                    const int i = i0 + u * NT * 4;
+                    if (i < nwords) {
+                        const uint32_t px = pl.div_ccw.div_small((uint32_t)i);
+                        const int wl = i - (int)px * ccw;
+                        const uint32_t m = m0 + px;
+                        const uint32_t R = g.div_wo.div(m);                 // image row of the pixel (h_out = h, w_out = w)
+                        uint8_t *dst = lds + ((int)R - r_lo) * pl.row_pitch + (int)(m - R * g.wo) * pl.ps + wl * E::BPB;
+                        const uint32_t wv[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+                            E::widen_word_lut(dst + q * E::BPB, lut, wv[q], true, g.c - (wl + q) * 32);
+                    }
+                }
+            }
+          }
+        } else {
         const int items = nrows * g.wp * ccw;
         constexpr int FB = RAW ? 4 : 8;        // items in flight per thread: loads first, then widening (every batch costs one round trip to L2 or HBM)
         for (int it0 = tid; it0 < items; it0 += NT * FB) {
@@ -236,15 +285,13 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
                     }
                 }
         }
-        if (!RAW && wbase == 0 && !K) {
-            // stage the matrix A of the same input rows (0 in the halo) for the K of this tile
-            for (int it = tid; it < nrows * g.wp; it += NT) {
-                const uint32_t rr = pl.div_wp.div_small((uint32_t)it);
-                const int xcol = it - (int)rr * g.wp - g.pw;
-                const int rowbase = rowinfo[rr];
-                const bool ok = rowbase >= 0 && xcol >= 0 && xcol < g.w;
-                a_lds[it] = ok ? A[(size_t)rowbase + xcol] : 0.0f;
-            }
+        }
+        if (stageA) {
+            // the matrix A of the same input rows (0 in the halo), for the K of this tile
+#pragma unroll
+            for (int u = 0; u < FA; ++u)
+                if (tid + u * NT < nrows * g.wp) a_lds[tid + u * NT] = a_reg[u];
+            for (int it = tid + FA * NT; it < nrows * g.wp; it += NT) a_lds[it] = a_load(it);
         }
         __syncthreads();
         // K of the tile's output pixels, an equal share per wave: the kh x kw taps of A in row-major order over the
@@ -319,7 +366,15 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     auto store_rows = [&](auto *dst, int i, int j, auto value_of) {
         const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(dst + (size_t)img_a * img_elems, 0, (int)span, 0x00020000);
         const int row0 = f0 + (wf_s * FW + i) * 32;                 // wave-uniform
-        if (row0 + 32 <= g.k_out) {
+        if (row0 + 32 <= g.k_out && howo == 1u && (g.k_out & 3) == 0) {
+            // planes of one pixel (fully connected layers): a lane's four consecutive filter rows are 16
+            // contiguous, aligned bytes
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                __builtin_amdgcn_raw_buffer_store_b128(v4u{value_of(4 * q), value_of(4 * q + 1), value_of(4 * q + 2),
+                                                           value_of(4 * q + 3)},
+                                                       rs, (int)voff[j], (row0 + 8 * q) * 4, 0);
+        } else if (row0 + 32 <= g.k_out) {
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 __builtin_amdgcn_raw_buffer_store_b32(value_of(v), rs, (int)voff[j],
@@ -542,7 +597,7 @@ static const int LDS_LIMIT = 160 * 1024;
 // par_bytes: alpha (fused epilogue: also scale and shift) of the workgroup's filters
 // channel words per K-step and bytes of the widening table of an operand format (Enc<fmt>::BPS, LUT_BYTES)
 static constexpr int fmt_bps(int fmt) { return fmt == 1 ? 2 : fmt == 2 ? 3 : 1; }
-static constexpr int fmt_lut_bytes(int fmt) { return fmt == 0 ? 512 * 8 : fmt == 1 ? 512 * 4 : 0; }     // 2, 3: none
+static constexpr int fmt_lut_bytes(int fmt) { return fmt == 0 ? 512 * 8 : 0; }     // int8 operands only
 static size_t plan_lds_bytes(const MfmaPlan &pl, int fmt, int wp, int PT, int fuse_rows, int par_bytes)
 {
     const size_t rest = (size_t)pl.region_bytes + (size_t)pl.max_rows * 4 +
@@ -658,6 +713,8 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     if (xnor_status s = allow_full_lds(kern, attr_done[linear])) return s;
     pl.ptiles = (g.m_total + PT - 1) / PT;
     pl.ftiles = (g.k_out + FT - 1) / FT;
+    pl.dense = FMT < 2 && g.taps == 1 && g.ph == 0 && g.pw == 0 && g.sh == 1 && g.sw == 1 && g.dil_h == 1 &&
+               g.dil_w == 1 && pl.cc_words == g.cw && g.cw % 4 == 0;
     // weight-heavy: the weight image outweighs the packed activations and there are filter tiles to spread
     pl.wmajor = pl.ftiles >= 8 && (long long)g.k_out * g.taps * g.c > 4LL * g.n * g.h * g.w * g.c;
     dim3 grid((unsigned)pl.ptiles, (unsigned)pl.ftiles), block(64 * WF * WP);
@@ -707,6 +764,7 @@ static xnor_status launch_cfg_pool(const uint32_t *xbits, const void *wimg, cons
     pl.ptiles = (int)ptiles;
     pl.ftiles = (g.k_out + FT - 1) / FT;
     pl.wmajor = 0;
+    pl.dense = 0;
     pl.pool = pool;
     if (pl.ftiles > 65535) return XNOR_ERR_UNSUPPORTED;
     const size_t img_bytes = wimg_f4_bytes(g.k_out, g.c, g.taps);

@@ -35,6 +35,8 @@ struct MfmaPlan {
     int lut_offset;   // LDS byte offset of the sign-byte widening table
     int ftiles;       // filter tiles of the launch
     int wmajor;       // 1: 1-D grid that keeps the pixel tiles of a filter tile on one XCD
+    int dense;        // 1: 1x1 filter, no padding, stride 1, one chunk, words per pixel a multiple of 4: the tile's
+                      //    packed words are one contiguous run of memory, staged 16 bytes per load
     FastDiv div_wp, div_hp, div_ccw, div_cw;
     PoolPlan pool;    // used by the pooled-epilogue instantiations only
 };
@@ -172,20 +174,25 @@ template <> struct Enc<1> {                    // 4-bit float E2M1
         }
         *reinterpret_cast<uint4 *>(dst) = v;
     }
-    // table form (see the int8 encoding): entry b (4 bytes) = the 8 nibbles of sign byte b
-    static constexpr int LUT_BYTES = 512 * 4;
-    static __device__ __forceinline__ void build_lut(uint8_t *lut, int tid, int nthreads) {
-        uint32_t *t = reinterpret_cast<uint32_t *>(lut);
-        for (int b = tid; b < 512; b += nthreads) t[b] = b < 256 ? widen8((uint32_t)b) : 0u;
+    // 8 sign bits -> 8 nibbles with one byte permute: an output byte holds two channels, i.e. one of four values
+    // (0xAA, 0xA2, 0x2A, 0x22 for the bit pairs 00, 01, 10, 11), and v_perm_b32 picks four bytes out of a 32-bit
+    // table by four selector bytes.  The selectors are the byte's four bit pairs spread to byte positions by two
+    // shift-ors and a mask: four vector instructions per output dword, no table in LDS (whose reads would hit
+    // random banks).  `byte` must be clean above bit 7.
+    static __device__ __forceinline__ uint32_t widen8_perm(uint32_t byte) {
+        uint32_t t = (byte << 6) | byte;
+        t = (t << 12) | t;
+        return __builtin_amdgcn_perm(0u, 0x222AA2AAu, t & 0x03030303u);
     }
-    static __device__ __forceinline__ void widen_word_lut(uint8_t *dst, const uint8_t *lut, uint32_t bits, bool ok,
-                                                          int nch) {
-        const uint8_t *base = lut + (ok ? 0 : 256 * 4);
+    static constexpr int LUT_BYTES = 0;
+    static __device__ __forceinline__ void build_lut(uint8_t *, int, int) {}
+    static __device__ __forceinline__ uint4 widen_word_regs(uint32_t bits, bool ok, int nch) {
         uint4 v;
-        v.x = *reinterpret_cast<const uint32_t *>(base + (bits & 255u) * 4);
-        v.y = *reinterpret_cast<const uint32_t *>(base + ((bits >> 8) & 255u) * 4);
-        v.z = *reinterpret_cast<const uint32_t *>(base + ((bits >> 16) & 255u) * 4);
-        v.w = *reinterpret_cast<const uint32_t *>(base + (bits >> 24) * 4);
+        v.x = widen8_perm(bits & 255u);
+        v.y = widen8_perm((bits >> 8) & 255u);
+        v.z = widen8_perm((bits >> 16) & 255u);
+        v.w = widen8_perm(bits >> 24);
+        if (!ok) v = make_uint4(0, 0, 0, 0);
         if (nch < 32) {
             uint32_t *d = reinterpret_cast<uint32_t *>(&v);
 #pragma unroll
@@ -194,7 +201,11 @@ template <> struct Enc<1> {                    // 4-bit float E2M1
                 d[q] &= r0 >= 8 ? 0xFFFFFFFFu : (r0 <= 0 ? 0u : (1u << (4 * r0)) - 1u);
             }
         }
-        *reinterpret_cast<uint4 *>(dst) = v;
+        return v;
+    }
+    static __device__ __forceinline__ void widen_word_lut(uint8_t *dst, const uint8_t *, uint32_t bits, bool ok,
+                                                          int nch) {
+        *reinterpret_cast<uint4 *>(dst) = widen_word_regs(bits, ok, nch);
     }
 };
 
@@ -240,7 +251,7 @@ template <> struct Enc<3> : Enc<0> {
 
 // Steps the offset table is padded by beyond the last K-step (copies of the last entry): operand
 // prefetches run ahead of the loop's end by at most one turn plus the activation depth.
-constexpr int KLOOP_TABLE_PAD = 12;
+constexpr int KLOOP_TABLE_PAD = 20;
 
 // Weight record stream of a chunk that holds every channel word: the records of a filter block are
 // consecutive, so each block gets its own buffer resource covering exactly nsteps records and the
@@ -322,7 +333,7 @@ __device__ __forceinline__ void mfma_kloop(typename E::acc_t (&acc)[FW][PW], con
 {
     constexpr int RW = DW + 1, RX = DX + 1;
     constexpr int TURN = ring_lcm(RW, RX);     // sub-steps after which both rings are back at slot 0
-    static_assert(RX <= RW && TURN <= 8 && TURN % 2 == 0, "unrolled turn: even, at most 8 sub-steps");
+    static_assert(RX <= RW && TURN <= 16 && TURN % 2 == 0, "unrolled turn: even, at most 16 sub-steps");
     static_assert(TURN + DX + 2 <= KLOOP_TABLE_PAD, "offset table padding");
     auto load_w = [&](v4i (&dst)[FW]) { ws.load(dst); };
     const int *tab = xoff_tab + tab_lane;
