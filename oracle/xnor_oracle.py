@@ -18,7 +18,8 @@ _lib = None
 def _load():
     global _lib
     if _lib is None:
-        path = build_oracle.build(force=False)
+        # XNOR_ORACLE_SANITIZE=1: the build instrumented with UndefinedBehaviorSanitizer (tests/test_sanitizers.py)
+        path = build_oracle.build(force=False, sanitize=os.environ.get("XNOR_ORACLE_SANITIZE") == "1")
         _lib = ctypes.CDLL(path)
     return _lib
 

@@ -68,6 +68,27 @@ def build(verbose: bool = False, incremental: bool = False, extra_flags=(), lib:
     return lib
 
 
+def build_host_ubsan(lib: str) -> str:
+    """libxnor with the host code of csrc/api.hip (argument validation and dispatch of every entry point)
+    instrumented by UndefinedBehaviorSanitizer, the other objects as built by build(): for the ABI tests that
+    run on the CPU.  Device code is never instrumented."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objdir = os.path.join(OBJ, "default")
+    objs = [os.path.join(objdir, os.path.basename(s)[:-4] + ".o") for s in sources()]
+    if not all(os.path.exists(o) for o in objs):
+        build()
+    # trap mode: a finding executes a trap instruction (the process dies with SIGILL) and no sanitizer runtime has
+    # to be linked into the shared library
+    san = ["-Xarch_host", "-fsanitize=undefined", "-Xarch_host", "-fsanitize-trap=undefined"]
+    api_obj = os.path.join(OBJ, "api_ubsan.o")
+    _run([hipcc] + HIPCC_FLAGS + san + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-c",
+                                         os.path.join(CSRC, "api.hip"), "-o", api_obj])
+    objs = [api_obj if os.path.basename(o) == "api.o" else o for o in objs]
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-Wno-unused-command-line-argument",
+          "-Wl,--version-script=" + os.path.join(CSRC, "libxnor.map")] + objs + ["-o", lib])
+    return lib
+
+
 if __name__ == "__main__":
     import sys
     print(build(verbose=True, incremental="--incremental" in sys.argv))
