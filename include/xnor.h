@@ -219,6 +219,21 @@ XNOR_API int xnor_conv2d_binactiv_noalloc(const uint32_t *xbits, const uint32_t 
  * out_pool float32 [n][k_out][h_pool][w_pool].  XNOR_ERR_UNSUPPORTED when the convolution rows under one
  * pooled row (pool_h rows of w_out pixels) exceed the largest pixel tile (192 pixels), or c*kh*kw >= 2^24.
  */
+/*
+ * Which of the two pooling fusions is the faster chain for a layer (block order BinConv -> Pool -> next block's
+ * BatchNorm -> BinActiv, sec. 3.2):
+ *   XNOR_POOL_IN_EPILOGUE (1): xnor_conv2d_pool, then xnor_binactiv on the pooled tensor
+ *   XNOR_POOL_ON_LOAD     (0): xnor_conv2d, then xnor_pool_binactiv on the unpooled tensor
+ * Pooling in the epilogue recomputes the convolution rows that neighbouring groups of pooled rows share and
+ * sends every result through LDS once more; measured on the AlexNet / ResNet-18 layer shapes it wins where
+ * output rows are short (w_out <= 16: 13- and 14-pixel rows, 1.1 to 1.25 times the matrix work) and loses on
+ * 27- and 28-pixel rows.  Also XNOR_POOL_ON_LOAD when xnor_conv2d_pool has no kernel for the geometry.
+ * Returns a negative xnor_status for an invalid descriptor or window.  Host-only, launches nothing.
+ */
+#define XNOR_POOL_ON_LOAD 0
+#define XNOR_POOL_IN_EPILOGUE 1
+XNOR_API int xnor_pool_fusion_choice(const xnor_conv_desc *d, int pool_h, int pool_w, int pstride_h, int pstride_w);
+
 XNOR_API int xnor_conv2d_pool(const uint32_t *xbits, const void *wmfma, const float *K, const float *A,
                      const float *alpha, float *out_pool, const xnor_conv_desc *d,
                      int pool_h, int pool_w, int pstride_h, int pstride_w, int relu, void *hip_stream);

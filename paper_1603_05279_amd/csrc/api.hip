@@ -226,6 +226,17 @@ int xnor_conv2d_pool(const uint32_t *xbits, const void *wmfma, const float *K, c
                                  relu ? 1 : 0, (hipStream_t)hip_stream);
 }
 
+int xnor_pool_fusion_choice(const xnor_conv_desc *d, int pool_h, int pool_w, int pstride_h, int pstride_w)
+{
+    ConvGeom g;
+    if (xnor_status s = make_geom(d, &g)) return s;
+    if (pool_h <= 0 || pool_w <= 0 || pstride_h <= 0 || pstride_w <= 0 || pool_h > g.ho || pool_w > g.wo)
+        return XNOR_ERR_SHAPE;
+    // the pooled epilogue needs the convolution rows under one pooled row inside its largest pixel tile
+    if ((long long)pool_h * g.wo > 192 || (long long)g.c * g.taps >= (1ll << 24)) return XNOR_POOL_ON_LOAD;
+    return g.wo <= 16 ? XNOR_POOL_IN_EPILOGUE : XNOR_POOL_ON_LOAD;
+}
+
 size_t xnor_conv2d_binactiv_workspace_bytes(const xnor_conv_desc *d)
 {
     ConvGeom g;

@@ -25,7 +25,7 @@ EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor
            "xnor_bwn_parts_bytes", "xnor_bwn_wimg_bytes", "xnor_bwn_split", "xnor_bwn_pack_weights",
            "xnor_bwn_conv2d",
            "xnor_bingrad_pack_weights", "xnor_bingrad_binarize", "xnor_bingrad_conv2d",
-           "xnor_conv2d_pool",
+           "xnor_conv2d_pool", "xnor_pool_fusion_choice",
            "xnor_kbit_input_bytes", "xnor_kbit_wimg_bytes", "xnor_kbit_pack_input", "xnor_kbit_pack_weights",
            "xnor_kbit_conv2d"]
 
@@ -103,6 +103,8 @@ def lib():
         L.xnor_bingrad_conv2d.restype = ip
         L.xnor_conv2d_pool.argtypes = [vp] * 6 + [ctypes.POINTER(ConvDesc)] + [ip] * 5 + [vp]
         L.xnor_conv2d_pool.restype = ip
+        L.xnor_pool_fusion_choice.argtypes = [ctypes.POINTER(ConvDesc), ip, ip, ip, ip]
+        L.xnor_pool_fusion_choice.restype = ip
         L.xnor_kbit_input_bytes.argtypes = [ip, ip, ip, ip]
         L.xnor_kbit_input_bytes.restype = ctypes.c_size_t
         L.xnor_kbit_wimg_bytes.argtypes = [ip, ip, ip, ip]
@@ -125,6 +127,14 @@ def ubench(kind, workgroups, iters, buf, nbytes=None, stream=None):
     nbytes = buf.numel() * buf.element_size() if nbytes is None else nbytes
     _check("xnor_ubench", lib().xnor_ubench(UBENCH[kind], int(workgroups), int(iters), ctypes.c_void_p(buf.data_ptr()),
                                             ctypes.c_size_t(nbytes), _stream(stream)))
+
+
+def pool_fusion_choice(desc, pool, pstride):
+    """1: pooling in the convolution's epilogue is the faster chain, 0: pooling on load in front of BinActiv."""
+    r = lib().xnor_pool_fusion_choice(ctypes.byref(desc), int(pool[0]), int(pool[1]), int(pstride[0]), int(pstride[1]))
+    if r < 0:
+        raise XnorError("xnor_pool_fusion_choice", r)
+    return r
 
 
 def status_string(status):

@@ -51,6 +51,21 @@ def test_small_queries():
     assert "NULL" in xnor.status_string(-1)
 
 
+def test_pool_fusion_choice_follows_the_measured_rule():
+    conv2 = xnor.make_desc(64, 96, 27, 27, 256, 5, 5, 1, 2)
+    conv5 = xnor.make_desc(128, 384, 13, 13, 256, 3, 3, 1, 1)
+    res14 = xnor.make_desc(256, 256, 14, 14, 256, 3, 3, 1, 1)
+    res28 = xnor.make_desc(256, 128, 28, 28, 128, 3, 3, 1, 1)
+    res56 = xnor.make_desc(256, 64, 56, 56, 64, 3, 3, 1, 1)
+    assert xnor.pool_fusion_choice(conv5, (3, 3), (2, 2)) == 1
+    assert xnor.pool_fusion_choice(res14, (2, 2), (2, 2)) == 1
+    assert xnor.pool_fusion_choice(conv2, (3, 3), (2, 2)) == 0
+    assert xnor.pool_fusion_choice(res28, (3, 3), (2, 2)) == 0
+    assert xnor.pool_fusion_choice(res56, (4, 4), (2, 2)) == 0        # four rows of 56 pixels exceed the pooled tile
+    with pytest.raises(xnor.XnorError):
+        xnor.pool_fusion_choice(conv5, (14, 14), (1, 1))              # window larger than the output
+
+
 def test_invalid_arguments_return_error_codes_without_launching():
     L = xnor.lib()
     good = xnor.make_desc(1, 64, 14, 14, 64, 3, 3, 1, 1)
