@@ -315,6 +315,9 @@ def main():
     ap.add_argument("--launches", type=int, default=60, help="back-to-back launches per per-layer kernel timing")
     ap.add_argument("--report", action="store_true", help="markdown tables instead of the JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--profile-pass", action="store_true",
+                    help="for rocprofv3 runs: three 256 MiB calibration copies (xnor_ubench), then only the warm-up and "
+                         "timed steps; prints a short JSON line and skips every other measurement")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip measured peaks, the inner-loop comparison and the config-3 chain (profiling runs)")
     args = ap.parse_args()
@@ -347,10 +350,23 @@ def main():
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
+    if args.profile_pass:
+        # a kernel of known HBM traffic for scaling FETCH_SIZE / WRITE_SIZE: reads 128 MiB, writes 128 MiB
+        cal = torch.empty((256 << 20,), dtype=torch.uint8, device="cuda")
+        for _ in range(3):
+            xnor.ubench("copy", 4096, 0, cal)
+        torch.cuda.synchronize()
+        del cal
     for s in range(args.warmup):
         step(s)
     dt = timed(args.steps, args.warmup)
     macs = sum(sh.macs for sh in shapes)
+    if args.profile_pass:
+        print(json.dumps({"profile_pass": True, "workload": args.workload, "buffers": args.buffers,
+                          "layers": [sh.name for sh in shapes], "rings": [st.ring for st in states],
+                          "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt / args.steps * 1e3,
+                          "kernels_per_step": 2 * len(shapes)}))
+        return
     # the same steps on one buffer set (served by the last-level cache where the layer fits it)
     for s in range(min(args.warmup, 5)):
         for st in states:

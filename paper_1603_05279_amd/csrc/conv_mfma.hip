@@ -859,15 +859,7 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
             else tile = 14;       // 128 x 32 (measured ahead of 64 x 64 at equal workgroup count)
         }
     }
-    // the fused epilogue is built for the tiles marked F (the default choices and the wide-filter ones)
-    // (the bfloat16-parts format is built for the default tilings only, and without the fused epilogue)
-#define XNOR_TILE(ID, FW, PW, WF, WP)                                                                     \
-    case ID:                                                                                              \
-        if constexpr (FMT >= 2) return XNOR_ERR_UNSUPPORTED;                                              \
-        else {                                                                                            \
-            if (fz) return XNOR_ERR_UNSUPPORTED;                                                          \
-            return launch_cfg<FMT, FW, PW, WF, WP, false>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, nullptr); \
-        }
+    // every tiling is built with and without the fused epilogue (bfloat16 parts and k-bit levels: without only)
 #define XNOR_TILE_F(ID, FW, PW, WF, WP)                                                                   \
     case ID:                                                                                              \
         if constexpr (FMT < 2) {                                                                          \
@@ -877,20 +869,13 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
     switch (tile) {
         XNOR_TILE_F(1, 2, 2, 2, 2);   // 128 filters x 128 pixels
         XNOR_TILE_F(2, 2, 2, 1, 4);   //  64 x 256
-        XNOR_TILE(3, 2, 4, 2, 2);     // 128 x 256
         XNOR_TILE_F(4, 2, 3, 4, 1);   // 256 x  96
         XNOR_TILE_F(5, 2, 4, 4, 1);   // 256 x 128
-        XNOR_TILE(6, 2, 6, 4, 1);     // 256 x 192
-        XNOR_TILE(7, 4, 2, 2, 2);     // 256 x 128
-        XNOR_TILE(8, 2, 4, 1, 4);     //  64 x 512
-        XNOR_TILE(9, 4, 4, 2, 2);     // 256 x 256
         XNOR_TILE_F(11, 1, 2, 2, 2);  //  64 x 128
-        XNOR_TILE(12, 1, 1, 2, 2);    //  64 x  64
         XNOR_TILE_F(13, 1, 2, 4, 1);  // 128 x  64
         XNOR_TILE_F(14, 1, 1, 4, 1);  // 128 x  32
     default: return XNOR_ERR_UNSUPPORTED;
     }
-#undef XNOR_TILE
 #undef XNOR_TILE_F
 }
 
