@@ -41,7 +41,11 @@ WORKLOADS = ["all", "tiny", "alexnet_conv2", "alexnet_conv345", "resnet18", "fc"
 # HBM bytes per launch of the convolution kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (each
 # scaled by the same counter over a plain copy of known size); source: the named file under profiles/.
 # None = not profiled.
-PROFILED_TRAFFIC = {}
+PROFILED_TRAFFIC = {
+    "tiny_64x14x14_k3": 378567, "alexnet_conv2": 59718605, "alexnet_conv3": 44969699, "alexnet_conv4": 43784672,
+    "alexnet_conv5": 28198169, "resnet18_64x56": 216596824, "resnet18_128x28": 108795502, "resnet18_256x14": 62275814,
+    "resnet18_512x7": 39390227, "fc_9216x4096": 25822468,
+}
 PROFILED_TRAFFIC_SOURCE = "profiles/conv_hbm_traffic.md"
 
 
