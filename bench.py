@@ -206,7 +206,7 @@ def cpu_baseline(states):
             "sample": f"the full workload once ({len(states)} layer(s), {macs / 1e9:.1f} G binop), {dt:.2f} s wall"}
 
 
-def chain_config3(torch, wl, xnor, launches):
+def chain_config3(torch, wl, xnor, launches, profile_runs=0):
     """Config 3 as the chain it is: block i+1 consumes block i's output.  Layer by layer (xnor_binactiv +
     xnor_conv2d per block) against the fused form (one xnor_binactiv, then xnor_conv2d_binactiv emits the next
     block's sign words and A; the float tensor between the blocks is never written)."""
@@ -234,6 +234,11 @@ def chain_config3(torch, wl, xnor, launches):
             else:
                 xnor.xnor_conv2d(b.xbits, pw.wbits, pw.wmfma, None, b.A, pw.alpha, b.out, None, s.desc, f4)
 
+    if profile_runs:           # rocprofv3 runs: the fused chain alone
+        for i in range(profile_runs):
+            fused(i)
+        torch.cuda.synchronize()
+        return None
     macs = sum(s.sh.macs for s in sts)
     res = {"G_binop": macs / 1e9}
     for name, fn in (("layerwise", layerwise), ("fused", fused)):
@@ -252,6 +257,24 @@ def chain_config3(torch, wl, xnor, launches):
                     "other_frac": other["frac"]})
     res["conv2d_binactiv"] = per
     return res
+
+
+def bwn_conv2_profile(torch, wl, xnor, runs):
+    """rocprofv3 runs: the Binary-Weight-Network convolution (sec. 3.1) on the alexnet_conv2 shape,
+    xnor_bwn_split + xnor_bwn_conv2d per run."""
+    sh = workload_shapes(wl, "alexnet_conv2")[0]
+    d = wl.conv_inputs(sh.layer, wl.config_seed("alexnet_conv2"))
+    x, w = torch.from_numpy(d["x"]).cuda(), torch.from_numpy(d["w"]).cuda()
+    desc = xnor.make_desc(sh.n, sh.c, sh.h, sh.w, sh.k, sh.kh, sh.kw, sh.stride, sh.pad)
+    parts = torch.empty((xnor.bwn_parts_bytes(sh.n, sh.c, sh.h, sh.w),), dtype=torch.uint8, device="cuda")
+    wimg = torch.empty((xnor.bwn_wimg_bytes(sh.k, sh.c, sh.kh, sh.kw),), dtype=torch.uint8, device="cuda")
+    alpha = torch.empty((sh.k,), dtype=torch.float32, device="cuda")
+    out = torch.empty((sh.n, sh.k, sh.ho, sh.wo), dtype=torch.float32, device="cuda")
+    xnor.xnor_bwn_pack_weights(w, alpha, wimg, sh.k, sh.c, sh.kh, sh.kw)
+    for _ in range(runs):
+        xnor.xnor_bwn_split(x, parts, sh.n, sh.c, sh.h, sh.w)
+        xnor.xnor_bwn_conv2d(parts, wimg, alpha, out, desc)
+    torch.cuda.synchronize()
 
 
 def measure_layers(torch, xnor, states, launches, compare_algos=True):
@@ -322,6 +345,10 @@ def main():
     ap.add_argument("--profile-pass", action="store_true",
                     help="for rocprofv3 runs: three 256 MiB calibration copies (xnor_ubench), then only the warm-up and "
                          "timed steps; prints a short JSON line and skips every other measurement")
+    ap.add_argument("--profile-extra", action="store_true",
+                    help="with --profile-pass: instead of the steps, --steps runs of the fused config-3 chain "
+                         "(xnor_binactiv, two xnor_conv2d_binactiv, xnor_conv2d), then of xnor_bwn_split + xnor_bwn_conv2d "
+                         "on the alexnet_conv2 shape")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip measured peaks, the inner-loop comparison and the config-3 chain (profiling runs)")
     args = ap.parse_args()
@@ -361,6 +388,13 @@ def main():
             xnor.ubench("copy", 4096, 0, cal)
         torch.cuda.synchronize()
         del cal
+        if args.profile_extra:
+            chain_config3(torch, wl, xnor, 0, profile_runs=args.steps)
+            bwn_conv2_profile(torch, wl, xnor, args.steps)
+            print(json.dumps({"profile_pass": True, "profile_extra": True, "runs": args.steps,
+                              "fused_chain_launches_per_run": "xnor_binactiv, xnor_conv2d_binactiv x2 (each + sum_planes), "
+                              "xnor_conv2d", "bwn_launches_per_run": "xnor_bwn_split, xnor_bwn_conv2d"}))
+            return
     for s in range(args.warmup):
         step(s)
     dt = timed(args.steps, args.warmup)
