@@ -172,6 +172,20 @@ def measured_peaks(torch, xnor):
     wgs, iters = 2048, 2000            # two waves per SIMD, about 0.3 ms per launch
     us = event_us(torch, lambda i: xnor.ubench("mfma_f4", wgs, iters, buf), 20)
     out["mfma_f4_TFLOP_s"] = wgs * 4 * iters * 8 * 2.0 * 32 * 32 * 64 / us / 1e6
+    # the same loop on operands that change with every instruction, sustained and as a burst of one convolution's length
+    us = event_us(torch, lambda i: xnor.ubench("mfma_f4_data", wgs, iters, buf), 20)
+    out["mfma_f4_changing_operands_TFLOP_s"] = wgs * 4 * iters * 8 * 2.0 * 32 * 32 * 64 / us / 1e6
+    torch.cuda.synchronize()
+    clk = buf[:16].view(torch.int64).cpu()
+    out["core_clock_GHz_sustained_mfma"] = round(float(clk[0]) / (float(clk[1]) * 10.0), 3)
+    event_us(torch, lambda i: xnor.ubench("mfma_f4_data", 512, 30, buf), 20)
+    torch.cuda.synchronize()
+    clk = buf[:16].view(torch.int64).cpu()
+    out["core_clock_GHz_10us_mfma_bursts"] = round(float(clk[0]) / (float(clk[1]) * 10.0), 3)
+    # 16-byte loads of a 4 MiB buffer that stays in L2, 64 KiB per workgroup and pass (the weight stream of the convolution)
+    us = event_us(torch, lambda i: xnor.ubench("l2_read", 2048, 64, buf, 4 << 20), 20)
+    out["l2_read_GB_s"] = 2048 * 64 * 65536 / us / 1e3
+    out["l2_read_bytes_per_clock_per_cu_at_2.4GHz"] = round(2048 * 64 * 65536 / (us * 1e-6) / 256 / 2.4e9, 1)
     us = event_us(torch, lambda i: xnor.ubench("mfma_i8", wgs, iters, buf), 20)
     out["mfma_i8_TOP_s"] = wgs * 4 * iters * 8 * 2.0 * 32 * 32 * 32 / us / 1e6
     us = event_us(torch, lambda i: xnor.ubench("popcount", wgs, 500, buf), 20)

@@ -30,6 +30,46 @@ __global__ __launch_bounds__(256) void ubench_mfma_f4_kernel(float *out, int ite
     if (s == 1.2345e30f) out[0] = s;            // keeps the loop alive; never true
 }
 
+// The same loop on operands that change with every instruction (four A and four B register sets of pseudo-random +-1
+// codes): real operands toggle the multiplier inputs, and the chip lowers its clock under that load.  Thread 0 of
+// workgroup 0 reports the loop's core-clock count and its 100 MHz wall-clock ticks.
+__global__ __launch_bounds__(256) void ubench_mfma_f4_data_kernel(unsigned long long *out, int iters)
+{
+    ub_v8i a[4], b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            uint32_t h = (threadIdx.x * 8u + j) * 2654435761u + i * 0x9e3779b9u;
+            h ^= h >> 15; h *= 0x85ebca6bu; h ^= h >> 13;
+            const uint32_t g = h * 0xc2b2ae35u ^ (h >> 16);
+            a[i][j] = j < 4 ? (int)(0x22222222u | (h & 0x88888888u)) : 0;      // each nibble 0x2 (+1) or 0xA (-1)
+            b[i][j] = j < 4 ? (int)(0x22222222u | (g & 0x88888888u)) : 0;
+        }
+    }
+    ub_v16f acc[UB_ACC];
+#pragma unroll
+    for (int i = 0; i < UB_ACC; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+    const unsigned long long c0 = __builtin_readcyclecounter(), r0 = wall_clock64();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < UB_ACC; ++i)
+            acc[i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[i & 3], b[(i >> 1) & 3], acc[i], 4, 4, 0, 127, 0, 127);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < UB_ACC; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[i][v];
+    const unsigned long long c1 = __builtin_readcyclecounter(), r1 = wall_clock64();
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        out[0] = c1 - c0 + (s == 1.2345e30f ? 1u : 0u);      // (the sums have to be used)
+        out[1] = r1 - r0;
+    }
+}
+
 __global__ __launch_bounds__(256) void ubench_mfma_i8_kernel(int *out, int iters)
 {
     ub_v4i a = {(int)threadIdx.x, 0x01ff01ff, 0x0101ffff, 0x01010101}, b = {0x01ff01ff, (int)threadIdx.x, 0x01010101, 0x0101ffff};
@@ -81,6 +121,24 @@ __global__ __launch_bounds__(256) void ubench_read_kernel(const uint4 *src, uint
     if (s == 0x9e3779b9u) out[0] = s;           // practically never: the sum only has to be used
 }
 
+// Every workgroup streams `passes` times over its own 64 KiB window of a small buffer that stays in L2 (window =
+// workgroup index modulo the number of windows): twice the vector L1, so nearly every line comes from L2, the way the
+// convolution's weight records do.
+__global__ __launch_bounds__(256) void ubench_l2_read_kernel(const uint4 *src, uint32_t *out, int windows, int passes)
+{
+    const uint4 *w = src + (size_t)(blockIdx.x % (unsigned)windows) * 4096 + threadIdx.x;
+    uint32_t s = 0;
+    for (int p = 0; p < passes; ++p) {
+        uint4 v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = w[u * 256];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) s += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+        asm volatile("" : "+v"(s));          // keeps every pass's loads
+    }
+    if (s == 0x9e3779b9u) out[0] = s;
+}
+
 __global__ __launch_bounds__(256) void ubench_copy_kernel(const uint4 *src, uint4 *dst, size_t n16)
 {
     const size_t stride = (size_t)gridDim.x * 256;
@@ -113,6 +171,15 @@ extern "C" int xnor_ubench(int kind, int workgroups, int iters, void *buf, size_
     case XNOR_UBENCH_COPY:
         if (bytes % 32) return XNOR_ERR_SHAPE;
         ubench_copy_kernel<<<grid, block, 0, st>>>(static_cast<const uint4 *>(buf), static_cast<uint4 *>(buf) + bytes / 32, bytes / 32);
+        break;
+    case XNOR_UBENCH_MFMA_F4_DATA:
+        if (bytes < 16) return XNOR_ERR_SHAPE;
+        ubench_mfma_f4_data_kernel<<<grid, block, 0, st>>>(static_cast<unsigned long long *>(buf), iters);
+        break;
+    case XNOR_UBENCH_L2_READ:
+        if (bytes % 65536 || bytes == 0 || bytes / 65536 > 0x7fffffffu) return XNOR_ERR_SHAPE;
+        ubench_l2_read_kernel<<<grid, block, 0, st>>>(static_cast<const uint4 *>(buf), static_cast<uint32_t *>(buf),
+                                                      (int)(bytes / 65536), iters);
         break;
     default: return XNOR_ERR_UNSUPPORTED;
     }
