@@ -106,5 +106,13 @@ def test_invalid_arguments_return_error_codes_without_launching():
     assert L.xnor_conv2d_binactiv_workspace_bytes(ctypes.byref(wide)) == 3 * 14 * 14 * 4
     assert L.xnor_set_tuning(99, 0) == ERR_UNSUP
     assert L.xnor_set_tuning(0, 0) == 0
+    # microbenchmarks: buffer, sizes and kind are checked before the launch
+    assert L.xnor_ubench(0, 256, 1, None, 64, None) == ERR_NULL
+    assert L.xnor_ubench(0, 0, 1, fake, 64, None) == ERR_SHAPE
+    assert L.xnor_ubench(3, 256, 0, fake, 48, None) == ERR_SHAPE            # fill: a multiple of 32 bytes
+    assert L.xnor_ubench(6, 256, 1, fake, 8, None) == ERR_SHAPE             # changing operands: 16 bytes of counts
+    assert L.xnor_ubench(7, 256, 1, fake, 65536 + 32, None) == ERR_SHAPE    # L2 stream: whole 64 KiB windows
+    assert L.xnor_ubench(0, 256, 1, odd, 64, None) == ERR_ALIGN
+    assert L.xnor_ubench(42, 256, 1, fake, 64, None) == ERR_UNSUP
     with pytest.raises(xnor.XnorError):
         xnor.output_hw(big_filter)

@@ -150,3 +150,22 @@ def test_graph_replays_of_the_widened_entry_points():
             assert torch.equal(out[name], eager[name]), (name, replay)
         sequence()                                    # eager work between replays
         torch.cuda.synchronize()
+
+
+def test_microbenchmark_kinds_run_and_report_plausible_counts():
+    """Every xnor_ubench kind launches; the changing-operand matrix loop reports its own core-clock and wall-clock
+    counts (a clock between 0.5 and 3 GHz, at least 32 cycles per matrix instruction and wave)."""
+    buf = torch.zeros(8 << 20, dtype=torch.uint8, device="cuda")
+    for kind, iters, nbytes in (("mfma_f4", 50, None), ("mfma_i8", 50, None), ("popcount", 20, None), ("fill", 0, 4 << 20),
+                                ("read", 0, 4 << 20), ("copy", 0, 8 << 20), ("l2_read", 4, 4 << 20)):
+        xnor.ubench(kind, 512, iters, buf, nbytes)
+    torch.cuda.synchronize()
+    buf.zero_()
+    iters = 200
+    xnor.ubench("mfma_f4_data", 256, iters, buf)
+    torch.cuda.synchronize()
+    clocks, ticks = (int(v) for v in buf[:16].view(torch.int64).cpu())
+    assert ticks > 0 and clocks > 0
+    ghz = clocks / (ticks * 10.0)
+    assert 0.5 < ghz < 3.0, ghz
+    assert clocks >= 32 * 8 * iters, clocks
