@@ -37,9 +37,24 @@ struct MfmaPlan {
     int wmajor;       // 1: 1-D grid that keeps the pixel tiles of a filter tile on one XCD
     int dense;        // 1: 1x1 filter, no padding, stride 1, one chunk, words per pixel a multiple of 4: the tile's
                       //    packed words are one contiguous run of memory, staged 16 bytes per load
+                      // 2: staging without per-item divisions or 64-bit addresses (see set_fast_staging)
     FastDiv div_wp, div_hp, div_ccw, div_cw;
     PoolPlan pool;    // used by the pooled-epilogue instantiations only
 };
+
+// The staging loop walks the items (padded row, padded column, channel word), word fastest, a workgroup-wide stride
+// of `threads` items at a time.  When the input is not dilated, every channel word is full (c a multiple of 32) and
+// pixel and byte counts fit 24 and 31 bits, a thread keeps its (row, column, word) in registers and advances them by
+// the stride's constant increments with carries, addresses LDS and memory with 24-bit multiply-adds, and reads the
+// packed words through a bounds-checked buffer (positions outside the image get an offset beyond it): no division,
+// no 64-bit arithmetic and no branch per item.
+inline void set_fast_staging(MfmaPlan *pl, const ConvGeom &g, int fmt)
+{
+    const long long px = (long long)g.n * g.h * g.w;
+    if (fmt < 2 && !pl->dense && g.dil_h == 1 && g.dil_w == 1 && g.c % 32 == 0 && px < (1 << 24) &&
+        g.cw < (1 << 16) && px * g.cw * 4 < 0x7fffffffLL && pl->row_pitch < (1 << 23))
+        pl->dense = 2;
+}
 
 // Most padded input rows touched by any run of `run` consecutive (flattened) output pixels that
 // starts at a multiple of `step`.  The row span only depends on the start modulo the pixels of one
@@ -179,20 +194,21 @@ template <> struct Enc<1> {                    // 4-bit float E2M1
     // table by four selector bytes.  The selectors are the byte's four bit pairs spread to byte positions by two
     // shift-ors and a mask: four vector instructions per output dword, no table in LDS (whose reads would hit
     // random banks).  `byte` must be clean above bit 7.
-    static __device__ __forceinline__ uint32_t widen8_perm(uint32_t byte) {
+    static __device__ __forceinline__ uint32_t widen8_perm(uint32_t byte, uint32_t tbl = 0x222AA2AAu) {
         uint32_t t = (byte << 6) | byte;
         t = (t << 12) | t;
-        return __builtin_amdgcn_perm(0u, 0x222AA2AAu, t & 0x03030303u);
+        return __builtin_amdgcn_perm(0u, tbl, t & 0x03030303u);
     }
     static constexpr int LUT_BYTES = 0;
     static __device__ __forceinline__ void build_lut(uint8_t *, int, int) {}
     static __device__ __forceinline__ uint4 widen_word_regs(uint32_t bits, bool ok, int nch) {
+        // positions outside the image pick from an all-zero table (code 0x0 = 0.0)
+        const uint32_t tbl = ok ? 0x222AA2AAu : 0u;
         uint4 v;
-        v.x = widen8_perm(bits & 255u);
-        v.y = widen8_perm((bits >> 8) & 255u);
-        v.z = widen8_perm((bits >> 16) & 255u);
-        v.w = widen8_perm(bits >> 24);
-        if (!ok) v = make_uint4(0, 0, 0, 0);
+        v.x = widen8_perm(bits & 255u, tbl);
+        v.y = widen8_perm((bits >> 8) & 255u, tbl);
+        v.z = widen8_perm((bits >> 16) & 255u, tbl);
+        v.w = widen8_perm(bits >> 24, tbl);
         if (nch < 32) {
             uint32_t *d = reinterpret_cast<uint32_t *>(&v);
 #pragma unroll
