@@ -86,7 +86,7 @@ size_t xnor_wmfma_bytes(int k_out, int c, int kh, int kw)
 
 int xnor_set_tuning(int mfma_tile, int lds_budget_bytes)
 {
-    if (mfma_tile < 0 || mfma_tile > 14 || lds_budget_bytes < 0 || lds_budget_bytes > 160 * 1024)
+    if (mfma_tile < 0 || mfma_tile > 15 || lds_budget_bytes < 0 || lds_budget_bytes > 160 * 1024)
         return XNOR_ERR_UNSUPPORTED;
     set_mfma_tuning(mfma_tile, lds_budget_bytes);
     return XNOR_OK;

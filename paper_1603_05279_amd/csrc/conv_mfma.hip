@@ -39,8 +39,11 @@ template <int KH, int KW> __device__ __forceinline__ float box_sum_lds(const flo
 }
 
 // Accumulator tiles of up to 8 result blocks leave room for two waves per SIMD (256 registers each).
-template <int FMT, int FW, int PW, int WF, int WP, bool FUSE, bool LINEAR, bool POOL = false>
-__global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 1)) void conv_mfma_kernel(
+// KS > 1: KS groups of WF x WP waves share the K loop of the same tile (group k takes the k-th run of steps) and add
+// their accumulators through LDS at the end: more weight loads in flight and more waves for the staging where a
+// problem offers few output tiles and a long K (fully connected layers).  Consecutive-record streams only.
+template <int FMT, int FW, int PW, int WF, int WP, bool FUSE, bool LINEAR, bool POOL = false, int KS = 1>
+__global__ __launch_bounds__(64 * WF * WP * KS, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 1)) void conv_mfma_kernel(
     const uint32_t *__restrict__ xbits, const v4i *__restrict__ wimg, uint32_t wimg_bytes,
     const float *__restrict__ K, const float *__restrict__ A, const float *__restrict__ alpha,
     float *__restrict__ out, int32_t *__restrict__ dot_out, ConvGeom g, MfmaPlan pl, FuseArgs fz)
@@ -49,7 +52,8 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     // operands staged as they are (no sign bits to widen, no K): bfloat16 parts and int8 levels
     constexpr bool RAW = FMT == 2 || FMT == 3;
     typedef typename E::acc_t acc_t;
-    constexpr int NT = 64 * WF * WP;
+    static_assert(KS == 1 || (LINEAR && !FUSE && !POOL), "waves along K: plain epilogue, consecutive records");
+    constexpr int NT = 64 * WF * WP * KS;
     constexpr int FT = 32 * FW * WF;
     constexpr int PT = 32 * PW * WP;
     // Weight prefetch depth.  Five steps pay off on long K loops; the 64-filter tiles serve layers
@@ -97,7 +101,8 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     const int tid = threadIdx.x;
     const int wave = tid >> 6, lane = tid & 63;
     const int l32 = lane & 31, half = lane >> 5;
-    const int wf = wave % WF, wp = wave / WF;
+    const int wk = wave / (WF * WP);                  // the wave's run of K-steps (0 without waves along K)
+    const int wf = (wave % (WF * WP)) % WF, wp = (wave % (WF * WP)) / WF;
     const int f0 = (int)ftile * FT;
     const uint32_t howo = (uint32_t)(g.ho * g.wo);
     // the tile's run of flattened output pixels [m0, m_end): PT consecutive ones, or (pooled epilogue) the
@@ -346,7 +351,7 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
         __syncthreads();
         // K of the tile's output pixels, an equal share per wave: the kh x kw taps of A in row-major order over the
         // staged rows (halo entries add +0.0f, the same bits as skipping them), divided by kh*kw
-        constexpr int KPW = (PT + WF * WP - 1) / (WF * WP);
+        constexpr int KPW = (PT + WF * WP * KS - 1) / (WF * WP * KS);
         if (!RAW && wbase == 0 && !K) for (int kt = wave * KPW + lane; kt < min((wave + 1) * KPW, PT); kt += 64) {
             const uint32_t m = min(m0 + (uint32_t)kt, m_end - 1u);
             const uint32_t img = g.div_howo.div(m);
@@ -375,7 +380,13 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
 
         // ---- software-pipelined K loop over this chunk's steps --------------------------------
         // record of step s: rec0 + s + (s / steps_per_tap) * tap_jump
-        if constexpr (LINEAR) {      // the chunk holds every channel word: consecutive records
+        if constexpr (LINEAR && KS > 1) {
+            const int per = (nsteps + KS - 1) / KS;
+            const int s0 = __builtin_amdgcn_readfirstlane(wk * per);
+            const int ns = max(0, min(per, nsteps - s0));
+            WStreamLinear<FW> ws(wimg, wrec0, wbase / E::BPS + s0, ns, wlane);
+            mfma_kloop<E, FW, PW, DW, 1>(acc, lds, pbase, xoff_tab + s0 * E::BPS, tab_lane, ws, ns);
+        } else if constexpr (LINEAR) {      // the chunk holds every channel word: consecutive records
             WStreamLinear<FW> ws(wimg, wrec0, wbase / E::BPS, nsteps, wlane);
             mfma_kloop<E, FW, PW, DW, 1>(acc, lds, pbase, xoff_tab, tab_lane, ws, nsteps);
         } else {
@@ -387,6 +398,33 @@ __global__ __launch_bounds__(64 * WF * WP, (FW * PW <= (FMT == 2 ? 6 : 8) ? 2 : 
     // 8*(v/4) + 4*half + v%4 of the 32-filter block, pixel column l32.  alpha of the lane's
     // filter rows is fetched once (clamped index, no branch), stores are predicated.
     if (!RAW && !K) __syncthreads();      // the K tile is complete
+    if constexpr (KS > 1) {
+        // the wave groups' partial sums (exact integers) meet in LDS, laid over the finished activation region
+        // ([group - 1][wave][block][register][lane]: consecutive lanes, consecutive words); group 0 adds them in order
+        __syncthreads();                  // every wave is done reading activations
+        typedef typename std::remove_reference<decltype(acc[0][0][0])>::type elem_t;
+        elem_t *redw = reinterpret_cast<elem_t *>(lds);
+        const int slot = ((wk - 1) * WF * WP + (wave % (WF * WP))) * FW * PW;
+        if (wk > 0) {
+#pragma unroll
+            for (int i = 0; i < FW; ++i)
+#pragma unroll
+                for (int j = 0; j < PW; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) redw[((slot + i * PW + j) * 16 + v) * 64 + lane] = acc[i][j][v];
+        }
+        __syncthreads();
+        if (wk > 0) return;               // (no barrier follows in the plain epilogue)
+#pragma unroll
+        for (int k = 1; k < KS; ++k)
+#pragma unroll
+            for (int i = 0; i < FW; ++i)
+#pragma unroll
+                for (int j = 0; j < PW; ++j)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        acc[i][j][v] += redw[(((k - 1) * WF * WP + wave) * FW * PW + i * PW + j) * 16 * 64 + v * 64 + lane];
+    }
     uint32_t pimg[PW], ppix[PW];
     float Km[PW];
     bool plive[PW];
@@ -738,7 +776,7 @@ __global__ __launch_bounds__(256) void sum_planes_kernel(const float *__restrict
     A_next[m] = s / k_out;
 }
 
-template <int FMT, int FW, int PW, int WF, int WP, bool FUSE>
+template <int FMT, int FW, int PW, int WF, int WP, bool FUSE, int KS = 1>
 static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const float *K, const float *A,
                               const float *alpha, float *out, int32_t *dot_out, const ConvGeom &g,
                               hipStream_t stream, const FuseArgs *fz)
@@ -757,8 +795,11 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     // two builds of every tiling: weight records consecutive (one chunk holds all channel words) or not
     // (a chunk of a 1x1 filter is a run of consecutive records too)
     const bool linear = pl.tap_jump == 0 || g.taps == 1;
-    auto kern = linear ? conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, true>
-                       : conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, false>;
+    // waves along K: consecutive weight records only, and the partial sums need the activation region's room
+    if (KS > 1 && (!linear || (size_t)pl.region_bytes < (size_t)(KS - 1) * WF * WP * FW * PW * 16 * 64 * 4))
+        return XNOR_ERR_UNSUPPORTED;
+    auto kern = linear ? conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, true, false, KS>
+                       : conv_mfma_kernel<FMT, FW, PW, WF, WP, FUSE, KS != 1, false, KS>;
     static std::atomic<bool> attr_done[2];       // per instantiation (zero-initialised: false)
     if (xnor_status s = allow_full_lds(kern, attr_done[linear])) return s;
     pl.ptiles = (g.m_total + PT - 1) / PT;
@@ -768,7 +809,7 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     set_fast_staging(&pl, g, FMT);
     // weight-heavy: the weight image outweighs the packed activations and there are filter tiles to spread
     pl.wmajor = pl.ftiles >= 8 && (long long)g.k_out * g.taps * g.c > 4LL * g.n * g.h * g.w * g.c;
-    dim3 grid((unsigned)pl.ptiles, (unsigned)pl.ftiles), block(64 * WF * WP);
+    dim3 grid((unsigned)pl.ptiles, (unsigned)pl.ftiles), block(64 * WF * WP * KS);
     if (pl.wmajor) {
         const long long wg = (long long)((pl.ftiles + 7) / 8) * pl.ptiles * 8;
         if (wg > 0x7fffffffLL) return XNOR_ERR_UNSUPPORTED;
@@ -908,7 +949,7 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
         if (w0 < (FMT == 2 ? 128 : 160)) {
             if (wgs(64, 128) >= cus) tile = 11;
             else if (wgs(128, 64) >= cus) tile = 13;
-            else tile = 14;       // 128 x 32 (measured ahead of 64 x 64 at equal workgroup count)
+            else tile = (FMT < 2 && !fz && g.taps == 1) ? 15 : 14;       // 128 x 32 (measured ahead of 64 x 64 at equal workgroup count), with eight waves where the records are consecutive
         }
     }
     // every tiling is built with and without the fused epilogue (bfloat16 parts and k-bit levels: without only)
@@ -926,6 +967,16 @@ static xnor_status launch_fmt(const uint32_t *xbits, const void *wimg, const flo
         XNOR_TILE_F(11, 1, 2, 2, 2);  //  64 x 128
         XNOR_TILE_F(13, 1, 2, 4, 1);  // 128 x  64
         XNOR_TILE_F(14, 1, 1, 4, 1);  // 128 x  32
+    case 15:                          // 128 x  32, two groups of four waves along K (no fused epilogue, packed-bit operands)
+        if constexpr (FMT < 2) {
+            if (!fz) {
+                const xnor_status s = launch_cfg<FMT, 1, 1, 4, 1, false, 2>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, nullptr);
+                // (the library's own choice falls back to the four-wave form where this one does not apply)
+                if (s != XNOR_ERR_UNSUPPORTED || g_tile_override.load(std::memory_order_relaxed) == 15) return s;
+                return launch_cfg<FMT, 1, 1, 4, 1, false>(xbits, wimg, K, A, alpha, out, dot_out, g, stream, nullptr);
+            }
+        }
+        return XNOR_ERR_UNSUPPORTED;
     default: return XNOR_ERR_UNSUPPORTED;
     }
 #undef XNOR_TILE_F

@@ -125,6 +125,33 @@ def test_linear_matches_oracle(algo):
     np.testing.assert_allclose(out.cpu().numpy(), r["out"], rtol=RTOL, atol=ATOL)
 
 
+@pytest.mark.parametrize("algo", ["mfma_i8", "mfma_f4"])
+@pytest.mark.parametrize("shape", [(37, 2048, 130), (70, 32 * 33, 200), (33, 4096 + 64, 33)])
+def test_linear_with_waves_along_K_matches_oracle(shape, algo):
+    """The 128 x 32 tiling whose two groups of four waves split the K loop (tile 15): even and odd step counts,
+    ragged batch and filter counts, both operand encodings; the integer map is exact whatever the split."""
+    rng = np.random.default_rng(150)
+    b, f, o = shape
+    x = rng.standard_normal((b, f)).astype(np.float32)
+    w = (0.01 * rng.standard_normal((o, f))).astype(np.float32)
+    r = xo.binary_linear(x, w)
+    xd, wd = to_dev(x), to_dev(w.reshape(o, f, 1, 1))
+    pw = xnor.PackedWeights(wd)
+    desc = xnor.make_desc(b, f, 1, 1, o, 1, 1)
+    bufs = xnor.ConvBuffers(desc, with_dot=True)
+    xnor.xnor_binactiv(xd.reshape(b, f, 1, 1), None, None, bufs.xbits, bufs.A, bufs.K, desc)
+    out = torch.full((b, o), float("nan"), device="cuda")
+    dot = torch.zeros((b, o), dtype=torch.int32, device="cuda")
+    xnor.set_tuning(15)
+    try:
+        xnor.xnor_linear(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, out, dot, b, f, o, xnor.ALGOS[algo])
+        torch.cuda.synchronize()
+    finally:
+        xnor.set_tuning(0)
+    assert np.array_equal(dot.cpu().numpy(), r["dot"])
+    np.testing.assert_allclose(out.cpu().numpy(), r["out"], rtol=RTOL, atol=ATOL)
+
+
 def test_auto_stays_exact_beyond_the_float_accumulator():
     """2^24 terms per dot product: the 4-bit path (float accumulator) is refused, the library's own choice must
     fall back to an exact integer path and still match the oracle bit for bit."""
