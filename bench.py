@@ -42,9 +42,9 @@ WORKLOADS = ["all", "tiny", "alexnet_conv2", "alexnet_conv345", "resnet18", "fc"
 # scaled by the same counter over a plain copy of known size); source: the named file under profiles/.
 # None = not profiled.
 PROFILED_TRAFFIC = {
-    "tiny_64x14x14_k3": 378567, "alexnet_conv2": 59718605, "alexnet_conv3": 44969699, "alexnet_conv4": 43784672,
-    "alexnet_conv5": 28198169, "resnet18_64x56": 216596824, "resnet18_128x28": 108795502, "resnet18_256x14": 62275814,
-    "resnet18_512x7": 39390227, "fc_9216x4096": 25822468,
+    "tiny_64x14x14_k3": 365130, "alexnet_conv2": 59476217, "alexnet_conv3": 43203361, "alexnet_conv4": 43764765,
+    "alexnet_conv5": 28170833, "resnet18_64x56": 216567166, "resnet18_128x28": 109436615, "resnet18_256x14": 62176033,
+    "resnet18_512x7": 39349586, "fc_9216x4096": 25772395,
 }
 PROFILED_TRAFFIC_SOURCE = "profiles/conv_hbm_traffic.md"
 
@@ -321,7 +321,7 @@ def measure_layers(torch, xnor, states, launches, compare_algos=True):
 
 
 def print_report(rows, peaks, chain, cpu):
-    print("Measured peaks (xnor_ubench): " + ", ".join(f"{k} {v:.0f}" for k, v in peaks.items() if k != "note"))
+    print("Measured peaks (xnor_ubench): " + ", ".join(f"{k} {v:.0f}" if v >= 100 else f"{k} {v:.3g}" for k, v in peaks.items() if k != "note"))
     print("\n| config / layer | G binop | conv fp4 us (ring) | conv fp4 us (one set) | conv int8 us | conv popcount us | "
           "BinActiv us (ring) | Tbinop/s | alg. MB | bound | frac of bound | frac of other roof | BinActiv GB/s | pack ms |")
     print("|---|---|---|---|---|---|---|---|---|---|---|---|---|---|")
