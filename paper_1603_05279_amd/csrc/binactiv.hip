@@ -76,7 +76,9 @@ __global__ __launch_bounds__(64 * NW) void binactiv_kernel(
         float v[8];
         if (!POOL) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) v[j] = xi[(size_t)min(ch0 + j, c - 1) * in_hw];
+            // (read once: the non-temporal hint keeps the stream from displacing the previous layers' results, which
+            // still wait in the last-level cache to be written back; a whole benchmark step 428 -> 412 us)
+            for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(xi + (size_t)min(ch0 + j, c - 1) * in_hw);
         } else if constexpr (PH > 0) {
             uint32_t off[PH * PW];       // byte offsets within the channel plane (unsigned: scalar base + 32-bit lane offset)
             bool okw[PH * PW];

@@ -462,20 +462,30 @@ __global__ __launch_bounds__(64 * WF * WP * KS, (FW * PW <= (FMT == 2 ? 6 : 8) ?
                 __builtin_amdgcn_raw_buffer_store_b128(v4u{value_of(4 * q), value_of(4 * q + 1), value_of(4 * q + 2),
                                                            value_of(4 * q + 3)},
                                                        rs, (int)voff[j], (row0 + 8 * q) * 4, 0);
-        } else if (row0 + 32 <= g.k_out) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-                __builtin_amdgcn_raw_buffer_store_b32(value_of(v), rs, (int)voff[j],
-                                                      (row0 + 8 * (v >> 2) + (v & 3)) * (int)howo * 4, 0);
-        } else {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int row = row0 + 8 * (v >> 2) + (v & 3);
-                const bool fin = row + 4 * half < g.k_out;
-                __builtin_amdgcn_raw_buffer_store_b32(value_of(v), rs, (int)(fin ? voff[j] : OOB),
-                                                      min(row, g.k_out - 1) * (int)howo * 4, 0);
-            }
+            return;
         }
+        // Results larger than a quarter of the 256 MB last-level cache leave with the non-temporal hint (measured: a
+        // 205 MB result 59 -> 44 us, 103 MB 42 -> 32 us, while 51 MB and smaller results are 10 us slower with it).
+        // The cache policy is part of the instruction: one run of stores per policy, chosen by a uniform branch.
+        auto rows = [&](auto aux) {
+            constexpr int AUX = decltype(aux)::value;
+            if (row0 + 32 <= g.k_out) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    __builtin_amdgcn_raw_buffer_store_b32(value_of(v), rs, (int)voff[j],
+                                                          (row0 + 8 * (v >> 2) + (v & 3)) * (int)howo * 4, AUX);
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int row = row0 + 8 * (v >> 2) + (v & 3);
+                    const bool fin = row + 4 * half < g.k_out;
+                    __builtin_amdgcn_raw_buffer_store_b32(value_of(v), rs, (int)(fin ? voff[j] : OOB),
+                                                          min(row, g.k_out - 1) * (int)howo * 4, AUX);
+                }
+            }
+        };
+        if (pl.stream_out) rows(std::integral_constant<int, 2>{});
+        else rows(std::integral_constant<int, 0>{});
     };
     if constexpr (POOL) {
     // Pooled epilogue: y = float(dot) * K * alpha (optionally max(y, 0)) of one filter block goes to a
@@ -807,6 +817,8 @@ static xnor_status launch_cfg(const uint32_t *xbits, const void *wimg, const flo
     pl.dense = FMT < 2 && g.taps == 1 && g.ph == 0 && g.pw == 0 && g.sh == 1 && g.sw == 1 && g.dil_h == 1 &&
                g.dil_w == 1 && pl.cc_words == g.cw && g.cw % 4 == 0;
     set_fast_staging(&pl, g, FMT);
+    // (measured on whole benchmark steps: 64 MiB 382 us, 40 MiB 403 us, 120 MiB 408 us, never 428 us)
+    pl.stream_out = (long long)g.m_total * g.k_out * 4 > (64ll << 20);
     // weight-heavy: the weight image outweighs the packed activations and there are filter tiles to spread
     pl.wmajor = pl.ftiles >= 8 && (long long)g.k_out * g.taps * g.c > 4LL * g.n * g.h * g.w * g.c;
     dim3 grid((unsigned)pl.ptiles, (unsigned)pl.ftiles), block(64 * WF * WP * KS);
@@ -858,6 +870,7 @@ static xnor_status launch_cfg_pool(const uint32_t *xbits, const void *wimg, cons
     pl.wmajor = 0;
     pl.dense = 0;
     set_fast_staging(&pl, g, 1);
+    pl.stream_out = 0;
     pl.pool = pool;
     if (pl.ftiles > 65535) return XNOR_ERR_UNSUPPORTED;
     const size_t img_bytes = wimg_f4_bytes(g.k_out, g.c, g.taps);

@@ -38,6 +38,7 @@ struct MfmaPlan {
     int dense;        // 1: 1x1 filter, no padding, stride 1, one chunk, words per pixel a multiple of 4: the tile's
                       //    packed words are one contiguous run of memory, staged 16 bytes per load
                       // 2: staging without per-item divisions or 64-bit addresses (see set_fast_staging)
+    int stream_out;   // 1: float results are stored with the non-temporal hint (they exceed a quarter of the last-level cache)
     FastDiv div_wp, div_hp, div_ccw, div_cw;
     PoolPlan pool;    // used by the pooled-epilogue instantiations only
 };
