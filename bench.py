@@ -191,11 +191,12 @@ def measured_peaks(torch, xnor):
     us = event_us(torch, lambda i: xnor.ubench("popcount", wgs, 500, buf), 20)
     out["valu_xor_bitcount_Tbinop_s"] = wgs * 256 * 500 * 128 * 32.0 / us / 1e6
     for name, nbytes in (("48MiB_llc_resident", 48 << 20), ("1GiB_through_hbm", 1 << 30)):
-        for kind, moved in (("fill", nbytes), ("read", nbytes), ("copy", nbytes)):
+        for kind, moved in (("fill", nbytes), ("fill_nt", nbytes), ("read", nbytes), ("copy", nbytes)):
             us = event_us(torch, lambda i: xnor.ubench(kind, 4096, 0, buf, nbytes), 30)
             out[f"{kind}_{name}_GB_s"] = moved / us / 1e3
     out["note"] = ("copy moves bytes/2 from the first half to the second (read + write counted); the 48 MiB figures "
-                   "stay in the 256 MB last-level cache, the 1 GiB ones pass through HBM")
+                   "stay in the 256 MB last-level cache, the 1 GiB ones pass through HBM; fill_nt stores with the "
+                   "non-temporal hint")
     del buf
     return out
 

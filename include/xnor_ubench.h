@@ -22,8 +22,9 @@ typedef enum {
     XNOR_UBENCH_COPY = 5,     /* 16-byte loads from the first half of buf, stores to the second half       */
     XNOR_UBENCH_MFMA_F4_DATA = 6, /* MFMA_F4 on operands that change with every instruction (pseudo-random +-1 codes);
                                      writes two 64-bit counts to buf: core clocks and 100 MHz ticks of workgroup 0's loop */
-    XNOR_UBENCH_L2_READ = 7   /* every workgroup reads its 64 KiB window of buf `iters` times with 16-byte loads:
+    XNOR_UBENCH_L2_READ = 7,  /* every workgroup reads its 64 KiB window of buf `iters` times with 16-byte loads:
                                  a stream out of L2, like the convolution's weight records                 */
+    XNOR_UBENCH_FILL_NT = 8   /* FILL with the non-temporal hint on every store                             */
 } xnor_ubench_kind;
 
 /*
@@ -31,7 +32,7 @@ typedef enum {
  *   kind       an xnor_ubench_kind
  *   workgroups grid size (256 threads each); the compute loops want a multiple of the 256 compute units
  *   iters      compute kinds: loop iterations per wave (8 matrix instructions, or 128 XOR + bitcount pairs,
- *              per iteration); L2_READ: passes over the window; ignored by FILL, READ and COPY
+ *              per iteration); L2_READ: passes over the window; ignored by FILL, FILL_NT, READ and COPY
  *   buf, bytes device buffer the memory kinds stream over (bytes a multiple of 32, 16-byte aligned; COPY moves
  *              bytes/2; L2_READ: a multiple of 64 KiB, workgroup i reads window i modulo bytes/64 KiB); the compute
  *              kinds write one word per thread to it only when a result has an impossible value (so it needs at

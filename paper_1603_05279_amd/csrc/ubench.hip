@@ -110,6 +110,14 @@ __global__ __launch_bounds__(256) void ubench_fill_kernel(uint4 *dst, size_t n16
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = make_uint4(1, 2, 3, 4);
 }
 
+// the same stores with the non-temporal hint (what the convolution uses for results beyond a quarter of the last-level cache)
+__global__ __launch_bounds__(256) void ubench_fill_nt_kernel(ub_v4i *dst, size_t n16)
+{
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride)
+        __builtin_nontemporal_store(ub_v4i{1, 2, 3, 4}, dst + i);
+}
+
 __global__ __launch_bounds__(256) void ubench_read_kernel(const uint4 *src, uint32_t *out, size_t n16)
 {
     const size_t stride = (size_t)gridDim.x * 256;
@@ -163,6 +171,10 @@ extern "C" int xnor_ubench(int kind, int workgroups, int iters, void *buf, size_
     case XNOR_UBENCH_FILL:
         if (bytes % 32) return XNOR_ERR_SHAPE;
         ubench_fill_kernel<<<grid, block, 0, st>>>(static_cast<uint4 *>(buf), bytes / 16);
+        break;
+    case XNOR_UBENCH_FILL_NT:
+        if (bytes % 32) return XNOR_ERR_SHAPE;
+        ubench_fill_nt_kernel<<<grid, block, 0, st>>>(static_cast<ub_v4i *>(buf), bytes / 16);
         break;
     case XNOR_UBENCH_READ:
         if (bytes % 32) return XNOR_ERR_SHAPE;

@@ -119,7 +119,7 @@ def lib():
     return _lib
 
 
-UBENCH = {"mfma_f4": 0, "mfma_i8": 1, "popcount": 2, "fill": 3, "read": 4, "copy": 5, "mfma_f4_data": 6, "l2_read": 7}
+UBENCH = {"mfma_f4": 0, "mfma_i8": 1, "popcount": 2, "fill": 3, "read": 4, "copy": 5, "mfma_f4_data": 6, "l2_read": 7, "fill_nt": 8}
 
 
 def ubench(kind, workgroups, iters, buf, nbytes=None, stream=None):

@@ -157,7 +157,7 @@ def test_microbenchmark_kinds_run_and_report_plausible_counts():
     counts (a clock between 0.5 and 3 GHz, at least 32 cycles per matrix instruction and wave)."""
     buf = torch.zeros(8 << 20, dtype=torch.uint8, device="cuda")
     for kind, iters, nbytes in (("mfma_f4", 50, None), ("mfma_i8", 50, None), ("popcount", 20, None), ("fill", 0, 4 << 20),
-                                ("read", 0, 4 << 20), ("copy", 0, 8 << 20), ("l2_read", 4, 4 << 20)):
+                                ("fill_nt", 0, 4 << 20), ("read", 0, 4 << 20), ("copy", 0, 8 << 20), ("l2_read", 4, 4 << 20)):
         xnor.ubench(kind, 512, iters, buf, nbytes)
     torch.cuda.synchronize()
     buf.zero_()
