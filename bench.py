@@ -42,9 +42,9 @@ WORKLOADS = ["all", "tiny", "alexnet_conv2", "alexnet_conv345", "resnet18", "fc"
 # scaled by the same counter over a plain copy of known size); source: the named file under profiles/.
 # None = not profiled.
 PROFILED_TRAFFIC = {
-    "tiny_64x14x14_k3": 365130, "alexnet_conv2": 59476217, "alexnet_conv3": 43203361, "alexnet_conv4": 43764765,
-    "alexnet_conv5": 28170833, "resnet18_64x56": 216567166, "resnet18_128x28": 109436615, "resnet18_256x14": 62176033,
-    "resnet18_512x7": 39349586, "fc_9216x4096": 25772395,
+    "tiny_64x14x14_k3": 386647, "alexnet_conv2": 55155760, "alexnet_conv3": 42750248, "alexnet_conv4": 43904293,
+    "alexnet_conv5": 28250697, "resnet18_64x56": 216572253, "resnet18_128x28": 121462590, "resnet18_256x14": 60098318,
+    "resnet18_512x7": 39472621, "fc_9216x4096": 25778614,
 }
 PROFILED_TRAFFIC_SOURCE = "profiles/conv_hbm_traffic.md"
 
@@ -140,7 +140,9 @@ class LayerState:
 
     def binactiv(self, r):
         b = self.bufs[r % self.ring]
-        self.xnor.xnor_binactiv(self.x[r % self.ring], self.sc, self.sf, b.xbits, b.A, None, self.desc)
+        # every layer's input comes from memory (its ring, or nothing has touched it since the previous step's nine
+        # other layers): the entry point for inputs that are in no cache
+        self.xnor.xnor_binactiv_streamed(self.x[r % self.ring], self.sc, self.sf, b.xbits, b.A, None, self.desc)
 
     def conv(self, r, algo):
         b, pw, sh, xn = self.bufs[r % self.ring], self.pw[r % len(self.pw)], self.sh, self.xnor

@@ -112,6 +112,16 @@ XNOR_API int xnor_binactiv(const float *x, const float *bn_scale, const float *b
                   uint32_t *xbits, float *A, float *K, const xnor_conv_desc *d, void *hip_stream);
 
 /*
+ * xnor_binactiv for an input that is in no cache (a network's input, a tensor nobody has touched since it went to
+ * memory): the same results bit for bit, with x read under the non-temporal hint, so that its stream does not push
+ * other kernels' results, which still wait in the last-level cache to be written back, out in front of it.
+ * xnor_binactiv itself does that only for inputs beyond a quarter of that cache (64 MiB); for smaller ones it cannot
+ * know where x is, and the hint is the slower choice when x was just written by the previous layer.
+ */
+XNOR_API int xnor_binactiv_streamed(const float *x, const float *bn_scale, const float *bn_shift,
+                           uint32_t *xbits, float *A, float *K, const xnor_conv_desc *d, void *hip_stream);
+
+/*
  * Max-pooling (and the optional ReLU) between one block's BinConv and the next block's BatchNorm and
  * BinActiv (block order BatchNorm -> BinActiv -> BinConv -> Pool of sec. 3.2, "Training XNOR-Networks"),
  * applied to the float tensor on load: the pooled tensor is never written.

@@ -117,8 +117,8 @@ int xnor_compute_K(const float *x, const float *bn_scale, const float *bn_shift,
     return launch_boxfilter(A, K, g, st);
 }
 
-int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
-                  uint32_t *xbits, float *A, float *K, const xnor_conv_desc *d, void *hip_stream)
+static int binactiv_entry(const float *x, const float *bn_scale, const float *bn_shift, uint32_t *xbits, float *A,
+                          float *K, const xnor_conv_desc *d, void *hip_stream, int streamed)
 {
     if (!x || !xbits || !A) return XNOR_ERR_NULL;
     ConvGeom g;
@@ -126,8 +126,20 @@ int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
     if (!aligned16(x) || !aligned16(xbits) || !aligned16(A) || !aligned16(K)) return XNOR_ERR_ALIGN;
     if (xnor_status s = check_bn(bn_scale, bn_shift)) return s;
     hipStream_t st = (hipStream_t)hip_stream;
-    if (xnor_status s = launch_binactiv(x, bn_scale, bn_shift, xbits, A, g.n, g.c, g.h * g.w, st)) return s;
+    if (xnor_status s = launch_binactiv(x, bn_scale, bn_shift, xbits, A, g.n, g.c, g.h * g.w, st, streamed)) return s;
     return K ? launch_boxfilter(A, K, g, st) : XNOR_OK;
+}
+
+int xnor_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
+                  uint32_t *xbits, float *A, float *K, const xnor_conv_desc *d, void *hip_stream)
+{
+    return binactiv_entry(x, bn_scale, bn_shift, xbits, A, K, d, hip_stream, 0);
+}
+
+int xnor_binactiv_streamed(const float *x, const float *bn_scale, const float *bn_shift,
+                           uint32_t *xbits, float *A, float *K, const xnor_conv_desc *d, void *hip_stream)
+{
+    return binactiv_entry(x, bn_scale, bn_shift, xbits, A, K, d, hip_stream, 1);
 }
 
 int xnor_pool_binactiv(const float *x, const float *bn_scale, const float *bn_shift,

@@ -23,6 +23,7 @@ struct PoolGeom {
     int pad_h, pad_w;
     int relu;               // max(., 0) before the normalisation (the optional ReLU of sec. 3.2)
     int stage;              // > 0: floats per channel of the per-wave LDS staging buffer (see the kernel)
+    int streamed;           // unpooled form: the caller says the input is not in any cache (read with the non-temporal hint)
 };
 
 // NW = waves per workgroup.  The pooled form runs 16: a pooled image has few pixels (13 x 13 after
@@ -30,7 +31,8 @@ struct PoolGeom {
 // dependent window loads; more waves share the channels instead.
 // PH x PW > 0: pooling window known at compile time (3 x 3 and 2 x 2 are built): all window loads of
 // a channel group are then in flight together; 0: any window, one window position at a time.
-template <bool WRITE_BITS, bool WRITE_A, bool BN, bool POOL, int NW, int PH = 0, int PW = 0>
+// STREAM: the float input is read with the non-temporal hint (see the loads).
+template <bool WRITE_BITS, bool WRITE_A, bool BN, bool POOL, int NW, int PH = 0, int PW = 0, bool STREAM = false>
 __global__ __launch_bounds__(64 * NW) void binactiv_kernel(
     const float *__restrict__ x, const float *__restrict__ bn_scale,
     const float *__restrict__ bn_shift, uint32_t *__restrict__ xbits, float *__restrict__ A,
@@ -75,10 +77,18 @@ __global__ __launch_bounds__(64 * NW) void binactiv_kernel(
         const int ch0 = gidx * 8;
         float v[8];
         if (!POOL) {
+            // An input beyond a quarter of the 256 MB last-level cache cannot be resident anyway and is read once: the
+            // non-temporal hint keeps its stream from displacing the previous layers' results, which still wait in that
+            // cache to be written back (a whole benchmark step 428 -> 412 us).  Smaller inputs keep the default policy:
+            // they are often the previous layer's result, still in cache (with the hint a chain of three 13 x 13 blocks
+            // took 93 instead of 86 us).
+            if constexpr (STREAM) {
 #pragma unroll
-            // (read once: the non-temporal hint keeps the stream from displacing the previous layers' results, which
-            // still wait in the last-level cache to be written back; a whole benchmark step 428 -> 412 us)
-            for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(xi + (size_t)min(ch0 + j, c - 1) * in_hw);
+                for (int j = 0; j < 8; ++j) v[j] = __builtin_nontemporal_load(xi + (size_t)min(ch0 + j, c - 1) * in_hw);
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[j] = xi[(size_t)min(ch0 + j, c - 1) * in_hw];
+            }
         } else if constexpr (PH > 0) {
             uint32_t off[PH * PW];       // byte offsets within the channel plane (unsigned: scalar base + 32-bit lane offset)
             bool okw[PH * PW];
@@ -279,7 +289,9 @@ static xnor_status launch_binactiv_one(dim3 grid, size_t lds, hipStream_t stream
                                        const float *bn_scale, const float *bn_shift, uint32_t *xbits, float *A, int c,
                                        int hw, int cw, int tiles, int blocks, const PoolGeom &pg)
 {
-    auto kern = binactiv_kernel<WB, WA, BN, POOL, NW, PH, PW>;
+    // (the cache policy is an instruction field: a kernel of its own for streamed inputs)
+    const bool stream_in = !POOL && (pg.streamed || (long long)(blocks / tiles) * c * hw * 4 > (64ll << 20));
+    auto kern = stream_in ? binactiv_kernel<WB, WA, BN, POOL, NW, PH, PW, !POOL> : binactiv_kernel<WB, WA, BN, POOL, NW, PH, PW, false>;
     if (lds > 48 * 1024) {      // the pooled form's staging buffer can pass the default dynamic LDS limit
         static std::atomic<bool> attr_done;      // false -> true only; a repeated attribute call is harmless
         if (!attr_done.load(std::memory_order_acquire)) {
@@ -337,7 +349,7 @@ static xnor_status launch_binactiv_nw(const float *x, const float *bn_scale, con
 }
 
 xnor_status launch_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
-                            uint32_t *xbits, float *A, int n, int c, int hw, hipStream_t stream)
+                            uint32_t *xbits, float *A, int n, int c, int hw, hipStream_t stream, int streamed)
 {
     if (hw == 1) {
         const int cw = (c + 31) / 32;
@@ -347,7 +359,9 @@ xnor_status launch_binactiv(const float *x, const float *bn_scale, const float *
             binactiv_vec_kernel<4><<<dim3((unsigned)n), dim3(256), 0, stream>>>(x, bn_scale, bn_shift, xbits, A, c, cw);
         return hip_status(hipGetLastError());
     }
-    return launch_binactiv_impl<false>(x, bn_scale, bn_shift, xbits, A, n, c, hw, PoolGeom{}, stream);
+    PoolGeom pg{};
+    pg.streamed = streamed;
+    return launch_binactiv_impl<false>(x, bn_scale, bn_shift, xbits, A, n, c, hw, pg, stream);
 }
 
 xnor_status launch_pool_binactiv(const float *x, const float *bn_scale, const float *bn_shift,

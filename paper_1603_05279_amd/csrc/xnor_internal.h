@@ -63,8 +63,9 @@ __device__ __forceinline__ float box_K(const float *__restrict__ A, const ConvGe
 inline xnor_status hip_status(hipError_t e) { return e == hipSuccess ? XNOR_OK : XNOR_ERR_HIP; }
 
 // kernels' host launchers (each returns an xnor_status, enqueues on `stream`, never synchronises)
+// streamed != 0: the caller states that x is in no cache (read with the non-temporal hint whatever its size)
 xnor_status launch_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
-                            uint32_t *xbits, float *A, int n, int c, int hw, hipStream_t stream);
+                            uint32_t *xbits, float *A, int n, int c, int hw, hipStream_t stream, int streamed = 0);
 // the same layer with a max-pool (and optional ReLU) applied to x on load; xbits / A are pooled-size
 xnor_status launch_pool_binactiv(const float *x, const float *bn_scale, const float *bn_shift,
                                  uint32_t *xbits, float *A, int n, int c, int h, int w, int ph, int pw,

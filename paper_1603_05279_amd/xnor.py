@@ -18,7 +18,7 @@ ALGOS = {"auto": XNOR_ALGO_AUTO, "popcount": XNOR_ALGO_POPCOUNT, "mfma_i8": XNOR
 
 EXPORTS = ["xnor_words_per_pixel", "xnor_output_hw", "xnor_status_string", "xnor_wmfma_bytes",
            "xnor_set_tuning", "xnor_ubench",
-           "xnor_binarize_pack", "xnor_compute_K", "xnor_binactiv", "xnor_pack_weights",
+           "xnor_binarize_pack", "xnor_compute_K", "xnor_binactiv", "xnor_binactiv_streamed", "xnor_pack_weights",
            "xnor_conv2d", "xnor_linear",
            "xnor_conv2d_binactiv_workspace_bytes", "xnor_conv2d_binactiv", "xnor_conv2d_binactiv_noalloc",
            "xnor_pool_binactiv",
@@ -71,6 +71,8 @@ def lib():
         L.xnor_compute_K.restype = ip
         L.xnor_binactiv.argtypes = [vp, vp, vp, vp, vp, vp, ctypes.POINTER(ConvDesc), vp]
         L.xnor_binactiv.restype = ip
+        L.xnor_binactiv_streamed.argtypes = L.xnor_binactiv.argtypes
+        L.xnor_binactiv_streamed.restype = ip
         L.xnor_pack_weights.argtypes = [vp, vp, vp, vp, ip, ip, ip, ip, vp]
         L.xnor_pack_weights.restype = ip
         L.xnor_conv2d.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ctypes.POINTER(ConvDesc), ip, vp]
@@ -205,6 +207,13 @@ def xnor_compute_K(x, bn_scale, bn_shift, A, K, desc, stream=None):
 
 def xnor_binactiv(x, bn_scale, bn_shift, xbits, A, K, desc, stream=None):
     _check("xnor_binactiv", lib().xnor_binactiv(
+        _ptr(x, torch.float32), _ptr(bn_scale, torch.float32), _ptr(bn_shift, torch.float32),
+        _ptr(xbits, torch.int32), _ptr(A, torch.float32), _ptr(K, torch.float32),
+        ctypes.byref(desc), _stream(stream)))
+
+
+def xnor_binactiv_streamed(x, bn_scale, bn_shift, xbits, A, K, desc, stream=None):
+    _check("xnor_binactiv_streamed", lib().xnor_binactiv_streamed(
         _ptr(x, torch.float32), _ptr(bn_scale, torch.float32), _ptr(bn_shift, torch.float32),
         _ptr(xbits, torch.int32), _ptr(A, torch.float32), _ptr(K, torch.float32),
         ctypes.byref(desc), _stream(stream)))

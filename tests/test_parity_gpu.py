@@ -6,7 +6,7 @@ import torch
 from oracle import xnor_oracle as xo
 from paper_1603_05279_amd import workloads as wl
 from paper_1603_05279_amd import xnor
-from tests.helpers import RTOL, ATOL, assert_block_matches_oracle, gpu_conv_block, to_dev
+from tests.helpers import RTOL, ATOL, assert_block_matches_oracle, gpu_conv_block, pack_signs_channels_last, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -65,6 +65,24 @@ def test_unfused_entry_points_give_identical_bits_and_K():
     b = gpu_conv_block(x, wt, (1, 1), (1, 1), fused=False)
     for key in ("xbits", "A", "K", "dot", "out"):
         assert np.array_equal(a[key], b[key]), key
+
+
+def test_streamed_binactiv_gives_identical_bits_A_and_K():
+    """xnor_binactiv_streamed differs from xnor_binactiv in the cache policy of its loads only."""
+    rng = np.random.default_rng(77)
+    n, c, h, w = 3, 70, 19, 23
+    x = to_dev(rng.standard_normal((n, c, h, w)).astype(np.float32))
+    sc = to_dev((0.5 + rng.random(c)).astype(np.float32))
+    sf = to_dev((0.1 * rng.standard_normal(c)).astype(np.float32))
+    desc = xnor.make_desc(n, c, h, w, 8, 3, 3, 1, 1)
+    a, b = xnor.ConvBuffers(desc), xnor.ConvBuffers(desc)
+    xnor.xnor_binactiv(x, sc, sf, a.xbits, a.A, a.K, desc)
+    xnor.xnor_binactiv_streamed(x, sc, sf, b.xbits, b.A, b.K, desc)
+    torch.cuda.synchronize()
+    assert torch.equal(a.xbits, b.xbits) and torch.equal(a.A, b.A) and torch.equal(a.K, b.K)
+    _, s_ref, a_ref = xo.binactiv(x.cpu().numpy(), sc.cpu().numpy(), sf.cpu().numpy())
+    assert np.array_equal(b.xbits.cpu().numpy().view(np.uint32), pack_signs_channels_last(s_ref))
+    np.testing.assert_allclose(b.A.cpu().numpy(), a_ref, rtol=RTOL, atol=ATOL)
 
 
 def test_batchnorm_block_matches_oracle_and_identity_fold():
