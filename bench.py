@@ -42,9 +42,9 @@ WORKLOADS = ["all", "tiny", "alexnet_conv2", "alexnet_conv345", "resnet18", "fc"
 # scaled by the same counter over a plain copy of known size); source: the named file under profiles/.
 # None = not profiled.
 PROFILED_TRAFFIC = {
-    "tiny_64x14x14_k3": 386647, "alexnet_conv2": 55155760, "alexnet_conv3": 42750248, "alexnet_conv4": 43904293,
-    "alexnet_conv5": 28250697, "resnet18_64x56": 216572253, "resnet18_128x28": 121462590, "resnet18_256x14": 60098318,
-    "resnet18_512x7": 39472621, "fc_9216x4096": 25778614,
+    "tiny_64x14x14_k3": 386647, "alexnet_conv2": 56224741, "alexnet_conv3": 43345486, "alexnet_conv4": 43906325,
+    "alexnet_conv5": 28255366, "resnet18_64x56": 216585722, "resnet18_128x28": 121670924, "resnet18_256x14": 60361062,
+    "resnet18_512x7": 39475287, "fc_9216x4096": 25778616,
 }
 PROFILED_TRAFFIC_SOURCE = "profiles/conv_hbm_traffic.md"
 
