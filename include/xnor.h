@@ -16,7 +16,7 @@
  *  - `hip_stream` is a hipStream_t (NULL = the default stream).  All work is enqueued on it
  *    asynchronously; no entry point synchronises.
  *  - Return value: XNOR_OK (0) or a negative xnor_status.  Arguments are validated before anything is
- *    launched.  The entry points that enqueue two kernels (xnor_compute_K, xnor_binactiv with K,
+ *    launched.  The entry points that enqueue two kernels (xnor_compute_K, xnor_binactiv and xnor_binactiv_streamed with K,
  *    xnor_bingrad_binarize, xnor_bingrad_conv2d, xnor_conv2d_binactiv) may have enqueued the first one
  *    when the second reports XNOR_ERR_UNSUPPORTED (no kernel fits the shape) or XNOR_ERR_HIP; the first
  *    kernel writes only that call's own outputs or scratch.
