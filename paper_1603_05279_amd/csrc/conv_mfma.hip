@@ -384,7 +384,9 @@ __global__ __launch_bounds__(64 * WF * WP * KS, (FW * PW <= (FMT == 2 ? 6 : 8) ?
             const int per = (nsteps + KS - 1) / KS;
             const int s0 = __builtin_amdgcn_readfirstlane(wk * per);
             const int ns = max(0, min(per, nsteps - s0));
-            WStreamLinear<FW> ws(wimg, wrec0, wbase / E::BPS + s0, ns, wlane);
+            // (problems that take this form are all weights: an image read once per call, which passes every XCD's L2 on its
+            // way and should not settle in the last-level cache: fully connected layer inside a step 27.3 -> 24.3 us)
+            WStreamLinear<FW, 2> ws(wimg, wrec0, wbase / E::BPS + s0, ns, wlane);
             mfma_kloop<E, FW, PW, DW, 1>(acc, lds, pbase, xoff_tab + s0 * E::BPS, tab_lane, ws, ns);
         } else if constexpr (LINEAR) {      // the chunk holds every channel word: consecutive records
             WStreamLinear<FW> ws(wimg, wrec0, wbase / E::BPS, nsteps, wlane);

@@ -276,7 +276,8 @@ constexpr int KLOOP_TABLE_PAD = 20;
 // the resource and are answered with zeros by the buffer bounds check instead of touching memory;
 // the check covers the vector offset only, which is why the step lives there and not in the scalar
 // offset.  No other bookkeeping in the loop.
-template <int FW> struct WStreamLinear {
+// AUX: cache policy of the loads (2 = non-temporal hint).
+template <int FW, int AUX = 0> struct WStreamLinear {
     __amdgpu_buffer_rsrc_t rsrc[FW];
     int voff;
     __device__ __forceinline__ WStreamLinear(const v4i *wimg, const int (&wrec0)[FW], int rec_start, int nsteps,
@@ -292,7 +293,7 @@ template <int FW> struct WStreamLinear {
     {
 #pragma unroll
         for (int i = 0; i < FW; ++i) {
-            const v4u r = __builtin_amdgcn_raw_buffer_load_b128(rsrc[i], voff, 0, 0);
+            const v4u r = __builtin_amdgcn_raw_buffer_load_b128(rsrc[i], voff, 0, AUX);
             dst[i] = v4i{(int)r[0], (int)r[1], (int)r[2], (int)r[3]};
         }
         voff += 1024;
