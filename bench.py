@@ -42,9 +42,9 @@ WORKLOADS = ["all", "tiny", "alexnet_conv2", "alexnet_conv345", "resnet18", "fc"
 # scaled by the same counter over a plain copy of known size); source: the named file under profiles/.
 # None = not profiled.
 PROFILED_TRAFFIC = {
-    "tiny_64x14x14_k3": 386647, "alexnet_conv2": 56224741, "alexnet_conv3": 43345486, "alexnet_conv4": 43906325,
-    "alexnet_conv5": 28255366, "resnet18_64x56": 216585722, "resnet18_128x28": 121670924, "resnet18_256x14": 60361062,
-    "resnet18_512x7": 39475287, "fc_9216x4096": 25778616,
+    "tiny_64x14x14_k3": 386645, "alexnet_conv2": 54798481, "alexnet_conv3": 42354811, "alexnet_conv4": 43865889,
+    "alexnet_conv5": 28249471, "resnet18_64x56": 216570124, "resnet18_128x28": 121632283, "resnet18_256x14": 60163628,
+    "resnet18_512x7": 39471446, "fc_9216x4096": 25778495,
 }
 PROFILED_TRAFFIC_SOURCE = "profiles/conv_hbm_traffic.md"
 
