@@ -170,6 +170,35 @@ def test_linear_with_waves_along_K_matches_oracle(shape, algo):
     np.testing.assert_allclose(out.cpu().numpy(), r["out"], rtol=RTOL, atol=ATOL)
 
 
+@pytest.mark.parametrize("algo", ["auto", "mfma_f4"])
+def test_linear_with_few_rows_falls_back_to_the_four_wave_tiling(algo):
+    """Five rows leave the activation region too small for the partial sums of the eight-wave tiling: asked for
+    explicitly it is refused, the library's own choice takes the four-wave form and matches the oracle."""
+    rng = np.random.default_rng(151)
+    b, f, o = 5, 4096 + 64, 33
+    x = rng.standard_normal((b, f)).astype(np.float32)
+    w = (0.01 * rng.standard_normal((o, f))).astype(np.float32)
+    r = xo.binary_linear(x, w)
+    xd, wd = to_dev(x), to_dev(w.reshape(o, f, 1, 1))
+    pw = xnor.PackedWeights(wd)
+    desc = xnor.make_desc(b, f, 1, 1, o, 1, 1)
+    bufs = xnor.ConvBuffers(desc, with_dot=True)
+    xnor.xnor_binactiv(xd.reshape(b, f, 1, 1), None, None, bufs.xbits, bufs.A, bufs.K, desc)
+    out = torch.full((b, o), float("nan"), device="cuda")
+    dot = torch.zeros((b, o), dtype=torch.int32, device="cuda")
+    xnor.set_tuning(15)
+    try:
+        with pytest.raises(xnor.XnorError) as e:
+            xnor.xnor_linear(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, out, dot, b, f, o, xnor.XNOR_ALGO_MFMA_F4)
+        assert e.value.status == -3
+    finally:
+        xnor.set_tuning(0)
+    xnor.xnor_linear(bufs.xbits, pw.wbits, pw.wmfma, bufs.K, pw.alpha, out, dot, b, f, o, xnor.ALGOS[algo])
+    torch.cuda.synchronize()
+    assert np.array_equal(dot.cpu().numpy(), r["dot"])
+    np.testing.assert_allclose(out.cpu().numpy(), r["out"], rtol=RTOL, atol=ATOL)
+
+
 def test_auto_stays_exact_beyond_the_float_accumulator():
     """2^24 terms per dot product: the 4-bit path (float accumulator) is refused, the library's own choice must
     fall back to an exact integer path and still match the oracle bit for bit."""
