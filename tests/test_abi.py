@@ -89,6 +89,10 @@ def test_invalid_arguments_return_error_codes_without_launching():
     assert L.xnor_conv2d(fake, fake, None, fake, None, fake, fake, None, ctypes.byref(big_filter), 1, None) == ERR_SHAPE
     zero_stride = xnor.make_desc(1, 8, 3, 3, 4, 3, 3, 0, 0)
     assert L.xnor_binactiv(fake, None, None, fake, fake, fake, ctypes.byref(zero_stride), None) == ERR_SHAPE
+    assert L.xnor_binactiv_streamed(fake, None, None, fake, fake, fake, ctypes.byref(zero_stride), None) == ERR_SHAPE
+    assert L.xnor_binactiv_streamed(None, None, None, fake, fake, fake, ctypes.byref(good), None) == ERR_NULL
+    assert L.xnor_binactiv_streamed(fake, None, None, odd, fake, fake, ctypes.byref(good), None) == ERR_ALIGN
+    assert L.xnor_binactiv_streamed(fake, fake, None, fake, fake, fake, ctypes.byref(good), None) == ERR_NULL   # scale without shift
     assert L.xnor_linear(fake, fake, None, fake, fake, fake, None, 0, 8, 8, 1, None) == ERR_SHAPE
     assert L.xnor_conv2d(fake, fake, None, fake, None, fake, fake, None, ctypes.byref(good), 3, None) == ERR_NULL
     # matrix-core kernels address a tile's results with 32-bit offsets: an image whose output exceeds
