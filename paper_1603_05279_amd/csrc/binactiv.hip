@@ -246,18 +246,22 @@ __global__ __launch_bounds__(64 * NWV) void binactiv_vec_kernel(
     const float *xi = x + (size_t)img * c;
     const bool bn = bn_scale != nullptr;
     float asum = 0.0f;
-    // four 64-channel segments per wave and turn: the loads (clamped, unconditional) are all in flight together
-    for (int base0 = wave * 64; base0 < c; base0 += 256 * NWV) {
-        float v[4], sc[4], sh[4];
+    // up to twelve 64-channel segments per wave and turn: the loads (clamped; segments past the last channel are skipped,
+    // which is uniform per wave) are all in flight together, so a row of 9216 channels costs one trip to memory, not three
+    constexpr int SEG = 12;
+    for (int base0 = wave * 64; base0 < c; base0 += 64 * SEG * NWV) {
+        float v[SEG], sc[SEG], sh[SEG];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int chc = min(base0 + u * 64 * NWV + lane, c - 1);
-            v[u] = xi[chc];
-            sc[u] = bn ? bn_scale[chc] : 1.0f;
-            sh[u] = bn ? bn_shift[chc] : 0.0f;
+        for (int u = 0; u < SEG; ++u) {
+            v[u] = 0.0f; sc[u] = 1.0f; sh[u] = 0.0f;
+            if (base0 + u * 64 * NWV < c) {
+                const int chc = min(base0 + u * 64 * NWV + lane, c - 1);
+                v[u] = xi[chc];
+                if (bn) { sc[u] = bn_scale[chc]; sh[u] = bn_shift[chc]; }
+            }
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < SEG; ++u) {
             const int base = base0 + u * 64 * NWV, ch = base + lane;
             const float y = bn ? __builtin_fmaf(v[u], sc[u], sh[u]) : v[u];
             const bool ok = ch < c;
