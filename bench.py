@@ -42,9 +42,9 @@ WORKLOADS = ["all", "tiny", "alexnet_conv2", "alexnet_conv345", "resnet18", "fc"
 # scaled by the same counter over a plain copy of known size); source: the named file under profiles/.
 # None = not profiled.
 PROFILED_TRAFFIC = {
-    "tiny_64x14x14_k3": 386645, "alexnet_conv2": 54798481, "alexnet_conv3": 42354811, "alexnet_conv4": 43865889,
-    "alexnet_conv5": 28249471, "resnet18_64x56": 216570124, "resnet18_128x28": 121632283, "resnet18_256x14": 60163628,
-    "resnet18_512x7": 39471446, "fc_9216x4096": 25778495,
+    "tiny_64x14x14_k3": 386648, "alexnet_conv2": 56262886, "alexnet_conv3": 42855315, "alexnet_conv4": 43883570,
+    "alexnet_conv5": 28248434, "resnet18_64x56": 216580891, "resnet18_128x28": 121813565, "resnet18_256x14": 60139770,
+    "resnet18_512x7": 39470434, "fc_9216x4096": 25778613,
 }
 PROFILED_TRAFFIC_SOURCE = "profiles/conv_hbm_traffic.md"
 
